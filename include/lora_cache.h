@@ -1,0 +1,220 @@
+/*
+ * lora_cache.h -- C ABI of the MI355X (gfx950) adapter cache pool and the batched
+ * heterogeneous-rank LoRA apply.
+ *
+ * What the library computes.  For one projection (h_in -> h_out) of one layer and a
+ * batch of T tokens cut into segments (one segment per request of the iteration:
+ * a decode request is one token, a prefill request its whole prompt), every token t
+ * of a segment that names cache slot i of rank r_i gets, in place,
+ *
+ *     base_out[t][:] += scale * alpha_i * (x[t][:] . A_i) . B_i
+ *
+ * with A_i [h_in][r_i] and B_i [r_i][h_out] read from the adapter cache pool.  This
+ * is the per-layer adapter work the paper describes in section 3.1 (two matrix
+ * products on top of the base product plus one addition that aggregates the
+ * results), for a batch in which requests carry different adapters of different
+ * ranks (section 2).  The pool is the paper's adapter cache (section 4.2): adapter
+ * weights kept resident in otherwise idle GPU memory, one entry per adapter with its
+ * id, rank, last-used stamp, use frequency and reference count; entries are
+ * read-only, so eviction discards and nothing is ever written back.
+ *
+ * Conventions.
+ *  - Every function returns LORA_OK (0) or a negative lora_status; nothing aborts or
+ *    throws.  lora_strerror() names a status; lora_last_hip_error() returns the HIP
+ *    status behind the last LORA_E_HIP on the calling thread.
+ *  - "device" pointers are HIP device memory owned by the caller (the Python binding
+ *    gets them from PyTorch); "host" pointers are ordinary host memory read during the
+ *    call, except the fill sources, which are read asynchronously (see there).
+ *  - Streams are hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; none blocks the host except where stated.
+ *  - One lora_cache_t must not be used from two host threads at once.  lora_apply /
+ *    lora_apply_plan calls that share a cache share its scratch (the T x rank
+ *    intermediate), so they must be ordered on the device: issue them on one stream,
+ *    or order the streams with events.
+ *  - Supported shapes: h_in and h_out multiples of 64; 1 <= rank <= LORA_MAX_RANK.
+ */
+#ifndef LORA_CACHE_H
+#define LORA_CACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LORA_OK = 0,
+    LORA_E_INVAL = -1,    /* null / negative / out-of-range argument, malformed segment arrays */
+    LORA_E_STATE = -2,    /* slot in the wrong state (apply on an unfilled slot, evict/refill while referenced) */
+    LORA_E_NOMEM = -3,    /* caller's pool buffer too small, no free plan, host allocation failed */
+    LORA_E_HIP = -4,      /* a HIP call failed; see lora_last_hip_error() */
+    LORA_E_NOTFOUND = -5  /* adapter id not cached */
+} lora_status;
+
+enum { LORA_F32 = 0, LORA_BF16 = 1 };                               /* element type of x, base_out, A, B */
+enum { LORA_SLOT_EMPTY = 0, LORA_SLOT_FILLING = 1, LORA_SLOT_READY = 2 };
+enum { LORA_CACHE_HOST_ONLY = 1 };                                  /* flags: slot table only, no device work */
+
+#define LORA_MAX_RANK 128
+#define LORA_TILE_TOKENS 64      /* tokens per matrix-core tile */
+#define LORA_MFMA_MIN_TOKENS 16  /* default: segments / pooled slots with fewer tokens take the GEMV path */
+
+typedef struct lora_cache lora_cache_t; /* opaque */
+typedef struct lora_plan lora_plan_t;   /* opaque: device-resident work lists of one batch */
+
+typedef struct {
+    int32_t h_in, h_out;
+} lora_proj_t;
+
+typedef struct {
+    int32_t n_proj;             /* projections per layer that carry adapters (q,k,v,o in the paper, section 3.2) */
+    const lora_proj_t *proj;    /* [n_proj] */
+    int32_t n_layers;           /* layer copies the pool holds */
+    int32_t n_classes;          /* rank classes; a slot of class c holds any adapter with rank <= class_rank[c] */
+    const int32_t *class_rank;  /* [n_classes], strictly increasing, <= LORA_MAX_RANK (paper: 8,16,32,64,128) */
+    const int32_t *class_slots; /* [n_classes] slots per class; slot ids run class by class */
+    int32_t dtype;              /* LORA_F32 | LORA_BF16 */
+    int32_t max_tokens;         /* largest T of any apply */
+    int32_t max_segments;       /* largest n_seg of any apply */
+    int32_t n_plans;            /* plans that may be alive at once (>= 0; 4 more are kept for lora_apply) */
+    int32_t mfma_min_tokens;    /* 0 = LORA_MFMA_MIN_TOKENS; ignored (no tile path) for LORA_F32 */
+    int32_t flags;
+} lora_cache_config_t;
+
+/* ---- sizes (pure host arithmetic) ------------------------------------------------ */
+
+/* Bytes of A and B of one adapter of `rank` for one projection, unpadded:
+ * rank * (h_in + h_out) * element size.  (Section 3.2's 64 MB for rank 32 on a 7B
+ * model is 4 projections x 32 layers of this at 16 bit.)  0 on bad arguments. */
+size_t lora_adapter_bytes(int32_t h_in, int32_t h_out, int32_t rank, int32_t dtype);
+
+/* Bytes the caller must provide to lora_cache_create: slabs of every (layer,
+ * projection, slot) + scratch + plan buffers + fill staging.  0 on a bad config. */
+size_t lora_cache_bytes_required(const lora_cache_config_t *cfg);
+
+/* ---- pool life cycle ----------------------------------------------------------------- */
+
+/* Carve `dev_pool` (device, >= lora_cache_bytes_required bytes, 256-byte aligned,
+ * caller-owned, must outlive the cache) into slabs and scratch, build the slot table.
+ * Uploads a small offset table (blocking).  With LORA_CACHE_HOST_ONLY, dev_pool may be
+ * NULL and only the slot-table calls work. */
+int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev_pool_bytes, lora_cache_t **out);
+int lora_cache_destroy(lora_cache_t *c);
+
+/* ---- cache entries (section 4.2: load a missing adapter, retrieve a cached one, evict) -- */
+
+/* Enqueue, on `fill_stream`, the copy of one (layer, projection) part of an adapter
+ * into `slot`: host_A [h_in][rank] and host_B [rank][h_out], row-major, element type =
+ * cfg.dtype.  The host buffers are read asynchronously: keep them unchanged until the
+ * stream has passed this call (pinned memory makes the copy truly asynchronous).  The
+ * first part filled into an EMPTY slot binds (adapter_id, rank, alpha) and moves it to
+ * FILLING; later parts must repeat the same three.  The slot reports READY once all
+ * n_layers * n_proj parts are enqueued and the last copy has completed.  An apply that
+ * names a part still in flight makes its stream wait for it; the fill in turn waits
+ * for applies enqueued earlier that read the slot.
+ * LORA_E_STATE if the slot is referenced (refcount > 0) and already complete, or bound
+ * to another adapter; LORA_E_INVAL if rank exceeds the slot's class. */
+int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha,
+                         int32_t layer, int32_t proj, const void *host_A, const void *host_B, void *fill_stream);
+
+/* Evict: any state -> EMPTY.  No write-back (entries are read-only).  LORA_E_STATE if refcount > 0. */
+int lora_cache_release_slot(lora_cache_t *c, int32_t slot);
+
+/* Reference counter of the entry (number of running requests that use it): delta = +1 / -1. */
+int lora_cache_slot_ref(lora_cache_t *c, int32_t slot, int32_t delta);
+
+/* adapter id -> slot and rank; LORA_E_NOTFOUND on a miss.  Counts a hit or a miss. */
+int lora_cache_lookup(lora_cache_t *c, int64_t adapter_id, int32_t *slot, int32_t *rank);
+
+typedef struct {
+    int64_t adapter_id;
+    int32_t rank, class_rank, state, refcount;
+    int64_t use_count; /* applies that named the slot ("frequency") */
+    int64_t last_used; /* sequence number of the last such apply ("last used"), 0 = never */
+    float alpha;
+    int32_t parts_filled;
+} lora_slot_info_t;
+int lora_cache_slot_info(lora_cache_t *c, int32_t slot, lora_slot_info_t *out);
+
+/* A free slot of the smallest class that fits `rank`, or LORA_E_NOMEM. */
+int lora_cache_find_free_slot(lora_cache_t *c, int32_t rank, int32_t *slot);
+
+typedef struct {
+    int64_t hits, misses, fills, bytes_filled, applies, evictions;
+} lora_cache_stats_t;
+int lora_cache_stats(const lora_cache_t *c, lora_cache_stats_t *out);
+
+/* Device address and byte size of the slab of (layer, proj, slot) -- for tests and tools. */
+int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t slot, void **dev_ptr, size_t *bytes);
+
+/* ---- indexing ------------------------------------------------------------------------ */
+
+/* One unit of work.  tok_off/n_tok name tokens in tok_list; a, b depend on the list:
+ * tiles: a = running tile number inside its segment or pool;  groups: unused;
+ * gs_items (GEMV shrink): a = first rank row, b = rows (<= 4);
+ * ge_items (GEMV expand): a = column offset inside a 1024-column super-chunk, b = columns.
+ * c holds the bit pattern of the slot's alpha (float) in device copies, 0 in lora_index output. */
+typedef struct {
+    int32_t tok_off, n_tok, slot, rank, a, b, c, d;
+} lora_item_t;
+
+typedef struct {
+    int32_t n_tok_list, n_tiles, n_groups, n_gs_items, n_ge_items;
+    int32_t *tok_list;     /* tokens of all tiles, then of all groups */
+    lora_item_t *tiles;    /* <= LORA_TILE_TOKENS tokens of one slot each (matrix-core path) */
+    lora_item_t *groups;   /* all remaining tokens of one slot (GEMV path) */
+    lora_item_t *gs_items; /* groups x blocks of 4 rank rows */
+    lora_item_t *ge_items; /* groups x column chunks */
+} lora_worklists_t;
+
+/* Pure host: build the canonical work lists of a batch (integer work only).
+ *  - seg_offsets [n_seg+1] non-decreasing, [0] = 0, [n_seg] = T; seg_slot [n_seg], < 0 =
+ *    no adapter (tokens keep base_out); seg_rank [n_seg] in 1..LORA_MAX_RANK where slot >= 0.
+ *  - A non-empty segment with slot >= 0 and at least mfma_min_tokens tokens is cut into
+ *    tiles of LORA_TILE_TOKENS consecutive tokens, in segment order.  Tokens of the other
+ *    such segments are pooled per slot (slots ascending, tokens ascending); a pool of at
+ *    least mfma_min_tokens tokens is cut into tiles too, any other is one group.
+ *    mfma_min_tokens = 0 turns tiles off (everything is pooled into groups).
+ *  - gs_items: per group one item per 4 rank rows.  ge_items: per group, with
+ *    rs = rank rounded up to 8 and Nc = 64 * max(1, 128 / rs), items (0,Nc), (Nc,Nc), ... < 1024.
+ * All segments that name one slot must carry the same rank (else LORA_E_INVAL).
+ * Arrays in *out are malloc'ed; free them with lora_worklists_free. */
+int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot, const int32_t *seg_rank,
+               int32_t n_seg, int32_t mfma_min_tokens, lora_worklists_t *out);
+void lora_worklists_free(lora_worklists_t *w);
+
+/* ---- apply --------------------------------------------------------------------------- */
+
+/* Index a batch once and keep its work lists on the device, so that the same batch can
+ * be applied to every projection of every layer of the iteration.  Checks every named
+ * slot against the slot table (exists, bound, seg_rank equals its rank).  The upload is
+ * enqueued on `stream`; the host arrays may be reused on return. */
+int lora_plan_create(lora_cache_t *c, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
+                     const int32_t *seg_rank, int32_t n_seg, void *stream, lora_plan_t **out);
+int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p);
+
+/* base_out[t] += scale*alpha*(x[t].A).B for the planned batch; x [T][h_in] and base_out
+ * [T][h_out] are device, row-major, contiguous, element type cfg.dtype.  Asynchronous on
+ * `stream`.  LORA_E_STATE if a named slot has no data for (layer, proj). */
+int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
+                    void *base_out, float scale, void *stream);
+
+/* One-call form: index + apply (uses one of 4 internal plans in rotation; blocks the
+ * host only if the plan used 4 calls ago is still in flight). */
+int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void *base_out, int32_t T,
+               const int32_t *seg_offsets, const int32_t *seg_slot, const int32_t *seg_rank, int32_t n_seg,
+               float scale, void *stream);
+
+/* When off (0), applies record no last-use event and fills do not wait for earlier
+ * applies: the caller then keeps refills away from slots in use (reference counts).
+ * Default on (1).  Turn off while capturing applies into a HIP graph. */
+int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
+
+const char *lora_strerror(int status);
+int lora_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_CACHE_H */

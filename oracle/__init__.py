@@ -86,7 +86,8 @@ def lora_apply(
     Ap = (dp * n_ad)()
     Bp = (dp * n_ad)()
     keep = []
-    for i in set(int(v) for v in sa if v >= 0):
+    lens = np.diff(so) if len(so) == len(sa) + 1 else np.zeros(len(sa), np.int64)
+    for i in set(int(v) for v, n in zip(sa, lens) if v >= 0 and n > 0):  # empty segments need no weights
         if i not in adapters:
             raise KeyError(f"segment names adapter {i} which was not supplied")
     for i, (A, B, al) in adapters.items():

@@ -1,0 +1,255 @@
+"""ctypes binding of liblora_cache.so: argument marshalling only.
+
+Every function has the name it has in include/lora_cache.h and returns what the C call
+returns (a status, or a size); `check()` turns a negative status into LoraError.  Device
+buffers are passed as integers (`tensor.data_ptr()`), streams as `torch.cuda.Stream.cuda_stream`.
+The library is required: importing this module fails loudly when the shared object has not
+been built (python -m paper_2411_17741_amd.build, or __graft_entry__.build()).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+from typing import Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblora_cache.so")
+
+LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND = 0, -1, -2, -3, -4, -5
+LORA_F32, LORA_BF16 = 0, 1
+LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
+LORA_CACHE_HOST_ONLY = 1
+LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS = 128, 64, 16
+
+
+class LoraError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {lora_strerror(status)} ({status})" + (f", hip error {lora_last_hip_error()}" if status == LORA_E_HIP else ""))
+        self.status = status
+
+
+class lora_proj_t(ctypes.Structure):
+    _fields_ = [("h_in", c_int32), ("h_out", c_int32)]
+
+
+class lora_cache_config_t(ctypes.Structure):
+    _fields_ = [
+        ("n_proj", c_int32), ("proj", POINTER(lora_proj_t)), ("n_layers", c_int32), ("n_classes", c_int32),
+        ("class_rank", POINTER(c_int32)), ("class_slots", POINTER(c_int32)), ("dtype", c_int32),
+        ("max_tokens", c_int32), ("max_segments", c_int32), ("n_plans", c_int32), ("mfma_min_tokens", c_int32),
+        ("flags", c_int32),
+    ]
+
+
+class lora_slot_info_t(ctypes.Structure):
+    _fields_ = [
+        ("adapter_id", c_int64), ("rank", c_int32), ("class_rank", c_int32), ("state", c_int32), ("refcount", c_int32),
+        ("use_count", c_int64), ("last_used", c_int64), ("alpha", c_float), ("parts_filled", c_int32),
+    ]
+
+
+class lora_cache_stats_t(ctypes.Structure):
+    _fields_ = [(n, c_int64) for n in ("hits", "misses", "fills", "bytes_filled", "applies", "evictions")]
+
+
+class lora_item_t(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("tok_off", "n_tok", "slot", "rank", "a", "b", "c", "d")]
+
+
+class lora_worklists_t(ctypes.Structure):
+    _fields_ = [
+        ("n_tok_list", c_int32), ("n_tiles", c_int32), ("n_groups", c_int32), ("n_gs_items", c_int32), ("n_ge_items", c_int32),
+        ("tok_list", POINTER(c_int32)), ("tiles", POINTER(lora_item_t)), ("groups", POINTER(lora_item_t)),
+        ("gs_items", POINTER(lora_item_t)), ("ge_items", POINTER(lora_item_t)),
+    ]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2411_17741_amd.build` "
+        "(there is no fallback path; the HIP library is the product)"
+    )
+_lib = ctypes.CDLL(LIB_PATH)
+
+_i32p = POINTER(c_int32)
+_SIGS = {
+    "lora_adapter_bytes": (c_size_t, [c_int32, c_int32, c_int32, c_int32]),
+    "lora_cache_bytes_required": (c_size_t, [POINTER(lora_cache_config_t)]),
+    "lora_cache_create": (c_int, [POINTER(lora_cache_config_t), c_void_p, c_size_t, POINTER(c_void_p)]),
+    "lora_cache_destroy": (c_int, [c_void_p]),
+    "lora_cache_fill_slot": (c_int, [c_void_p, c_int32, c_int64, c_int32, c_float, c_int32, c_int32, c_void_p, c_void_p, c_void_p]),
+    "lora_cache_release_slot": (c_int, [c_void_p, c_int32]),
+    "lora_cache_slot_ref": (c_int, [c_void_p, c_int32, c_int32]),
+    "lora_cache_lookup": (c_int, [c_void_p, c_int64, _i32p, _i32p]),
+    "lora_cache_slot_info": (c_int, [c_void_p, c_int32, POINTER(lora_slot_info_t)]),
+    "lora_cache_find_free_slot": (c_int, [c_void_p, c_int32, _i32p]),
+    "lora_cache_stats": (c_int, [c_void_p, POINTER(lora_cache_stats_t)]),
+    "lora_cache_slab": (c_int, [c_void_p, c_int32, c_int32, c_int32, POINTER(c_void_p), POINTER(c_size_t)]),
+    "lora_index": (c_int, [c_int32, _i32p, _i32p, _i32p, c_int32, c_int32, POINTER(lora_worklists_t)]),
+    "lora_worklists_free": (None, [POINTER(lora_worklists_t)]),
+    "lora_plan_create": (c_int, [c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_void_p, POINTER(c_void_p)]),
+    "lora_plan_destroy": (c_int, [c_void_p, c_void_p]),
+    "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
+    "lora_apply": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_float, c_void_p]),
+    "lora_cache_set_fencing": (c_int, [c_void_p, c_int32]),
+    "lora_strerror": (c_char_p, [c_int]),
+    "lora_last_hip_error": (c_int, []),
+}
+EXPORTS = tuple(_SIGS)
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)  # AttributeError here = the library does not export a declared symbol
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def lora_strerror(status: int) -> str:
+    return _lib.lora_strerror(int(status)).decode()
+
+
+def lora_last_hip_error() -> int:
+    return int(_lib.lora_last_hip_error())
+
+
+def check(status: int, what: str = "liblora_cache") -> int:
+    if status < 0:
+        raise LoraError(status, what)
+    return status
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(_i32p)
+
+
+def make_config(proj: Sequence[Sequence[int]], n_layers: int, class_rank: Sequence[int], class_slots: Sequence[int],
+                dtype: int, max_tokens: int, max_segments: int, n_plans: int = 2, mfma_min_tokens: int = 0, flags: int = 0):
+    """Returns (config struct, keep-alive tuple of the arrays it points to)."""
+    pa = (lora_proj_t * len(proj))(*[lora_proj_t(int(a), int(b)) for a, b in proj])
+    cr = (c_int32 * len(class_rank))(*[int(v) for v in class_rank])
+    cs = (c_int32 * len(class_slots))(*[int(v) for v in class_slots])
+    cfg = lora_cache_config_t(len(proj), pa, int(n_layers), len(class_rank), cr, cs, int(dtype), int(max_tokens),
+                              int(max_segments), int(n_plans), int(mfma_min_tokens), int(flags))
+    cfg._keep = (pa, cr, cs)
+    return cfg
+
+
+def lora_adapter_bytes(h_in: int, h_out: int, rank: int, dtype: int) -> int:
+    return int(_lib.lora_adapter_bytes(h_in, h_out, rank, dtype))
+
+
+def lora_cache_bytes_required(cfg: lora_cache_config_t) -> int:
+    return int(_lib.lora_cache_bytes_required(ctypes.byref(cfg)))
+
+
+def lora_cache_create(cfg: lora_cache_config_t, dev_pool: int, dev_pool_bytes: int):
+    """-> (status, handle)"""
+    h = c_void_p()
+    rc = _lib.lora_cache_create(ctypes.byref(cfg), c_void_p(dev_pool or None), dev_pool_bytes, ctypes.byref(h))
+    return rc, h
+
+
+def lora_cache_destroy(cache) -> int:
+    return _lib.lora_cache_destroy(cache)
+
+
+def lora_cache_fill_slot(cache, slot: int, adapter_id: int, rank: int, alpha: float, layer: int, proj: int,
+                         host_A: int, host_B: int, fill_stream: int = 0) -> int:
+    return _lib.lora_cache_fill_slot(cache, slot, adapter_id, rank, alpha, layer, proj, c_void_p(host_A or None),
+                                     c_void_p(host_B or None), c_void_p(fill_stream or None))
+
+
+def lora_cache_release_slot(cache, slot: int) -> int:
+    return _lib.lora_cache_release_slot(cache, slot)
+
+
+def lora_cache_slot_ref(cache, slot: int, delta: int) -> int:
+    return _lib.lora_cache_slot_ref(cache, slot, delta)
+
+
+def lora_cache_lookup(cache, adapter_id: int):
+    """-> (status, slot, rank)"""
+    s, r = c_int32(-1), c_int32(0)
+    rc = _lib.lora_cache_lookup(cache, adapter_id, ctypes.byref(s), ctypes.byref(r))
+    return rc, s.value, r.value
+
+
+def lora_cache_slot_info(cache, slot: int):
+    """-> (status, lora_slot_info_t)"""
+    info = lora_slot_info_t()
+    rc = _lib.lora_cache_slot_info(cache, slot, ctypes.byref(info))
+    return rc, info
+
+
+def lora_cache_find_free_slot(cache, rank: int):
+    s = c_int32(-1)
+    rc = _lib.lora_cache_find_free_slot(cache, rank, ctypes.byref(s))
+    return rc, s.value
+
+
+def lora_cache_stats(cache):
+    st = lora_cache_stats_t()
+    rc = _lib.lora_cache_stats(cache, ctypes.byref(st))
+    return rc, st
+
+
+def lora_cache_slab(cache, layer: int, proj: int, slot: int):
+    """-> (status, device address, bytes)"""
+    p, n = c_void_p(), c_size_t()
+    rc = _lib.lora_cache_slab(cache, layer, proj, slot, ctypes.byref(p), ctypes.byref(n))
+    return rc, (p.value or 0), n.value
+
+
+def _items(ptr, n):
+    return [tuple(getattr(ptr[i], f) for f in ("tok_off", "n_tok", "slot", "rank", "a", "b")) for i in range(n)]
+
+
+def lora_index(T: int, seg_offsets, seg_slot, seg_rank, mfma_min_tokens: int):
+    """-> (status, dict of python lists with the same keys as the C struct)"""
+    so, ss, sr = _i32(seg_offsets), _i32(seg_slot), _i32(seg_rank)
+    w = lora_worklists_t()
+    rc = _lib.lora_index(T, _ptr(so), _ptr(ss), _ptr(sr), len(ss), mfma_min_tokens, ctypes.byref(w))
+    if rc != LORA_OK:
+        return rc, None
+    out = {
+        "tok_list": [w.tok_list[i] for i in range(w.n_tok_list)],
+        "tiles": _items(w.tiles, w.n_tiles),
+        "groups": _items(w.groups, w.n_groups),
+        "gs_items": _items(w.gs_items, w.n_gs_items),
+        "ge_items": _items(w.ge_items, w.n_ge_items),
+    }
+    _lib.lora_worklists_free(ctypes.byref(w))
+    return rc, out
+
+
+def lora_plan_create(cache, T: int, seg_offsets, seg_slot, seg_rank, stream: int = 0):
+    """-> (status, plan handle)"""
+    so, ss, sr = _i32(seg_offsets), _i32(seg_slot), _i32(seg_rank)
+    p = c_void_p()
+    rc = _lib.lora_plan_create(cache, T, _ptr(so), _ptr(ss), _ptr(sr), len(ss), c_void_p(stream or None), ctypes.byref(p))
+    return rc, p
+
+
+def lora_plan_destroy(cache, plan) -> int:
+    return _lib.lora_plan_destroy(cache, plan)
+
+
+def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, scale: float, stream: int = 0) -> int:
+    return _lib.lora_apply_plan(cache, plan, layer, proj, c_void_p(x or None), c_void_p(base_out or None), scale,
+                                c_void_p(stream or None))
+
+
+def lora_apply(cache, layer: int, proj: int, x: int, base_out: int, T: int, seg_offsets, seg_slot, seg_rank,
+               scale: float, stream: int = 0) -> int:
+    so, ss, sr = _i32(seg_offsets), _i32(seg_slot), _i32(seg_rank)
+    return _lib.lora_apply(cache, layer, proj, c_void_p(x or None), c_void_p(base_out or None), T, _ptr(so), _ptr(ss),
+                           _ptr(sr), len(ss), scale, c_void_p(stream or None))
+
+
+def lora_cache_set_fencing(cache, on: int) -> int:
+    return _lib.lora_cache_set_fencing(cache, on)

@@ -1,0 +1,681 @@
+// Host side of liblora_cache: pool layout, slot table (the adapter cache's entries and their
+// metadata, paper section 4.2), fills from host memory, plans and the apply launches.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "lora_internal.h"
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                          \
+    do {                                       \
+        hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) {                \
+            g_last_hip = (int)e_;              \
+            return LORA_E_HIP;                 \
+        }                                      \
+    } while (0)
+
+constexpr int N_INTERNAL_PLANS = 4;
+constexpr int N_STAGES = 2;
+constexpr int N_APPLY_EVENTS = 64;
+constexpr size_t ALIGN = 256;
+
+size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
+int esize_of(int dtype) { return dtype == LORA_BF16 ? 2 : 4; }
+
+struct Slot {
+    int32_t cls = 0;
+    bool bound = false;
+    int64_t adapter_id = 0;
+    int32_t rank = 0;
+    float alpha = 1.f;
+    int32_t refcount = 0;
+    int64_t use_count = 0, last_used = 0;
+    uint32_t generation = 0;  // bumped whenever the slot is bound to another adapter or evicted
+    std::vector<uint8_t> part;  // [n_layers * n_proj] 1 = data enqueued
+    int32_t parts_filled = 0;
+    hipEvent_t fill_ev = nullptr;
+    bool fill_pending = false;
+};
+
+struct Stage {
+    char *dev = nullptr;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+
+}  // namespace
+
+struct lora_plan {
+    bool in_use = false;
+    bool internal = false;
+    char *dev = nullptr;
+    char *pinned = nullptr;
+    hipEvent_t ev_upload = nullptr, ev_last_use = nullptr;
+    bool upload_pending = false, use_pending = false;
+    int32_t T = 0;
+    int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
+    size_t off_tiles = 0, off_gs = 0, off_ge = 0;
+    std::vector<int32_t> slots;        // distinct slots the batch names
+    std::vector<uint32_t> generations;  // their generation at plan time
+};
+
+struct lora_cache {
+    std::vector<lora_proj_t> proj;
+    std::vector<int32_t> class_rank, class_slots, class_first;
+    int32_t n_layers = 0, n_slots = 0, dtype = 0, esize = 0;
+    int32_t max_tokens = 0, max_segments = 0, n_user_plans = 0, mfma_min = 0, flags = 0;
+    int32_t v_stride = 0;
+    bool host_only = false;
+
+    char *pool = nullptr;
+    size_t pool_bytes = 0;
+    size_t layer_stride = 0;
+    std::vector<int64_t> slot_off;  // [n_proj][n_slots], relative to the layer base
+    std::vector<size_t> slab_bytes;  // [n_proj][n_classes]
+    size_t off_table = 0, off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
+
+    std::vector<Slot> slots;
+    std::unordered_map<int64_t, int32_t> id2slot;
+    std::vector<lora_plan> plans;  // user plans first, then the internal ring
+    uint64_t internal_next = 0;
+    Stage stage[N_STAGES];
+    uint64_t stage_next = 0;
+
+    bool fencing = true;
+    int64_t apply_seq = 0;
+    hipEvent_t apply_ev[N_APPLY_EVENTS] = {};
+    int64_t apply_ev_seq[N_APPLY_EVENTS] = {};
+
+    lora_cache_stats_t stats = {};
+};
+
+namespace {
+
+bool config_ok(const lora_cache_config_t *cfg)
+{
+    if (!cfg || cfg->n_proj < 1 || !cfg->proj || cfg->n_layers < 1 || cfg->n_classes < 1 || !cfg->class_rank ||
+        !cfg->class_slots)
+        return false;
+    if (cfg->dtype != LORA_F32 && cfg->dtype != LORA_BF16) return false;
+    if (cfg->max_tokens < 1 || cfg->max_segments < 1 || cfg->n_plans < 0 || cfg->mfma_min_tokens < 0) return false;
+    for (int p = 0; p < cfg->n_proj; ++p)
+        if (cfg->proj[p].h_in < 64 || cfg->proj[p].h_out < 64 || cfg->proj[p].h_in % 64 || cfg->proj[p].h_out % 64)
+            return false;
+    int64_t total_slots = 0;
+    for (int c = 0; c < cfg->n_classes; ++c) {
+        if (cfg->class_rank[c] < 1 || cfg->class_rank[c] > LORA_MAX_RANK || cfg->class_slots[c] < 0) return false;
+        if (c && cfg->class_rank[c] <= cfg->class_rank[c - 1]) return false;
+        total_slots += cfg->class_slots[c];
+    }
+    return total_slots >= 1 && total_slots < (1 << 24);
+}
+
+// Fills every layout field of `c` from the config; used by bytes_required and create alike.
+void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
+{
+    c.proj.assign(cfg->proj, cfg->proj + cfg->n_proj);
+    c.class_rank.assign(cfg->class_rank, cfg->class_rank + cfg->n_classes);
+    c.class_slots.assign(cfg->class_slots, cfg->class_slots + cfg->n_classes);
+    c.n_layers = cfg->n_layers;
+    c.dtype = cfg->dtype;
+    c.esize = esize_of(cfg->dtype);
+    c.max_tokens = cfg->max_tokens;
+    c.max_segments = cfg->max_segments;
+    c.n_user_plans = cfg->n_plans;
+    c.mfma_min = cfg->dtype == LORA_BF16 ? (cfg->mfma_min_tokens ? cfg->mfma_min_tokens : LORA_MFMA_MIN_TOKENS) : 0;
+    c.flags = cfg->flags;
+    c.host_only = (cfg->flags & LORA_CACHE_HOST_ONLY) != 0;
+
+    const int n_proj = cfg->n_proj, n_cls = cfg->n_classes;
+    c.class_first.resize(n_cls);
+    c.n_slots = 0;
+    for (int k = 0; k < n_cls; ++k) {
+        c.class_first[k] = c.n_slots;
+        c.n_slots += c.class_slots[k];
+    }
+    c.slab_bytes.assign((size_t)n_proj * n_cls, 0);
+    c.slot_off.assign((size_t)n_proj * c.n_slots, 0);
+    size_t off = 0, max_part = 0;
+    for (int p = 0; p < n_proj; ++p) {
+        const size_t width = (size_t)c.proj[p].h_in + (size_t)c.proj[p].h_out;
+        for (int k = 0; k < n_cls; ++k) {
+            const size_t sb = align_up((size_t)lora::rank_storage(c.class_rank[k]) * width * c.esize);
+            c.slab_bytes[(size_t)p * n_cls + k] = sb;
+            for (int s = 0; s < c.class_slots[k]; ++s) {
+                c.slot_off[(size_t)p * c.n_slots + c.class_first[k] + s] = (int64_t)off;
+                off += sb;
+            }
+        }
+        max_part = std::max(max_part, (size_t)c.class_rank[n_cls - 1] * width * c.esize);
+    }
+    c.layer_stride = off;
+    c.v_stride = (c.class_rank[n_cls - 1] + 31) / 32 * 32;
+
+    const size_t max_tiles = (size_t)c.max_tokens / LORA_TILE_TOKENS + 2 * (size_t)c.max_segments + 2;
+    const size_t max_items = max_tiles + (size_t)c.max_segments * (LORA_MAX_RANK / 4 + 16);
+    c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) + 3 * ALIGN;
+    c.stage_cap = align_up(max_part) + ALIGN;
+
+    size_t cur = c.layer_stride * (size_t)c.n_layers;
+    c.off_table = cur = align_up(cur);
+    cur += align_up(sizeof(int64_t) * c.slot_off.size());
+    c.off_v = cur;
+    cur += align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
+    c.off_plans = cur;
+    cur += c.plan_cap * (size_t)(c.n_user_plans + N_INTERNAL_PLANS);
+    c.off_stage = cur;
+    cur += c.stage_cap * N_STAGES;
+    c.total = cur;
+}
+
+int class_of_slot(const lora_cache &c, int32_t slot)
+{
+    int k = (int)c.class_first.size() - 1;
+    while (k > 0 && slot < c.class_first[k]) --k;
+    return k;
+}
+
+void unbind(lora_cache &c, Slot &s)
+{
+    if (s.bound) {
+        auto it = c.id2slot.find(s.adapter_id);
+        if (it != c.id2slot.end() && &c.slots[it->second] == &s) c.id2slot.erase(it);
+    }
+    s.bound = false;
+    s.adapter_id = 0;
+    s.rank = 0;
+    s.alpha = 1.f;
+    s.use_count = 0;
+    s.parts_filled = 0;
+    std::fill(s.part.begin(), s.part.end(), 0);
+    ++s.generation;
+}
+
+int slot_state(lora_cache &c, Slot &s)
+{
+    if (!s.bound) return LORA_SLOT_EMPTY;
+    if (s.parts_filled < (int32_t)s.part.size()) return LORA_SLOT_FILLING;
+    if (s.fill_pending && !c.host_only) {
+        if (hipEventQuery(s.fill_ev) == hipSuccess) s.fill_pending = false;
+        else return LORA_SLOT_FILLING;
+    }
+    return LORA_SLOT_READY;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+bool is_capturing(hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs != hipStreamCaptureStatusNone;
+}
+
+// Validates a batch against the slot table and writes its work lists into plan `p`
+// (pinned copy + upload on `st`).
+int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
+               const int32_t *seg_rank, int32_t n_seg, hipStream_t st)
+{
+    if (T < 0 || T > c.max_tokens || n_seg < 0 || n_seg > c.max_segments) return LORA_E_INVAL;
+    lora_worklists_t w;
+    int rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, c.mfma_min, &w);
+    if (rc != LORA_OK) return rc;
+
+    p.slots.clear();
+    p.generations.clear();
+    auto check = [&](const lora_item_t &it) -> int {
+        if (it.slot >= c.n_slots) return LORA_E_INVAL;
+        const Slot &s = c.slots[it.slot];
+        if (!s.bound) return LORA_E_STATE;
+        if (s.rank != it.rank) return LORA_E_INVAL;
+        if (p.slots.empty() || p.slots.back() != it.slot) {
+            p.slots.push_back(it.slot);
+        }
+        return LORA_OK;
+    };
+    for (int i = 0; i < w.n_tiles && rc == LORA_OK; ++i) rc = check(w.tiles[i]);
+    for (int i = 0; i < w.n_groups && rc == LORA_OK; ++i) rc = check(w.groups[i]);
+    if (rc != LORA_OK) {
+        lora_worklists_free(&w);
+        return rc;
+    }
+    std::sort(p.slots.begin(), p.slots.end());
+    p.slots.erase(std::unique(p.slots.begin(), p.slots.end()), p.slots.end());
+    for (int32_t s : p.slots) p.generations.push_back(c.slots[s].generation);
+
+    auto stamp = [&](lora_item_t *items, int n) {
+        for (int i = 0; i < n; ++i) std::memcpy(&items[i].c, &c.slots[items[i].slot].alpha, sizeof(float));
+    };
+    stamp(w.tiles, w.n_tiles);
+    stamp(w.gs_items, w.n_gs_items);
+    stamp(w.ge_items, w.n_ge_items);
+
+    p.T = T;
+    p.n_tok_list = w.n_tok_list;
+    p.n_tiles = w.n_tiles;
+    p.n_gs = w.n_gs_items;
+    p.n_ge = w.n_ge_items;
+    p.off_tiles = align_up(sizeof(int32_t) * (size_t)w.n_tok_list);
+    p.off_gs = p.off_tiles + align_up(sizeof(lora_item_t) * (size_t)w.n_tiles);
+    p.off_ge = p.off_gs + align_up(sizeof(lora_item_t) * (size_t)w.n_gs_items);
+    const size_t bytes = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    if (bytes > c.plan_cap) {
+        lora_worklists_free(&w);
+        return LORA_E_NOMEM;
+    }
+    if (!c.host_only) {
+        // A captured upload would re-read the pinned copy on every replay; plans are made
+        // outside of captures.
+        if (is_capturing(st)) {
+            lora_worklists_free(&w);
+            return LORA_E_STATE;
+        }
+        // the pinned copy may still be the source of an earlier upload; the device copy may
+        // still be read by earlier applies
+        if (p.upload_pending) {
+            HIP_TRY(hipEventSynchronize(p.ev_upload));
+            p.upload_pending = false;
+        }
+        if (p.use_pending) {
+            HIP_TRY(hipStreamWaitEvent(st, p.ev_last_use, 0));
+            p.use_pending = false;
+        }
+        std::memcpy(p.pinned, w.tok_list, sizeof(int32_t) * (size_t)w.n_tok_list);
+        std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
+        std::memcpy(p.pinned + p.off_gs, w.gs_items, sizeof(lora_item_t) * (size_t)w.n_gs_items);
+        std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
+        lora_worklists_free(&w);
+        if (bytes) {
+            HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipEventRecord(p.ev_upload, st));
+            p.upload_pending = true;
+        }
+    } else {
+        lora_worklists_free(&w);
+    }
+    return LORA_OK;
+}
+
+int choose_k_splits(int n_tiles, int h_in)
+{
+    // enough blocks to cover the chip twice, k ranges of at least 256
+    int want = (512 + n_tiles - 1) / n_tiles;
+    const int cap = std::max(1, h_in / 256);
+    want = std::max(1, std::min(want, cap));
+    int k_len = (h_in + want - 1) / want;
+    k_len = (k_len + 63) / 64 * 64;
+    return (h_in + k_len - 1) / k_len;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *lora_strerror(int status)
+{
+    switch (status) {
+        case LORA_OK: return "ok";
+        case LORA_E_INVAL: return "invalid argument";
+        case LORA_E_STATE: return "cache slot in the wrong state";
+        case LORA_E_NOMEM: return "out of pool / plan / host memory";
+        case LORA_E_HIP: return "HIP call failed";
+        case LORA_E_NOTFOUND: return "adapter not cached";
+        default: return "unknown status";
+    }
+}
+
+int lora_last_hip_error(void) { return g_last_hip; }
+
+size_t lora_adapter_bytes(int32_t h_in, int32_t h_out, int32_t rank, int32_t dtype)
+{
+    if (h_in < 1 || h_out < 1 || rank < 1 || (dtype != LORA_F32 && dtype != LORA_BF16)) return 0;
+    return (size_t)rank * ((size_t)h_in + (size_t)h_out) * esize_of(dtype);
+}
+
+size_t lora_cache_bytes_required(const lora_cache_config_t *cfg)
+{
+    if (!config_ok(cfg)) return 0;
+    lora_cache tmp;
+    compute_layout(tmp, cfg);
+    return tmp.total;
+}
+
+int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev_pool_bytes, lora_cache_t **out)
+{
+    if (!out) return LORA_E_INVAL;
+    *out = nullptr;
+    if (!config_ok(cfg)) return LORA_E_INVAL;
+    lora_cache *c = new (std::nothrow) lora_cache;
+    if (!c) return LORA_E_NOMEM;
+    compute_layout(*c, cfg);
+    c->slots.resize(c->n_slots);
+    for (int32_t s = 0; s < c->n_slots; ++s) {
+        c->slots[s].cls = class_of_slot(*c, s);
+        c->slots[s].part.assign((size_t)c->n_layers * c->proj.size(), 0);
+    }
+    c->plans.resize(c->n_user_plans + N_INTERNAL_PLANS);
+    for (size_t i = 0; i < c->plans.size(); ++i) c->plans[i].internal = (int)i >= c->n_user_plans;
+    if (c->host_only) {
+        *out = c;
+        return LORA_OK;
+    }
+    if (!dev_pool || (reinterpret_cast<uintptr_t>(dev_pool) & (ALIGN - 1))) {
+        delete c;
+        return LORA_E_INVAL;
+    }
+    if (dev_pool_bytes < c->total) {
+        delete c;
+        return LORA_E_NOMEM;
+    }
+    c->pool = static_cast<char *>(dev_pool);
+    c->pool_bytes = dev_pool_bytes;
+
+    int rc = LORA_OK;
+    auto fail = [&](hipError_t e) {
+        if (e != hipSuccess && rc == LORA_OK) {
+            g_last_hip = (int)e;
+            rc = LORA_E_HIP;
+        }
+    };
+    fail(hipMemcpy(c->pool + c->off_table, c->slot_off.data(), sizeof(int64_t) * c->slot_off.size(), hipMemcpyHostToDevice));
+    for (size_t i = 0; i < c->plans.size() && rc == LORA_OK; ++i) {
+        lora_plan &p = c->plans[i];
+        p.dev = c->pool + c->off_plans + c->plan_cap * i;
+        fail(hipHostMalloc(reinterpret_cast<void **>(&p.pinned), c->plan_cap, hipHostMallocDefault));
+        fail(hipEventCreateWithFlags(&p.ev_upload, hipEventDisableTiming));
+        fail(hipEventCreateWithFlags(&p.ev_last_use, hipEventDisableTiming));
+    }
+    for (int i = 0; i < N_STAGES && rc == LORA_OK; ++i) {
+        c->stage[i].dev = c->pool + c->off_stage + c->stage_cap * i;
+        fail(hipEventCreateWithFlags(&c->stage[i].ev, hipEventDisableTiming));
+    }
+    for (int i = 0; i < N_APPLY_EVENTS && rc == LORA_OK; ++i) fail(hipEventCreateWithFlags(&c->apply_ev[i], hipEventDisableTiming));
+    if (rc != LORA_OK) {
+        lora_cache_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return LORA_OK;
+}
+
+int lora_cache_destroy(lora_cache_t *c)
+{
+    if (!c) return LORA_E_INVAL;
+    if (!c->host_only) {
+        for (auto &p : c->plans) {
+            if (p.pinned) (void)hipHostFree(p.pinned);
+            if (p.ev_upload) (void)hipEventDestroy(p.ev_upload);
+            if (p.ev_last_use) (void)hipEventDestroy(p.ev_last_use);
+        }
+        for (auto &s : c->stage)
+            if (s.ev) (void)hipEventDestroy(s.ev);
+        for (auto &e : c->apply_ev)
+            if (e) (void)hipEventDestroy(e);
+        for (auto &s : c->slots)
+            if (s.fill_ev) (void)hipEventDestroy(s.fill_ev);
+    }
+    delete c;
+    return LORA_OK;
+}
+
+int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha, int32_t layer,
+                         int32_t proj, const void *host_A, const void *host_B, void *fill_stream)
+{
+    if (!c || slot < 0 || slot >= c->n_slots || layer < 0 || layer >= c->n_layers || proj < 0 ||
+        proj >= (int32_t)c->proj.size() || rank < 1)
+        return LORA_E_INVAL;
+    Slot &s = c->slots[slot];
+    if (rank > c->class_rank[s.cls]) return LORA_E_INVAL;
+    if (!c->host_only && (!host_A || !host_B)) return LORA_E_INVAL;
+    const size_t part = (size_t)layer * c->proj.size() + proj;
+
+    if (s.bound) {
+        if (s.adapter_id != adapter_id || s.rank != rank || s.alpha != alpha) return LORA_E_STATE;
+        if (s.part[part] && s.refcount > 0) return LORA_E_STATE;  // would overwrite data in use
+    } else {
+        auto other = c->id2slot.find(adapter_id);
+        if (other != c->id2slot.end()) return LORA_E_STATE;  // the adapter is already cached elsewhere
+        s.bound = true;
+        s.adapter_id = adapter_id;
+        s.rank = rank;
+        s.alpha = alpha;
+        s.use_count = 0;
+        ++s.generation;
+        c->id2slot[adapter_id] = slot;
+    }
+
+    const int32_t h_in = c->proj[proj].h_in, h_out = c->proj[proj].h_out;
+    const size_t bytes_a = (size_t)rank * h_in * c->esize, bytes_b = (size_t)rank * h_out * c->esize;
+    if (!c->host_only) {
+        hipStream_t st = static_cast<hipStream_t>(fill_stream);
+        Stage &sg = c->stage[c->stage_next++ % N_STAGES];
+        if (sg.pending) HIP_TRY(hipStreamWaitEvent(st, sg.ev, 0));
+        if (c->fencing && s.last_used > 0) {
+            // applies enqueued earlier may still read this slab
+            HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
+        }
+        char *stage_b = sg.dev + align_up(bytes_a);
+        HIP_TRY(hipMemcpyAsync(sg.dev, host_A, bytes_a, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(stage_b, host_B, bytes_b, hipMemcpyHostToDevice, st));
+        char *slab = c->pool + (size_t)layer * c->layer_stride + c->slot_off[(size_t)proj * c->n_slots + slot];
+        HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, st));
+        HIP_TRY(hipEventRecord(sg.ev, st));
+        sg.pending = true;
+        if (!s.fill_ev) HIP_TRY(hipEventCreateWithFlags(&s.fill_ev, hipEventDisableTiming));
+        HIP_TRY(hipEventRecord(s.fill_ev, st));
+        s.fill_pending = true;
+    }
+    if (!s.part[part]) {
+        s.part[part] = 1;
+        ++s.parts_filled;
+    }
+    ++c->stats.fills;
+    c->stats.bytes_filled += (int64_t)(bytes_a + bytes_b);
+    return LORA_OK;
+}
+
+int lora_cache_release_slot(lora_cache_t *c, int32_t slot)
+{
+    if (!c || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;
+    Slot &s = c->slots[slot];
+    if (s.refcount > 0) return LORA_E_STATE;
+    if (s.bound) ++c->stats.evictions;
+    unbind(*c, s);
+    return LORA_OK;
+}
+
+int lora_cache_slot_ref(lora_cache_t *c, int32_t slot, int32_t delta)
+{
+    if (!c || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;
+    Slot &s = c->slots[slot];
+    if (!s.bound) return LORA_E_STATE;
+    if (s.refcount + delta < 0) return LORA_E_STATE;
+    s.refcount += delta;
+    return LORA_OK;
+}
+
+int lora_cache_lookup(lora_cache_t *c, int64_t adapter_id, int32_t *slot, int32_t *rank)
+{
+    if (!c) return LORA_E_INVAL;
+    auto it = c->id2slot.find(adapter_id);
+    if (it == c->id2slot.end()) {
+        ++c->stats.misses;
+        return LORA_E_NOTFOUND;
+    }
+    ++c->stats.hits;
+    if (slot) *slot = it->second;
+    if (rank) *rank = c->slots[it->second].rank;
+    return LORA_OK;
+}
+
+int lora_cache_slot_info(lora_cache_t *c, int32_t slot, lora_slot_info_t *out)
+{
+    if (!c || !out || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;
+    Slot &s = c->slots[slot];
+    out->adapter_id = s.adapter_id;
+    out->rank = s.rank;
+    out->class_rank = c->class_rank[s.cls];
+    out->state = slot_state(*c, s);
+    out->refcount = s.refcount;
+    out->use_count = s.use_count;
+    out->last_used = s.last_used;
+    out->alpha = s.alpha;
+    out->parts_filled = s.parts_filled;
+    return LORA_OK;
+}
+
+int lora_cache_find_free_slot(lora_cache_t *c, int32_t rank, int32_t *slot)
+{
+    if (!c || !slot || rank < 1) return LORA_E_INVAL;
+    for (size_t k = 0; k < c->class_rank.size(); ++k) {
+        if (c->class_rank[k] < rank) continue;
+        for (int32_t s = c->class_first[k]; s < c->class_first[k] + c->class_slots[k]; ++s)
+            if (!c->slots[s].bound) {
+                *slot = s;
+                return LORA_OK;
+            }
+    }
+    return LORA_E_NOMEM;
+}
+
+int lora_cache_stats(const lora_cache_t *c, lora_cache_stats_t *out)
+{
+    if (!c || !out) return LORA_E_INVAL;
+    *out = c->stats;
+    return LORA_OK;
+}
+
+int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t slot, void **dev_ptr, size_t *bytes)
+{
+    if (!c || layer < 0 || layer >= c->n_layers || proj < 0 || proj >= (int32_t)c->proj.size() || slot < 0 ||
+        slot >= c->n_slots)
+        return LORA_E_INVAL;
+    if (dev_ptr)
+        *dev_ptr = c->pool ? c->pool + (size_t)layer * c->layer_stride + c->slot_off[(size_t)proj * c->n_slots + slot]
+                           : nullptr;
+    if (bytes) *bytes = c->slab_bytes[(size_t)proj * c->class_rank.size() + c->slots[slot].cls];
+    return LORA_OK;
+}
+
+int lora_cache_set_fencing(lora_cache_t *c, int32_t on)
+{
+    if (!c) return LORA_E_INVAL;
+    c->fencing = on != 0;
+    return LORA_OK;
+}
+
+int lora_plan_create(lora_cache_t *c, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
+                     const int32_t *seg_rank, int32_t n_seg, void *stream, lora_plan_t **out)
+{
+    if (!c || !out) return LORA_E_INVAL;
+    *out = nullptr;
+    lora_plan *p = nullptr;
+    for (int i = 0; i < c->n_user_plans; ++i)
+        if (!c->plans[i].in_use) {
+            p = &c->plans[i];
+            break;
+        }
+    if (!p) return LORA_E_NOMEM;
+    const int rc = build_plan(*c, *p, T, seg_offsets, seg_slot, seg_rank, n_seg, static_cast<hipStream_t>(stream));
+    if (rc != LORA_OK) return rc;
+    p->in_use = true;
+    *out = p;
+    return LORA_OK;
+}
+
+int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p)
+{
+    if (!c || !p || p->internal || !p->in_use) return LORA_E_INVAL;
+    if (p < c->plans.data() || p >= c->plans.data() + c->n_user_plans) return LORA_E_INVAL;
+    p->in_use = false;
+    return LORA_OK;
+}
+
+int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
+                    float scale, void *stream)
+{
+    if (!c || !p || !p->in_use || c->host_only) return LORA_E_INVAL;
+    if (layer < 0 || layer >= c->n_layers || proj < 0 || proj >= (int32_t)c->proj.size()) return LORA_E_INVAL;
+    if (p->T > 0 && (!x || !base_out || !aligned16(x) || !aligned16(base_out))) return LORA_E_INVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t part = (size_t)layer * c->proj.size() + proj;
+
+    for (size_t i = 0; i < p->slots.size(); ++i) {
+        Slot &s = c->slots[p->slots[i]];
+        if (!s.bound || s.generation != p->generations[i] || !s.part[part]) return LORA_E_STATE;
+    }
+    for (int32_t sl : p->slots) {
+        Slot &s = c->slots[sl];
+        if (s.fill_pending) {
+            if (hipEventQuery(s.fill_ev) == hipSuccess) s.fill_pending = false;
+            else HIP_TRY(hipStreamWaitEvent(st, s.fill_ev, 0));
+        }
+    }
+
+    lora::ApplyArgs a;
+    a.layer_base = c->pool + (size_t)layer * c->layer_stride;
+    a.slot_off = reinterpret_cast<const int64_t *>(c->pool + c->off_table) + (size_t)proj * c->n_slots;
+    a.tok_list = reinterpret_cast<const int32_t *>(p->dev);
+    a.x = x;
+    a.y = base_out;
+    a.v = reinterpret_cast<float *>(c->pool + c->off_v);
+    a.h_in = c->proj[proj].h_in;
+    a.h_out = c->proj[proj].h_out;
+    a.v_stride = c->v_stride;
+    a.scale = scale;
+    const lora_item_t *tiles = reinterpret_cast<const lora_item_t *>(p->dev + p->off_tiles);
+    const lora_item_t *gs = reinterpret_cast<const lora_item_t *>(p->dev + p->off_gs);
+    const lora_item_t *ge = reinterpret_cast<const lora_item_t *>(p->dev + p->off_ge);
+
+    if (p->n_tiles > 0) {
+        const int splits = choose_k_splits(p->n_tiles, a.h_in);
+        if (splits > 1) HIP_TRY(lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st));
+        HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, st));
+    }
+    HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st));
+    HIP_TRY(lora::launch_mfma_expand(a, tiles, p->n_tiles, st));
+    HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st));
+
+    const int64_t seq = ++c->apply_seq;
+    ++c->stats.applies;
+    for (int32_t sl : p->slots) {
+        c->slots[sl].last_used = seq;
+        ++c->slots[sl].use_count;
+    }
+    if (c->fencing && !is_capturing(st)) {
+        HIP_TRY(hipEventRecord(c->apply_ev[seq % N_APPLY_EVENTS], st));
+        c->apply_ev_seq[seq % N_APPLY_EVENTS] = seq;
+        HIP_TRY(hipEventRecord(p->ev_last_use, st));
+        p->use_pending = true;
+    }
+    return LORA_OK;
+}
+
+int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void *base_out, int32_t T,
+               const int32_t *seg_offsets, const int32_t *seg_slot, const int32_t *seg_rank, int32_t n_seg, float scale,
+               void *stream)
+{
+    if (!c || c->host_only) return LORA_E_INVAL;
+    lora_plan &p = c->plans[c->n_user_plans + (c->internal_next % N_INTERNAL_PLANS)];
+    int rc = build_plan(*c, p, T, seg_offsets, seg_slot, seg_rank, n_seg, static_cast<hipStream_t>(stream));
+    if (rc != LORA_OK) return rc;
+    ++c->internal_next;
+    p.in_use = true;
+    rc = lora_apply_plan(c, &p, layer, proj, x, base_out, scale, stream);
+    p.in_use = false;
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Device-side helpers for the gfx950 kernels: 8-element chunks of fp32 / bf16, conversions,
+// wavefront reduction.
+#pragma once
+
+#include "lora_internal.h"
+
+namespace lora {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// 8 consecutive elements: one 16-byte vector of bf16, two of fp32.
+template <typename E> struct Chunk;
+template <> struct __attribute__((aligned(16))) Chunk<__bf16> { uint4 v; };
+template <> struct __attribute__((aligned(16))) Chunk<float> { float4 lo, hi; };
+
+template <typename E> __device__ __forceinline__ Chunk<E> load_chunk(const E *p)
+{
+    return *reinterpret_cast<const Chunk<E> *>(p);
+}
+template <typename E> __device__ __forceinline__ void store_chunk(E *p, const Chunk<E> &c)
+{
+    *reinterpret_cast<Chunk<E> *>(p) = c;
+}
+template <typename E> __device__ __forceinline__ Chunk<E> zero_chunk();
+template <> __device__ __forceinline__ Chunk<__bf16> zero_chunk<__bf16>()
+{
+    Chunk<__bf16> c;
+    c.v = make_uint4(0, 0, 0, 0);
+    return c;
+}
+template <> __device__ __forceinline__ Chunk<float> zero_chunk<float>()
+{
+    Chunk<float> c;
+    c.lo = make_float4(0, 0, 0, 0);
+    c.hi = make_float4(0, 0, 0, 0);
+    return c;
+}
+
+// bf16 pair packed in a 32-bit word: element 0 in the low half
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ void unpack_chunk(const Chunk<__bf16> &c, float (&f)[8])
+{
+    f[0] = bf_lo(c.v.x); f[1] = bf_hi(c.v.x);
+    f[2] = bf_lo(c.v.y); f[3] = bf_hi(c.v.y);
+    f[4] = bf_lo(c.v.z); f[5] = bf_hi(c.v.z);
+    f[6] = bf_lo(c.v.w); f[7] = bf_hi(c.v.w);
+}
+__device__ __forceinline__ void unpack_chunk(const Chunk<float> &c, float (&f)[8])
+{
+    f[0] = c.lo.x; f[1] = c.lo.y; f[2] = c.lo.z; f[3] = c.lo.w;
+    f[4] = c.hi.x; f[5] = c.hi.y; f[6] = c.hi.z; f[7] = c.hi.w;
+}
+
+template <typename E> __device__ __forceinline__ float dot_chunk(const Chunk<E> &a, const Chunk<E> &b)
+{
+    float fa[8], fb[8];
+    unpack_chunk(a, fa);
+    unpack_chunk(b, fb);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += fa[i] * fb[i];
+    return s;
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(__bf16 v) { return (float)v; }
+template <typename E> __device__ __forceinline__ E from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ __bf16 from_float<__bf16>(float v) { return (__bf16)v; }  // round to nearest even
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+}  // namespace lora

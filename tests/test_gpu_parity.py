@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same seeded
+inputs.  Tolerances for bf16 storage with fp32 accumulation: relative Frobenius error <= 1e-2
+and every element within 2e-2 * RMS(y).  Because the adapter delta is several times smaller
+than base_out, the error is also measured against the delta alone: what is left of the
+Frobenius error after allowing for the single bf16 rounding of the stored output (at most 2^-9
+of |y|) must stay within 2e-2 of |y - base_out|_F, so a kernel that does nothing, or drops a
+segment, fails.  fp32 instances: 1e-5 / 1e-4 / 1e-4 with 2^-24.  Integer-valued inputs must match
+bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = {"bf16": dict(rel_fro=1e-2, max_abs_over_rms=2e-2, delta_rel_fro=2e-2),
+       "f32": dict(rel_fro=1e-5, max_abs_over_rms=1e-4, delta_rel_fro=1e-4)}
+
+
+def _mods():
+    from paper_2411_17741_amd import binding as B
+    from paper_2411_17741_amd import harness as H
+    return B, H
+
+
+def _oracle_adapters(inst, p, which):
+    return {int(a): (*inst.adapter_weights(int(a), p), float(inst.alpha[a])) for a in which}
+
+
+EPS = {"bf16": 2.0**-9, "f32": 2.0**-24}
+
+
+def _check(m, dtype, what):
+    for k, lim in TOL[dtype].items():
+        assert m[k] <= lim, f"{what}: {k} = {m[k]:.3e} > {lim}"
+
+
+def _full_parity(inst, p=0, layer=0, pi=None, mfma_min_tokens=0):
+    B, H = _mods()
+    own = pi is None
+    if own:
+        pi = H.PooledInstance(inst, mfma_min_tokens=mfma_min_tokens)
+    try:
+        x, base = inst.x(p), inst.base_out(p)
+        xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+        pi.apply(layer, p, xd, yd)
+        torch.cuda.synchronize()
+        y = yd.float().cpu().numpy()
+        ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, p, inst.used_adapters()), inst.scale)
+        m = H.error_metrics(y, ref, base, EPS[inst.dtype])
+        _check(m, inst.dtype, f"{inst.name} proj {p}")
+        ta = inst.token_adapter()
+        assert np.array_equal(y[ta < 0], base[ta < 0]), "tokens without adapter must be untouched"
+        return m
+    finally:
+        if own:
+            pi.close()
+
+
+def test_tiny_fp32():
+    B, H = _mods()
+    inst = wl.tiny()
+    pi = H.PooledInstance(inst)
+    x = inst.x(0)
+    base = (x.astype(np.float64) @ inst.base_weight(0).astype(np.float64)).astype(np.float32)
+    xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+    pi.apply(0, 0, xd, yd)
+    torch.cuda.synchronize()
+    ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
+    _check(H.error_metrics(yd.cpu().numpy(), ref, base, EPS["f32"]), "f32", "tiny")
+    pi.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_small_mixed_all_paths(dtype, seed):
+    inst = wl.small_mixed(seed=seed, dtype=dtype)
+    B, H = _mods()
+    pi = H.PooledInstance(inst)
+    try:
+        for p in range(len(inst.projs)):
+            _full_parity(inst, p, pi=pi)
+    finally:
+        pi.close()
+
+
+def test_decode_config():
+    _full_parity(wl.decode())
+
+
+def test_prefill_config():
+    _full_parity(wl.prefill())
+
+
+@pytest.mark.parametrize("m0", [1, 8, 64])
+def test_threshold_between_paths_does_not_change_results(m0):
+    _full_parity(wl.small_mixed(seed=2), p=0, mfma_min_tokens=m0)
+    _full_parity(wl.small_mixed(seed=2), p=1, mfma_min_tokens=m0)
+
+
+def test_integer_inputs_are_bit_exact():
+    """Small integers: every product and partial sum is exact in fp32 and the result is a
+    bf16 number, so any difference is an indexing error, not rounding."""
+    B, H = _mods()
+    rng = np.random.default_rng(0)
+    ii = wl.small_mixed(seed=5)
+    wcache = {}
+
+    def adapter_weights(a, p):
+        if (a, p) not in wcache:
+            pr, r = ii.projs[p], int(ii.ranks[a])
+            g = np.random.default_rng(1000 * a + p)
+            A = g.integers(-1, 2, size=(pr.h_in, r)).astype(np.float32) * (g.random((pr.h_in, r)) < 0.02)
+            Bm = g.integers(-1, 2, size=(r, pr.h_out)).astype(np.float32) * (g.random((r, pr.h_out)) < 0.1)
+            wcache[(a, p)] = (A.astype(np.float32), Bm.astype(np.float32))
+        return wcache[(a, p)]
+
+    ii.adapter_weights = adapter_weights
+    ii.scale = 1.0
+    pi = H.PooledInstance(ii)
+    try:
+        for p in range(len(ii.projs)):
+            x = rng.integers(-2, 3, size=(ii.T, ii.projs[p].h_in)).astype(np.float32)
+            base = rng.integers(-8, 9, size=(ii.T, ii.projs[p].h_out)).astype(np.float32)
+            xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+            pi.apply(0, p, xd, yd)
+            torch.cuda.synchronize()
+            ref = oracle.lora_apply(x, base, ii.seg_offsets, ii.seg_adapter, _oracle_adapters(ii, p, ii.used_adapters()), ii.scale)
+            y = yd.float().cpu().numpy().astype(np.float64)
+            assert np.abs(ref).max() < 256 and np.array_equal(ref, np.round(ref))
+            assert np.abs(ref - base).max() > 0
+            assert np.array_equal(y, ref)
+    finally:
+        pi.close()
+
+
+def test_zero_B_leaves_base_bit_identical():
+    B, H = _mods()
+    inst = wl.small_mixed(seed=3)
+    orig = inst.adapter_weights
+    inst.adapter_weights = lambda a, p: (orig(a, p)[0], np.zeros_like(orig(a, p)[1]))
+    pi = H.PooledInstance(inst)
+    try:
+        x, base = inst.x(0), inst.base_out(0)
+        xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+        pi.apply(0, 0, xd, yd)
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.float().cpu().numpy(), base)
+    finally:
+        pi.close()
+
+
+def _custom_instance(lens, adapters, ranks, h_in=256, h_out=320, dtype="bf16", seed=0):
+    """Segments of the given lengths, segment g -> pool adapter adapters[g] (-1 = none)."""
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    return wl.Instance(
+        name="custom", dtype=dtype, seed=seed, projs=[wl.Projection("p", h_in, h_out, 0)],
+        ranks=np.asarray(ranks, np.int32), adapter_ids=np.arange(len(ranks), dtype=np.int64) + 1,
+        alpha=np.linspace(0.5, 1.5, len(ranks)).astype(np.float32), scale=2.0,
+        seg_offsets=off, seg_adapter=np.asarray(adapters, np.int32),
+    )
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_lengths_and_odd_ranks(dtype):
+    """Tile boundaries (15/16/17, 63/64/65, 128/129), empty segments, base-only segments,
+    ranks that are not multiples of 8 or 16, per-adapter alpha."""
+    lens = [15, 16, 17, 0, 63, 64, 65, 1, 129, 128, 2, 0, 1]
+    ranks = [1, 4, 8, 12, 16, 24, 40, 100, 128, 7]
+    adapters = [0, 1, 2, 3, 4, 5, 6, -1, 7, 8, 9, 2, 9]
+    _full_parity(_custom_instance(lens, adapters, ranks, dtype=dtype))
+
+
+def test_empty_and_adapterless_batches():
+    B, H = _mods()
+    inst = _custom_instance([3, 2], [-1, -1], [8])
+    pi = H.PooledInstance(inst, adapters=[0])
+    try:
+        x, base = inst.x(0), inst.base_out(0)
+        xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+        pi.apply(0, 0, xd, yd)
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.float().cpu().numpy(), base)
+        # T = 0
+        assert B.lora_apply(pi.pool.handle, 0, 0, 0, 0, 0, [0], [], [], 1.0) == B.LORA_OK
+        assert B.lora_apply(pi.pool.handle, 0, 0, xd.data_ptr(), yd.data_ptr(), 0, [0, 0], [0], [8], 1.0) == B.LORA_OK
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.float().cpu().numpy(), base)
+    finally:
+        pi.close()
+
+
+def test_single_token_max_rank_wide_projection():
+    inst = _custom_instance([1], [0], [128], h_in=11008, h_out=4096)
+    _full_parity(inst)
+    inst = _custom_instance([1, 70], [0, 1], [128, 128], h_in=4096, h_out=11008, seed=1)
+    _full_parity(inst)
+
+
+def test_apply_errors():
+    B, H = _mods()
+    inst = _custom_instance([4, 4], [0, 1], [8, 16])
+    pi = H.PooledInstance(inst, adapters=[0])  # adapter 1 is not resident
+    try:
+        x, base = inst.x(0), inst.base_out(0)
+        xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+        h = pi.pool.handle
+        args = (inst.seg_offsets, pi.seg_slot, pi.seg_rank, 2.0)
+        assert B.lora_apply(h, 0, 0, xd.data_ptr(), yd.data_ptr(), inst.T, *args) == B.LORA_E_STATE
+        pi.fill([1], [0])
+        assert B.lora_apply(h, 1, 0, xd.data_ptr(), yd.data_ptr(), inst.T, *args) == B.LORA_E_INVAL  # no such layer
+        assert B.lora_apply(h, 0, 0, 0, yd.data_ptr(), inst.T, *args) == B.LORA_E_INVAL
+        assert B.lora_apply(h, 0, 0, xd.data_ptr() + 2, yd.data_ptr(), inst.T, *args) == B.LORA_E_INVAL  # misaligned
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.float().cpu().numpy(), base), "failed calls must not touch base_out"
+        assert B.lora_apply(h, 0, 0, xd.data_ptr(), yd.data_ptr(), inst.T, *args) == B.LORA_OK
+        torch.cuda.synchronize()
+        # evicted slot: plan made before the eviction is refused
+        rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+        assert rc == B.LORA_OK
+        assert B.lora_cache_release_slot(h, int(pi.slot_of[1])) == B.LORA_OK
+        assert B.lora_apply_plan(h, plan, 0, 0, xd.data_ptr(), yd.data_ptr(), 2.0) == B.LORA_E_STATE
+    finally:
+        pi.close()
+
+
+def test_plan_reuse_over_projections_and_layers():
+    """One plan per iteration, applied to every projection of every layer copy."""
+    B, H = _mods()
+    inst = wl.small_mixed(seed=7)
+    pi = H.PooledInstance(inst, n_layers=2)
+    try:
+        plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+        for layer in range(2):
+            for p in range(len(inst.projs)):
+                x, base = inst.x(p), inst.base_out(p)
+                xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+                pi.pool.apply_plan(plan, layer, p, xd, yd, inst.scale)
+                torch.cuda.synchronize()
+                ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, p, inst.used_adapters()), inst.scale)
+                _check(H.error_metrics(yd.float().cpu().numpy(), ref, base), "bf16", f"layer {layer} proj {p}")
+        pi.pool.plan_destroy(plan)
+        rc, info = B.lora_cache_slot_info(pi.pool.handle, int(pi.seg_slot[pi.seg_slot >= 0][0]))
+        assert info.use_count == 4 and info.last_used > 0 and info.state == B.LORA_SLOT_READY
+    finally:
+        pi.close()

@@ -1,0 +1,185 @@
+"""CPU-only checks of the C ABI: the library loads and exports what the header declares, the
+indexer equals the oracle's indexer bit for bit, byte accounting, slot-table state machine,
+argument validation.  No kernel is launched here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from paper_2411_17741_amd import binding as B
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "lora_cache.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(lora_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(B._lib, n), f"{n} declared in lora_cache.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+# ---------------------------------------------------------------------------------------
+def _index_both(T, off, slot, rank, m0):
+    rc, got = B.lora_index(T, off, slot, rank, m0)
+    assert rc == B.LORA_OK
+    want = oracle.index(T, off, slot, rank, m0)
+    for k in ("tok_list", "tiles", "groups", "gs_items", "ge_items"):
+        assert got[k] == [tuple(v) if not isinstance(v, int) else v for v in want[k]], k
+
+
+@pytest.mark.parametrize("name", ["tiny", "decode", "prefill", "small_mixed", "stress", "mixed"])
+@pytest.mark.parametrize("m0", [0, 16])
+def test_indexer_matches_oracle_on_configs(name, m0):
+    inst = wl.CONFIGS[name]()
+    slot = np.where(inst.seg_adapter >= 0, inst.seg_adapter * 3 + 1, -1)
+    _index_both(inst.T, inst.seg_offsets, slot, inst.seg_rank, m0)
+
+
+def test_indexer_matches_oracle_on_random_batches():
+    rng = np.random.default_rng(0)
+    for trial in range(200):
+        n_seg = int(rng.integers(0, 40))
+        lens = rng.choice([0, 1, 1, 1, 2, 5, 15, 16, 17, 63, 64, 65, 130], size=n_seg)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        n_slots = int(rng.integers(1, 12))
+        slot_rank = rng.choice([1, 4, 8, 12, 16, 24, 32, 40, 64, 100, 128], size=n_slots)
+        slot = rng.integers(-1, n_slots, size=n_seg).astype(np.int32)
+        rank = np.where(slot >= 0, slot_rank[np.maximum(slot, 0)], 0).astype(np.int32)
+        m0 = int(rng.choice([0, 1, 8, 16, 64]))
+        _index_both(int(off[-1]), off, slot, rank, m0)
+
+
+def test_indexer_rejects_malformed_batches():
+    ok = dict(T=4, off=[0, 2, 4], slot=[0, 1], rank=[8, 16])
+    assert B.lora_index(ok["T"], ok["off"], ok["slot"], ok["rank"], 16)[0] == B.LORA_OK
+    bad = [
+        (4, [1, 2, 4], [0, 1], [8, 16]),      # does not start at 0
+        (4, [0, 2, 3], [0, 1], [8, 16]),      # does not end at T
+        (4, [0, 3, 2, 4], [0, 1, 0], [8, 16, 8]),  # decreasing
+        (4, [0, 2, 4], [0, 1], [8, 0]),       # rank 0 on an active segment
+        (4, [0, 2, 4], [0, 1], [8, 129]),     # rank above the maximum
+        (4, [0, 2, 4], [0, 0], [8, 16]),      # one slot, two ranks
+    ]
+    for T, off, slot, rank in bad:
+        assert B.lora_index(T, off, slot, rank, 16)[0] == B.LORA_E_INVAL
+    # empty batch and batch without adapters are fine
+    rc, w = B.lora_index(0, [0], [], [], 16)
+    assert rc == B.LORA_OK and w["tok_list"] == []
+    rc, w = B.lora_index(3, [0, 3], [-1], [0], 16)
+    assert rc == B.LORA_OK and w["tok_list"] == [] and w["tiles"] == [] and w["groups"] == []
+
+
+# ---------------------------------------------------------------------------------------
+def test_adapter_bytes_match_the_papers_footprint():
+    """Section 3.2: a rank-32 adapter of Llama-7B (q,k,v,o x 32 layers, 16 bit) takes 64 MB;
+    the Llama-70B one (k,v are 8192->1024) about 256 MB."""
+    per_proj = B.lora_adapter_bytes(4096, 4096, 32, B.LORA_BF16)
+    assert per_proj * 4 * 32 == 64 * 1024 * 1024
+    b70 = (2 * B.lora_adapter_bytes(8192, 8192, 32, B.LORA_BF16) + 2 * B.lora_adapter_bytes(8192, 1024, 32, B.LORA_BF16)) * 80
+    assert abs(b70 / 2**20 - 250) < 1
+    assert B.lora_adapter_bytes(4096, 4096, 0, B.LORA_BF16) == 0
+    assert B.lora_adapter_bytes(4096, 4096, 8, 7) == 0
+
+
+def test_pool_bytes_account_for_every_slab():
+    proj = [(4096, 4096)] * 4
+    cfg = B.make_config(proj, 32, [8, 16, 32, 64, 128], [0, 0, 1, 0, 0], B.LORA_BF16, 64, 64)
+    cfg0 = B.make_config(proj, 32, [8, 16, 32, 64, 128], [0, 0, 2, 0, 0], B.LORA_BF16, 64, 64)
+    one, two = B.lora_cache_bytes_required(cfg), B.lora_cache_bytes_required(cfg0)
+    # adding one rank-32 slot to a 7B-shaped q,k,v,o pool of 32 layers adds exactly the 64 MiB of section 3.2
+    # (plus 8 bytes per projection in the offset table, rounded to the 256-byte granule)
+    assert 0 <= (two - one) - 64 * 1024 * 1024 <= 256
+    assert B.lora_cache_bytes_required(B.make_config(proj, 0, [8], [1], B.LORA_BF16, 64, 64)) == 0
+    assert B.lora_cache_bytes_required(B.make_config([(100, 64)], 1, [8], [1], B.LORA_BF16, 64, 64)) == 0  # h_in % 64
+    assert B.lora_cache_bytes_required(B.make_config(proj, 1, [16, 8], [1, 1], B.LORA_BF16, 64, 64)) == 0  # not increasing
+    assert B.lora_cache_bytes_required(B.make_config(proj, 1, [256], [1], B.LORA_BF16, 64, 64)) == 0  # above LORA_MAX_RANK
+
+
+def _host_cache(n_layers=2, n_proj=2, class_slots=(2, 1)):
+    cfg = B.make_config([(64, 128)] * n_proj, n_layers, [8, 32], list(class_slots), B.LORA_BF16, 64, 16, flags=B.LORA_CACHE_HOST_ONLY)
+    rc, h = B.lora_cache_create(cfg, 0, 0)
+    assert rc == B.LORA_OK
+    return h
+
+
+def test_slot_table_state_machine():
+    """Cache-entry life cycle of section 4.2: load a missing adapter, look it up, count
+    references, never evict or overwrite an entry that running requests use."""
+    h = _host_cache()
+    st = lambda s: B.lora_cache_slot_info(h, s)[1]
+    assert st(0).state == B.LORA_SLOT_EMPTY
+    assert B.lora_cache_lookup(h, 77)[0] == B.LORA_E_NOTFOUND
+    # rank must fit the class of the slot (slots 0,1: class 8; slot 2: class 32)
+    assert B.lora_cache_fill_slot(h, 0, 77, 16, 1.0, 0, 0, 0, 0) == B.LORA_E_INVAL
+    assert B.lora_cache_find_free_slot(h, 16) == (B.LORA_OK, 2)
+    assert B.lora_cache_find_free_slot(h, 4) == (B.LORA_OK, 0)
+    assert B.lora_cache_find_free_slot(h, 33)[0] == B.LORA_E_NOMEM
+    # four parts (2 layers x 2 projections): FILLING until the last one
+    for i, (l, p) in enumerate([(0, 0), (0, 1), (1, 0), (1, 1)]):
+        assert B.lora_cache_fill_slot(h, 2, 77, 16, 0.5, l, p, 0, 0) == B.LORA_OK
+        info = st(2)
+        assert info.parts_filled == i + 1
+        assert info.state == (B.LORA_SLOT_READY if i == 3 else B.LORA_SLOT_FILLING)
+    info = st(2)
+    assert (info.adapter_id, info.rank, info.class_rank, info.alpha) == (77, 16, 32, 0.5)
+    assert B.lora_cache_lookup(h, 77) == (B.LORA_OK, 2, 16)
+    # the same adapter cannot be cached twice; a bound slot cannot take another adapter
+    assert B.lora_cache_fill_slot(h, 0, 77, 8, 0.5, 0, 0, 0, 0) == B.LORA_E_STATE
+    assert B.lora_cache_fill_slot(h, 2, 78, 16, 0.5, 0, 0, 0, 0) == B.LORA_E_STATE
+    # reference counting: referenced entries can be neither evicted nor overwritten
+    assert B.lora_cache_slot_ref(h, 2, +1) == B.LORA_OK
+    assert B.lora_cache_release_slot(h, 2) == B.LORA_E_STATE
+    assert B.lora_cache_fill_slot(h, 2, 77, 16, 0.5, 0, 0, 0, 0) == B.LORA_E_STATE
+    assert B.lora_cache_slot_ref(h, 2, -1) == B.LORA_OK
+    assert B.lora_cache_slot_ref(h, 2, -1) == B.LORA_E_STATE
+    assert B.lora_cache_slot_ref(h, 0, +1) == B.LORA_E_STATE  # empty slot
+    assert B.lora_cache_fill_slot(h, 2, 77, 16, 0.5, 0, 0, 0, 0) == B.LORA_OK  # unreferenced refill is allowed
+    # eviction discards (no write-back), the id is forgotten, the slot can be rebound
+    assert B.lora_cache_release_slot(h, 2) == B.LORA_OK
+    assert st(2).state == B.LORA_SLOT_EMPTY
+    assert B.lora_cache_lookup(h, 77)[0] == B.LORA_E_NOTFOUND
+    assert B.lora_cache_fill_slot(h, 2, 78, 32, 1.0, 0, 0, 0, 0) == B.LORA_OK
+    rc, stats = B.lora_cache_stats(h)
+    assert (stats.hits, stats.misses, stats.evictions, stats.fills) == (1, 2, 1, 6)
+    # out-of-range arguments
+    assert B.lora_cache_fill_slot(h, 3, 1, 8, 1.0, 0, 0, 0, 0) == B.LORA_E_INVAL
+    assert B.lora_cache_fill_slot(h, 0, 1, 8, 1.0, 2, 0, 0, 0) == B.LORA_E_INVAL
+    assert B.lora_cache_fill_slot(h, 0, 1, 8, 1.0, 0, 2, 0, 0) == B.LORA_E_INVAL
+    assert B.lora_cache_release_slot(h, -1) == B.LORA_E_INVAL
+    assert B.lora_cache_slot_info(h, 9)[0] == B.LORA_E_INVAL
+    # no device work on a host-only cache
+    assert B.lora_apply(h, 0, 0, 0, 0, 0, [0], [], [], 1.0) == B.LORA_E_INVAL
+    assert B.lora_cache_destroy(h) == B.LORA_OK
+
+
+def test_plan_validation_against_slot_table():
+    h = _host_cache(n_layers=1, n_proj=1)
+    assert B.lora_cache_fill_slot(h, 0, 5, 8, 1.0, 0, 0, 0, 0) == B.LORA_OK
+    mk = lambda T, off, slot, rank: B.lora_plan_create(h, T, off, slot, rank)[0]
+    assert mk(3, [0, 3], [0], [8]) == B.LORA_OK
+    assert mk(3, [0, 3], [0], [4]) == B.LORA_E_INVAL    # rank differs from the cached adapter's
+    assert mk(3, [0, 3], [1], [8]) == B.LORA_E_STATE    # empty slot
+    assert mk(3, [0, 3], [3], [8]) == B.LORA_E_INVAL    # no such slot
+    assert mk(65, [0, 65], [0], [8]) == B.LORA_E_INVAL  # more tokens than max_tokens
+    assert mk(3, [0, 2], [0], [8]) == B.LORA_E_INVAL
+    assert mk(3, [0, 3], [0], [8]) == B.LORA_OK
+    assert mk(3, [0, 3], [0], [8]) == B.LORA_E_NOMEM    # both user plans taken
+    assert B.lora_cache_destroy(h) == B.LORA_OK
+
+
+def test_create_rejects_bad_arguments():
+    cfg = B.make_config([(64, 64)], 1, [8], [1], B.LORA_BF16, 16, 4)
+    assert B.lora_cache_create(cfg, 0, 0)[0] == B.LORA_E_INVAL         # device pool required
+    assert B.lora_cache_create(cfg, 0x1001, 1 << 30)[0] == B.LORA_E_INVAL  # misaligned
+    assert B.lora_cache_create(cfg, 0x1000, 16)[0] == B.LORA_E_NOMEM   # too small
+    assert B.lora_strerror(B.LORA_E_STATE) != B.lora_strerror(B.LORA_E_INVAL)
