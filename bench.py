@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched heterogeneous-rank LoRA apply on one MI355X.
+
+A step = one pass of the whole hot path over one batch, the way a serving iteration runs
+it: index the batch once (host), upload its work lists, then run shrink + expand for every
+projection of every layer copy the pool holds, reading the adapters from the cache pool.
+The layer copies are distinct memory and the activations rotate over several buffer sets, so
+that slabs and activations come from HBM and not from the 256 MB Infinity Cache.  Inputs are
+resident in HBM before the timed region starts.  value = tokens x layers / time: the rate at
+which tokens pass one layer's LoRA apply.
+
+Prints ONE JSON line: tokens/s per layer, the roofline figure of the dominant kernel (HIP
+events around each kernel, in a second pass of the same steps) and the CPU oracle's rate on a
+bounded sample of the same workload.
+
+    python bench.py [--workload decode|prefill|mixed|stress] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+WORKLOAD_TEXT = {
+    "decode": "decode: 64 one-token requests, one 4096->4096 bf16 projection, pool of 100 adapters (ranks 8..128), Zipf(1.0)",
+    "prefill": "prefill: 8 prompts lognormal(6,0.8) in [32,2048], one 4096->4096 bf16 projection, distinct adapters of rank 16/64/128",
+    "mixed": "mixed: 224 decode + 32 prompts, 7B-shaped layer (q,k,v,o,gate,up,down) bf16, pool of 500, Zipf(1.2)",
+    "stress": "stress: 512 decode + 4x512 prompt tokens, 13B-shaped layer bf16, pool of 1000 in 4 layer copies, Zipf(1.2)",
+}
+DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4}
+DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20}
+
+
+def algorithmic_bytes(inst, w, esize=2):
+    """Bytes each kernel kind must move per launch, per projection: every distinct slab it
+    needs once at its true rank, its tokens' x rows once, its tokens' base_out rows read and
+    written once.  The T x rank intermediate is not counted."""
+    tok_n = lambda items: sum(it[1] for it in items)
+    slabs = lambda items: {it[2]: it[3] for it in items}
+    out = []
+    for pr in inst.projs:
+        g, t = slabs(w["groups"]), slabs(w["tiles"])
+        ng, nt = tok_n(w["groups"]), tok_n(w["tiles"])
+        out.append({
+            "gemv_shrink": esize * (sum(g.values()) * pr.h_in + ng * pr.h_in),
+            "gemv_expand": esize * (sum(g.values()) * pr.h_out + 2 * ng * pr.h_out),
+            "mfma_shrink": esize * (sum(t.values()) * pr.h_in + nt * pr.h_in),
+            "mfma_expand": esize * (sum(t.values()) * pr.h_out + 2 * nt * pr.h_out),
+            "zero": 0,
+        })
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="decode", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--layers", type=int, default=0, help="layer copies of the pool to rotate over")
+    ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1\n")
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
+        return 2
+    import workloads as wl
+    from paper_2411_17741_amd import binding as B
+    from paper_2411_17741_amd import harness as H
+
+    steps = args.steps or DEFAULT_STEPS[args.workload]
+    n_layers = args.layers or DEFAULT_LAYERS[args.workload]
+    inst = wl.CONFIGS[args.workload](seed=0)
+    t_setup = time.time()
+    pi = H.PooledInstance(inst, n_layers=n_layers)
+    h = pi.pool.handle
+    dev = torch.device("cuda:0")
+
+    # activation sets: enough of them that one rotation exceeds the Infinity Cache
+    x_keys = sorted({p.x_key: p.h_in for p in inst.projs}.items())
+    set_bytes = 2 * inst.T * (sum(w for _, w in x_keys) + sum(p.h_out for p in inst.projs))
+    n_sets = args.sets or int(min(16, max(2, -(-768 * 2**20 // max(1, set_bytes)))))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    xs, ys = [], []
+    for _ in range(n_sets):
+        xs.append({k: (torch.randn((inst.T, w), generator=gen, device=dev) * inst.sigma_x).to(torch.bfloat16) for k, w in x_keys})
+        ys.append([(torch.randn((inst.T, p.h_out), generator=gen, device=dev) * inst.sigma_base).to(torch.bfloat16) for p in inst.projs])
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    B.check(B.lora_cache_set_fencing(h, 1))
+    n_proj = len(inst.projs)
+
+    descs = B.make_descs([(l, p, xs[l % n_sets][inst.projs[p].x_key].data_ptr(), ys[l % n_sets][p].data_ptr())
+                          for l in range(n_layers) for p in range(n_proj)])
+
+    def step(s: int) -> None:
+        rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
+        B.check(rc, "lora_plan_create")
+        B.check(B.lora_apply_plan_multi(h, plan, descs, inst.scale, sh), "lora_apply_plan_multi")
+        B.check(B.lora_plan_destroy(h, plan))
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(args.warmup + s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / steps
+    ms_per_layer = ms_per_step / n_layers
+    tokens_per_s = inst.T / (ms_per_layer * 1e-3)
+
+    rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS)
+    B.check(rc)
+    per_proj = algorithmic_bytes(inst, w)
+    step_bytes = sum(sum(v.values()) for v in per_proj)
+    step_flops = sum(2 * it[1] * it[3] * (p.h_in + p.h_out) for p in inst.projs for it in (w["tiles"] + w["groups"]))
+
+    roofline = None
+    kernels = {}
+    if not args.no_kernel_timing:
+        # second pass over the same steps with an event pair around every kernel
+        B.check(B.lora_cache_set_timing(h, 1))
+        n_steps_timed = max(1, min(steps, 200 // n_layers))
+        n_timed = n_steps_timed * n_layers  # layer passes
+        for s in range(n_steps_timed):
+            step(args.warmup + s)
+        torch.cuda.synchronize()
+        rc, tm = B.lora_cache_read_timing(h)
+        B.check(rc)
+        B.check(B.lora_cache_set_timing(h, 0))
+        for kind, (ms, n) in tm.items():
+            if n:
+                kbytes = sum(v[kind] for v in per_proj) * n_timed  # all projections, all timed layer passes
+                kernels[kind] = {"launches": int(n), "avg_us": ms * 1e3 / n, "algorithmic_bytes_per_launch": kbytes / n,
+                                 "achieved_GBs": kbytes / (ms * 1e-3) / 1e9 if ms > 0 else None}
+        dom = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
+        roofline = {
+            "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+            "avg_launch_us": kernels[dom]["avg_us"], "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
+        }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        # bounded sample: evenly spaced tokens of the batch, each as its own one-token segment
+        n_samp = min(inst.T, 64 if args.workload == "decode" else 256)
+        rows = np.unique(np.linspace(0, inst.T - 1, n_samp).astype(np.int64))
+        ta = inst.token_adapter()[rows]
+        off = np.arange(len(rows) + 1, dtype=np.int32)
+        data = []
+        for p in range(n_proj):
+            ads = {int(a): (*inst.adapter_weights(int(a), p), float(inst.alpha[a])) for a in np.unique(ta[ta >= 0])}
+            data.append((inst.x(p, rows).astype(np.float64), inst.base_out(p, rows).astype(np.float64), ads))
+        reps, t_cpu = 0, 0.0
+        while reps < 20 and t_cpu < 2.0:
+            t1 = time.perf_counter()
+            for x_, b_, ads in data:
+                oracle.lora_apply(x_, b_, off, ta, ads, inst.scale)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        cpu = {"value": len(rows) * reps / t_cpu, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{len(rows)} evenly spaced tokens of the batch, all {n_proj} projection(s), {reps} repetition(s), fp64"}
+
+    out = {
+        "metric": "lora_apply_tokens_per_s_per_layer", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
+                   "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
+                   "ms_per_layer": ms_per_layer,
+                   "tiles": len(w["tiles"]), "gemv_groups": len(w["groups"])},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "layer": {"algorithmic_bytes": step_bytes, "flops": step_flops, "achieved_GBs": step_bytes / (ms_per_layer * 1e-3) / 1e9,
+                  "hbm_frac": step_bytes / (ms_per_layer * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "achieved_TFLOPs": step_flops / (ms_per_layer * 1e-3) / 1e12, "setup_s": t_setup},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    pi.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -59,6 +59,7 @@ enum { LORA_CACHE_HOST_ONLY = 1 };                                  /* flags: sl
 #define LORA_MAX_RANK 128
 #define LORA_TILE_TOKENS 64      /* tokens per matrix-core tile */
 #define LORA_MFMA_MIN_TOKENS 16  /* default: segments / pooled slots with fewer tokens take the GEMV path */
+#define LORA_GEMV_BATCH 4        /* tokens one GEMV work item handles */
 
 typedef struct lora_cache lora_cache_t; /* opaque */
 typedef struct lora_plan lora_plan_t;   /* opaque: device-resident work lists of one batch */
@@ -152,9 +153,9 @@ int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t 
 
 /* One unit of work.  tok_off/n_tok name tokens in tok_list; a, b depend on the list:
  * tiles: a = running tile number inside its segment or pool;  groups: unused;
- * gs_items (GEMV shrink): a = first rank row, b = rows (<= 4);
- * ge_items (GEMV expand): a = column offset inside a 1024-column super-chunk, b = columns.
- * c holds the bit pattern of the slot's alpha (float) in device copies, 0 in lora_index output. */
+ * gs_items (GEMV shrink): n_tok <= LORA_GEMV_BATCH, a = first rank row, b = rows (<= 4);
+ * ge_items (GEMV expand): n_tok <= LORA_GEMV_BATCH, a = column offset inside a 1024-column
+ * super-chunk, b = columns.  c, d are 0. */
 typedef struct {
     int32_t tok_off, n_tok, slot, rank, a, b, c, d;
 } lora_item_t;
@@ -176,8 +177,9 @@ typedef struct {
  *    such segments are pooled per slot (slots ascending, tokens ascending); a pool of at
  *    least mfma_min_tokens tokens is cut into tiles too, any other is one group.
  *    mfma_min_tokens = 0 turns tiles off (everything is pooled into groups).
- *  - gs_items: per group one item per 4 rank rows.  ge_items: per group, with
- *    rs = rank rounded up to 8 and Nc = 64 * max(1, 128 / rs), items (0,Nc), (Nc,Nc), ... < 1024.
+ *  - A group is worked on in token batches: runs of up to LORA_GEMV_BATCH consecutive entries of
+ *    its part of tok_list.  gs_items: per batch one item per 4 rank rows.  ge_items: per batch,
+ *    with rs = rank rounded up to 8 and Nc = 64 * max(1, 128 / rs), items (0,Nc), (Nc,Nc), ... < 1024.
  * All segments that name one slot must carry the same rank (else LORA_E_INVAL).
  * Arrays in *out are malloc'ed; free them with lora_worklists_free. */
 int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot, const int32_t *seg_rank,
@@ -200,6 +202,17 @@ int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p);
 int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
                     void *base_out, float scale, void *stream);
 
+/* The same for a list of (layer, projection, x, base_out): descs[0..n) are applied in order
+ * on `stream`, as n calls of lora_apply_plan would (one iteration's worth of applies with a
+ * single trip through the binding).  Nothing is enqueued if any entry fails validation. */
+typedef struct {
+    int32_t layer, proj;
+    const void *x;  /* device [T][h_in] */
+    void *base_out; /* device [T][h_out], in/out */
+} lora_apply_desc_t;
+int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int32_t n, float scale,
+                          void *stream);
+
 /* One-call form: index + apply (uses one of 4 internal plans in rotation; blocks the
  * host only if the plan used 4 calls ago is still in flight). */
 int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void *base_out, int32_t T,
@@ -210,6 +223,15 @@ int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void
  * applies: the caller then keeps refills away from slots in use (reference counts).
  * Default on (1).  Turn off while capturing applies into a HIP graph. */
 int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
+
+/* Per-kernel timing for benchmarks.  While on (1), every kernel an apply launches is
+ * bracketed by a pair of HIP events on the apply's stream (this serialises the kernels and
+ * costs a few microseconds each, so time whole steps with timing off).
+ * lora_cache_read_timing waits for the recorded events, adds up the elapsed milliseconds and
+ * launch counts per kernel kind since the last read, and forgets them. */
+enum { LORA_K_ZERO = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4, LORA_K_COUNT = 5 };
+int lora_cache_set_timing(lora_cache_t *c, int32_t on);
+int lora_cache_read_timing(lora_cache_t *c, double ms[LORA_K_COUNT], int64_t launches[LORA_K_COUNT]);
 
 const char *lora_strerror(int status);
 int lora_last_hip_error(void);

@@ -24,10 +24,12 @@ Canonical work lists (the library's contract for `lora_index`):
 * `tok_list` = tokens of all tiles (long-segment tiles first, then gathered
   tiles), then tokens of all groups.  A tile or group names its tokens as
   (`tok_off`, `n_tok`) into `tok_list`.
-* Shrink items of a group: one per block of 4 rank rows, (j0, n_rows).
-* Expand items of a group: with rs = rank rounded up to a multiple of 8 and
-  Nc = 64 * max(1, 128 // rs) columns per item, one item per Nc columns of a
-  1024-column super-chunk: (col_off, n_cols) for col_off = 0, Nc, ... < 1024.
+* A group is worked on in *token batches*: runs of up to 4 consecutive entries
+  of its part of `tok_list`.  Shrink items: per batch, one per block of 4 rank
+  rows, (j0, n_rows).  Expand items: per batch, with rs = rank rounded up to a
+  multiple of 8 and Nc = 64 * max(1, 128 // rs) columns per item, one item per
+  Nc columns of a 1024-column super-chunk: (col_off, n_cols) for col_off = 0,
+  Nc, ... < 1024.  Items name their batch as (`tok_off`, `n_tok` <= 4).
 """
 from __future__ import annotations
 
@@ -99,16 +101,20 @@ def index(
     gs_items: List[Item] = []
     ge_items: List[Item] = []
     for (off, n, slot, rank, _, _) in groups:
-        j0 = 0
-        while j0 < rank:
-            gs_items.append((off, n, slot, rank, j0, min(4, rank - j0)))
-            j0 += 4
+        for b0 in range(0, n, 4):
+            bn = min(4, n - b0)
+            j0 = 0
+            while j0 < rank:
+                gs_items.append((off + b0, bn, slot, rank, j0, min(4, rank - j0)))
+                j0 += 4
         rs = (rank + 7) // 8 * 8
         nc = 64 * max(1, 128 // rs)
-        c = 0
-        while c < 1024:
-            ge_items.append((off, n, slot, rank, c, nc))
-            c += nc
+        for b0 in range(0, n, 4):
+            bn = min(4, n - b0)
+            c = 0
+            while c < 1024:
+                ge_items.append((off + b0, bn, slot, rank, c, nc))
+                c += nc
     return {
         "tok_list": tok_list,
         "tiles": tiles,

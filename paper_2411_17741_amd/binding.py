@@ -59,6 +59,10 @@ class lora_item_t(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in ("tok_off", "n_tok", "slot", "rank", "a", "b", "c", "d")]
 
 
+class lora_apply_desc_t(ctypes.Structure):
+    _fields_ = [("layer", c_int32), ("proj", c_int32), ("x", c_void_p), ("base_out", c_void_p)]
+
+
 class lora_worklists_t(ctypes.Structure):
     _fields_ = [
         ("n_tok_list", c_int32), ("n_tiles", c_int32), ("n_groups", c_int32), ("n_gs_items", c_int32), ("n_ge_items", c_int32),
@@ -93,8 +97,11 @@ _SIGS = {
     "lora_plan_create": (c_int, [c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_void_p, POINTER(c_void_p)]),
     "lora_plan_destroy": (c_int, [c_void_p, c_void_p]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
+    "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
     "lora_apply": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_float, c_void_p]),
     "lora_cache_set_fencing": (c_int, [c_void_p, c_int32]),
+    "lora_cache_set_timing": (c_int, [c_void_p, c_int32]),
+    "lora_cache_read_timing": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "lora_strerror": (c_char_p, [c_int]),
     "lora_last_hip_error": (c_int, []),
 }
@@ -244,11 +251,38 @@ def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, s
                                 c_void_p(stream or None))
 
 
+def make_descs(entries):
+    """[(layer, proj, x device address, base_out device address), ...] -> C array for lora_apply_plan_multi."""
+    arr = (lora_apply_desc_t * len(entries))()
+    for i, (layer, proj, x, y) in enumerate(entries):
+        arr[i] = lora_apply_desc_t(int(layer), int(proj), c_void_p(x or None), c_void_p(y or None))
+    return arr
+
+
+def lora_apply_plan_multi(cache, plan, descs, scale: float, stream: int = 0) -> int:
+    return _lib.lora_apply_plan_multi(cache, plan, descs, len(descs), scale, c_void_p(stream or None))
+
+
 def lora_apply(cache, layer: int, proj: int, x: int, base_out: int, T: int, seg_offsets, seg_slot, seg_rank,
                scale: float, stream: int = 0) -> int:
     so, ss, sr = _i32(seg_offsets), _i32(seg_slot), _i32(seg_rank)
     return _lib.lora_apply(cache, layer, proj, c_void_p(x or None), c_void_p(base_out or None), T, _ptr(so), _ptr(ss),
                            _ptr(sr), len(ss), scale, c_void_p(stream or None))
+
+
+KERNEL_KINDS = ("zero", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand")
+
+
+def lora_cache_set_timing(cache, on: int) -> int:
+    return _lib.lora_cache_set_timing(cache, on)
+
+
+def lora_cache_read_timing(cache):
+    """-> (status, {kind: (milliseconds, launches)})"""
+    ms = (ctypes.c_double * len(KERNEL_KINDS))()
+    n = (c_int64 * len(KERNEL_KINDS))()
+    rc = _lib.lora_cache_read_timing(cache, ms, n)
+    return rc, {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_KINDS)}
 
 
 def lora_cache_set_fencing(cache, on: int) -> int:

@@ -1,158 +1,284 @@
 // GEMV path of the batched LoRA apply for gfx950: tokens whose slot has only a few tokens in
 // the batch (decode requests, short prompts).  Both kernels are bandwidth-bound streams of
-// the slot's slab; every slab byte is read once per group of tokens that share the slot.
+// the slot's slab.  A work item is a batch of up to 4 tokens of one slot; every load an item
+// needs -- slab, activations, intermediate -- is issued before the first one is used, so an
+// item costs one trip to memory, and the batches of a popular slot run side by side (its slab
+// then comes out of L2 for all but the first).
 //
-//   shrink:  v[t][j] = sum_k x[t][k] * A[k][j]        one wavefront per rank row j of At
-//   expand:  y[t][n] += s * sum_j v[t][j] * B[j][n]   one lane per output column n of Bp
+//   shrink:  v[t][j] = sum_k x[t][k] * A[k][j]        wavefronts own (parts of) rank rows of At
+//   expand:  y[t][n] += s * sum_j v[t][j] * B[j][n]   lanes own output columns of Bp
 //
 // (paper section 3.1: the two adapter products and the aggregation into the base output.)
 #include "lora_device.h"
 
 namespace lora {
 
+constexpr int TB = LORA_GEMV_BATCH;
+
 // ---------------------------------------------------------------------------------------
-// shrink.  Block = 4 wavefronts = up to 4 consecutive rank rows of one group.  A wavefront
-// keeps U chunks (8 elements each) of its row per lane in registers, i.e. a K block of
-// U*512 elements, while the block stages the same K block of up to TB token rows of x in
-// LDS; every wavefront then forms its dot products against the staged rows and the partial
-// sums are reduced across the 64 lanes at the end.
+// shrink.  Block = 4 wavefronts working on R rank rows, W = 4/R wavefronts per row, each
+// covering every W-th run of 64 chunks (8 elements each) of the row: 8 chunk loads per lane
+// per pass.  x chunks of the item's tokens are read at the same offsets, straight from global
+// memory (the wavefronts of a block read the same lines at the same time).  Partial sums are
+// reduced over the 64 lanes and, for W > 1, over the W wavefronts through LDS.  A work item
+// names 4 rows, so an item takes W blocks.
 // ---------------------------------------------------------------------------------------
-template <typename E, int U>
-__global__ __launch_bounds__(256) void gemv_shrink_kernel(ApplyArgs a, const lora_item_t *__restrict__ items)
+template <typename E, int R>
+__global__ __launch_bounds__(256) void gemv_shrink_kernel(ApplyArgs a, const GemvItem *__restrict__ items)
 {
-    constexpr int KB = U * 512;
-    constexpr int TB = 4;
-    __shared__ __attribute__((aligned(16))) E xs[TB * KB];
+    constexpr int W = 4 / R;
+    constexpr int U = 8;
+    __shared__ float red[4][TB];
 
-    const lora_item_t it = items[blockIdx.x];
+    const GemvItem it = items[blockIdx.x / W];
+    const int part = blockIdx.x % W;
+    if (part * R >= it.n_rows) return;  // whole block has no row (uniform)
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const E *At = reinterpret_cast<const E *>(a.layer_base + a.slot_off[it.slot]);
-    const bool row_ok = w < it.b;
-    const int j = it.a + w;
-    const E *arow = At + (size_t)j * a.h_in;
+    const int rr = part * R + w / W, kp = w % W;  // row inside the item, k part of this wavefront
+    const bool row_ok = rr < it.n_rows;
+    const int j = it.a + rr;
+    const E *arow = reinterpret_cast<const E *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)j * a.h_in;
     const E *x = static_cast<const E *>(a.x);
+    const int n_chunks = a.h_in >> 3;
 
-    for (int t0 = 0; t0 < it.n_tok; t0 += TB) {
-        const int nb = min(TB, it.n_tok - t0);
+    float acc[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) acc[t] = 0.f;
+
+    // Loads are unconditional (addresses clamped to something valid, results masked), so that
+    // the compiler can issue all of them back to back and wait once.
+    constexpr int TS = sizeof(E) == 2 ? TB : 2;  // tokens whose x chunks are in registers at once
+    const E *arow_safe = row_ok ? arow : arow - (size_t)rr * a.h_in;  // the item's first row always exists
+    for (int c0 = 0; c0 < n_chunks; c0 += W * 64 * U) {
+        Chunk<E> av[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + (u * W + kp) * 64 + lane;
+            av[u] = load_chunk(arow_safe + (size_t)min(c, n_chunks - 1) * 8);
+        }
+#pragma unroll
+        for (int t0 = 0; t0 < TB; t0 += TS) {
+            Chunk<E> xv[TS][U];
+#pragma unroll
+            for (int t = 0; t < TS; ++t) {
+                const int tok = it.tok[t0 + t] >= 0 ? it.tok[t0 + t] : it.tok[0];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + (u * W + kp) * 64 + lane;
+                    xv[t][u] = load_chunk(x + (size_t)tok * a.h_in + (size_t)min(c, n_chunks - 1) * 8);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < TS; ++t) {
+                if (it.tok[t0 + t] >= 0) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int cb = c0 + (u * W + kp) * 64;  // uniform over the wavefront
+                        if (cb + 64 <= n_chunks) {
+                            acc[t0 + t] = dot_chunk_acc(acc[t0 + t], av[u], xv[t][u]);
+                        } else if (cb < n_chunks) {  // ragged end of the row: clamped lanes do not count
+                            const float d = dot_chunk_acc(0.f, av[u], xv[t][u]);
+                            acc[t0 + t] += cb + lane < n_chunks ? d : 0.f;
+                        }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+        if (it.tok[t] >= 0) acc[t] = wave_sum(acc[t]);
+    if (W > 1) {
+        if (lane == 0) {
+#pragma unroll
+            for (int t = 0; t < TB; ++t) red[w][t] = acc[t];
+        }
+        __syncthreads();
+        if (kp == 0) {
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                float s = 0.f;
+#pragma unroll
+                for (int q = 0; q < W; ++q) s += red[w + q][t];
+                acc[t] = s;
+            }
+        }
+    }
+    if (lane == 0 && kp == 0 && row_ok) {
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+            if (it.tok[t] >= 0) a.v[(size_t)it.tok[t] * a.v_stride + j] = acc[t];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// expand, ranks whose storage is 8, 16, 32, 64 or 128 rows (RS8 = 1, 2, 4, 8, 16 granules).
+// Block = one wavefront; a lane owns P = 16/RS8 output columns (n = c0 + lane + 64p) and
+// loads all of its 16 chunks of Bp, the scaled v of the item's tokens (one value per lane,
+// broadcast with readlane when used) and the base_out values it will update, all up front.
+// ---------------------------------------------------------------------------------------
+template <typename E, int RS8>
+__device__ __forceinline__ void gemv_expand_body(const ApplyArgs &a, const GemvItem &it, int c0, int c1, const E *Bp)
+{
+    constexpr int P = 16 / RS8;
+    const int lane = threadIdx.x;
+    const float s = a.scale * it.alpha;
+    E *y = static_cast<E *>(a.y);
+
+    // Loads are unconditional (columns and tokens clamped to valid ones, results discarded), so
+    // that all of them are issued back to back; stores come after all the arithmetic.
+    Chunk<E> b[P][RS8];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int n = c0 + lane + 64 * p;
+        const int ns = n < c1 ? n : c0 + lane;
+#pragma unroll
+        for (int j8 = 0; j8 < RS8; ++j8) b[p][j8] = load_chunk(Bp + ((size_t)j8 * a.h_out + ns) * 8);
+    }
+    float vlo[TB], vhi[TB];
+    E yv[TB][P];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        const int tok = it.tok[t] >= 0 ? it.tok[t] : it.tok[0];
+        const float *vr = a.v + (size_t)tok * a.v_stride;  // rows are at least 128 floats long
+        vlo[t] = vr[lane];
+        vhi[t] = RS8 > 8 ? vr[lane + 64] : 0.f;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int n = c0 + lane + 64 * p;
+            yv[t][p] = y[(size_t)tok * a.h_out + (n < c1 ? n : c0 + lane)];
+        }
+    }
+    float acc[TB][P];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        if (lane >= it.rank) vlo[t] = 0.f;  // what lies beyond the rank was never written
+        if (lane + 64 >= it.rank) vhi[t] = 0.f;
+#pragma unroll
+        for (int p = 0; p < P; ++p) acc[t][p] = 0.f;
+    }
+#pragma unroll
+    for (int j8 = 0; j8 < RS8; ++j8) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            float bf[8];
+            unpack_chunk(b[p][j8], bf);
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                if (it.tok[t] >= 0) {  // uniform
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int jj = j8 * 8 + i;
+                        const float vj = __builtin_bit_cast(
+                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, jj < 64 ? vlo[t] : vhi[t]), jj & 63));
+                        acc[t][p] += vj * bf[i];
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        if (it.tok[t] >= 0) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int n = c0 + lane + 64 * p;
+                if (n < c1) y[(size_t)it.tok[t] * a.h_out + n] = from_float<E>(to_float(yv[t][p]) + s * acc[t][p]);
+            }
+        }
+    }
+}
+
+// Any other rank: granule loop, v of the item's tokens staged in LDS.
+template <typename E>
+__device__ __forceinline__ void gemv_expand_generic(const ApplyArgs &a, const GemvItem &it, int c0, int c1, const E *Bp,
+                                                    float (*vs)[LORA_MAX_RANK])
+{
+    const int lane = threadIdx.x;
+    const int rs = rank_storage(it.rank), rs8 = rs >> 3;
+    const float s = a.scale * it.alpha;
+    E *y = static_cast<E *>(a.y);
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        if (it.tok[t] >= 0) {
+            const float *vr = a.v + (size_t)it.tok[t] * a.v_stride;
+            for (int jj = lane; jj < rs; jj += 64) vs[t][jj] = jj < it.rank ? s * vr[jj] : 0.f;
+        }
+    }
+    __syncthreads();
+    for (int n = c0 + lane; n < c1; n += 64) {
         float acc[TB];
 #pragma unroll
         for (int t = 0; t < TB; ++t) acc[t] = 0.f;
-
-        for (int k0 = 0; k0 < a.h_in; k0 += KB) {
-            Chunk<E> av[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int k = k0 + (u * 64 + lane) * 8;
-                if (row_ok && k < a.h_in) av[u] = load_chunk(arow + k);
-                else av[u] = zero_chunk<E>();
-            }
-            __syncthreads();  // everyone is done reading the previous K block
-            for (int t = 0; t < nb; ++t) {
-                const E *xr = x + (size_t)a.tok_list[it.tok_off + t0 + t] * a.h_in;
-                for (int c = threadIdx.x; c < KB / 8; c += 256) {
-                    const int k = k0 + c * 8;
-                    store_chunk(&xs[t * KB + c * 8], k < a.h_in ? load_chunk(xr + k) : zero_chunk<E>());
-                }
-            }
-            __syncthreads();
+#pragma unroll 4
+        for (int j8 = 0; j8 < rs8; ++j8) {
+            float bf[8];
+            unpack_chunk(load_chunk(Bp + ((size_t)j8 * a.h_out + n) * 8), bf);
 #pragma unroll
             for (int t = 0; t < TB; ++t) {
-                if (t < nb) {
+                if (it.tok[t] >= 0) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const Chunk<E> xv = load_chunk(&xs[t * KB + (u * 64 + lane) * 8]);
-                        acc[t] += dot_chunk(av[u], xv);
-                    }
+                    for (int i = 0; i < 8; ++i) acc[t] += vs[t][j8 * 8 + i] * bf[i];
                 }
             }
         }
 #pragma unroll
         for (int t = 0; t < TB; ++t) {
-            if (t < nb) {
-                const float s = wave_sum(acc[t]);
-                if (lane == 0 && row_ok) a.v[(size_t)a.tok_list[it.tok_off + t0 + t] * a.v_stride + j] = s;
+            if (it.tok[t] >= 0) {
+                E *yp = y + (size_t)it.tok[t] * a.h_out + n;
+                *yp = from_float<E>(to_float(*yp) + acc[t]);
             }
         }
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// expand.  Block = one wavefront = a run of output columns of one group.  A lane owns one
-// column per pass; per granule of 8 ranks it reads the 8 B values of its column with one
-// chunk load (the wavefront reads 64 consecutive chunks) and multiplies them with the
-// scaled v of up to TB tokens, broadcast from LDS.
-// ---------------------------------------------------------------------------------------
 template <typename E>
-__global__ __launch_bounds__(64) void gemv_expand_kernel(ApplyArgs a, const lora_item_t *__restrict__ items)
+__global__ __launch_bounds__(64) void gemv_expand_kernel(ApplyArgs a, const GemvItem *__restrict__ items)
 {
-    constexpr int TB = 4;
     __shared__ __attribute__((aligned(16))) float vs[TB][LORA_MAX_RANK];
 
-    const lora_item_t it = items[blockIdx.x];
+    const GemvItem it = items[blockIdx.x];
+    const int rs = rank_storage(it.rank);
+    const int n_cols = 64 * max(1, 128 / rs);
     const int c0 = blockIdx.y * 1024 + it.a;
     if (c0 >= a.h_out) return;
-    const int c1 = min(min(c0 + it.b, (int)(blockIdx.y + 1) * 1024), a.h_out);
-    const int lane = threadIdx.x;
-    const int rs = rank_storage(it.rank), rs8 = rs >> 3;
-    const E *Bp = reinterpret_cast<const E *>(a.layer_base + a.slot_off[it.slot]) + (size_t)rs * a.h_in;
-    const float s = a.scale * __int_as_float(it.c);
-    E *y = static_cast<E *>(a.y);
-
-    for (int t0 = 0; t0 < it.n_tok; t0 += TB) {
-        const int nb = min(TB, it.n_tok - t0);
-        __syncthreads();
-        for (int t = 0; t < nb; ++t) {
-            const float *vr = a.v + (size_t)a.tok_list[it.tok_off + t0 + t] * a.v_stride;
-            for (int jj = lane; jj < rs; jj += 64) vs[t][jj] = jj < it.rank ? s * vr[jj] : 0.f;
-        }
-        __syncthreads();
-        for (int n = c0 + lane; n < c1; n += 64) {
-            float acc[TB];
-#pragma unroll
-            for (int t = 0; t < TB; ++t) acc[t] = 0.f;
-#pragma unroll 4
-            for (int j8 = 0; j8 < rs8; ++j8) {
-                float bf[8];
-                unpack_chunk(load_chunk(Bp + ((size_t)j8 * a.h_out + n) * 8), bf);
-#pragma unroll
-                for (int t = 0; t < TB; ++t) {
-                    if (t < nb) {
-                        const float4 v0 = *reinterpret_cast<const float4 *>(&vs[t][j8 * 8]);
-                        const float4 v1 = *reinterpret_cast<const float4 *>(&vs[t][j8 * 8 + 4]);
-                        acc[t] += v0.x * bf[0] + v0.y * bf[1] + v0.z * bf[2] + v0.w * bf[3] + v1.x * bf[4] +
-                                  v1.y * bf[5] + v1.z * bf[6] + v1.w * bf[7];
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < TB; ++t) {
-                if (t < nb) {
-                    E *yp = y + (size_t)a.tok_list[it.tok_off + t0 + t] * a.h_out + n;
-                    *yp = from_float<E>(to_float(*yp) + acc[t]);
-                }
-            }
-        }
+    const int c1 = min(min(c0 + n_cols, (int)(blockIdx.y + 1) * 1024), a.h_out);
+    const E *Bp = reinterpret_cast<const E *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
+    switch (rs) {  // uniform over the block
+        case 8: gemv_expand_body<E, 1>(a, it, c0, c1, Bp); break;
+        case 16: gemv_expand_body<E, 2>(a, it, c0, c1, Bp); break;
+        case 32: gemv_expand_body<E, 4>(a, it, c0, c1, Bp); break;
+        case 64: gemv_expand_body<E, 8>(a, it, c0, c1, Bp); break;
+        case 128: gemv_expand_body<E, 16>(a, it, c0, c1, Bp); break;
+        default: gemv_expand_generic<E>(a, it, c0, c1, Bp, vs); break;
     }
 }
 
-hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const lora_item_t *items, int n_items, hipStream_t st)
+hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
-    if (dtype == LORA_BF16)
-        hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 8>), dim3(n_items), dim3(256), 0, st, a, items);
-    else
-        hipLaunchKernelGGL((gemv_shrink_kernel<float, 4>), dim3(n_items), dim3(256), 0, st, a, items);
+    // one pass of a wavefront covers 4096 elements of a row; longer rows are split over 2 or 4
+    // wavefronts so that a row still takes one pass
+    const int w = a.h_in <= 4096 ? 1 : (a.h_in <= 8192 ? 2 : 4);
+    const dim3 grid(n_items * w), block(256);
+    if (dtype == LORA_BF16) {
+        if (w == 1) hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 4>), grid, block, 0, st, a, items);
+        else if (w == 2) hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 2>), grid, block, 0, st, a, items);
+        else hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 1>), grid, block, 0, st, a, items);
+    } else {
+        if (w == 1) hipLaunchKernelGGL((gemv_shrink_kernel<float, 4>), grid, block, 0, st, a, items);
+        else if (w == 2) hipLaunchKernelGGL((gemv_shrink_kernel<float, 2>), grid, block, 0, st, a, items);
+        else hipLaunchKernelGGL((gemv_shrink_kernel<float, 1>), grid, block, 0, st, a, items);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const lora_item_t *items, int n_items, hipStream_t st)
+hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
     const dim3 grid(n_items, (a.h_out + 1023) / 1024);
-    if (dtype == LORA_BF16)
-        hipLaunchKernelGGL((gemv_expand_kernel<__bf16>), grid, dim3(64), 0, st, a, items);
-    else
-        hipLaunchKernelGGL((gemv_expand_kernel<float>), grid, dim3(64), 0, st, a, items);
+    if (dtype == LORA_BF16) hipLaunchKernelGGL((gemv_expand_kernel<__bf16>), grid, dim3(64), 0, st, a, items);
+    else hipLaunchKernelGGL((gemv_expand_kernel<float>), grid, dim3(64), 0, st, a, items);
     return hipGetLastError();
 }
 

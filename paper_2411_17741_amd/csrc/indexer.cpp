@@ -95,11 +95,19 @@ extern "C" int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *
     const int32_t n_tile_tok = (int32_t)tile_tok.size();
     for (auto &gr : groups) {
         gr.tok_off += n_tile_tok;
-        for (int32_t j0 = 0; j0 < gr.rank; j0 += 4)
-            gs.push_back(make_item(gr.tok_off, gr.n_tok, gr.slot, gr.rank, j0, std::min(4, gr.rank - j0)));
         const int32_t rs = lora::rank_storage(gr.rank);
         const int32_t nc = 64 * std::max(1, 128 / rs);
-        for (int32_t c = 0; c < 1024; c += nc) ge.push_back(make_item(gr.tok_off, gr.n_tok, gr.slot, gr.rank, c, nc));
+        // token batches of up to LORA_GEMV_BATCH tokens: every batch gets its own items so that
+        // batches run side by side instead of one after the other
+        for (int32_t b0 = 0; b0 < gr.n_tok; b0 += LORA_GEMV_BATCH) {
+            const int32_t bn = std::min<int32_t>(LORA_GEMV_BATCH, gr.n_tok - b0);
+            for (int32_t j0 = 0; j0 < gr.rank; j0 += 4)
+                gs.push_back(make_item(gr.tok_off + b0, bn, gr.slot, gr.rank, j0, std::min(4, gr.rank - j0)));
+        }
+        for (int32_t b0 = 0; b0 < gr.n_tok; b0 += LORA_GEMV_BATCH) {
+            const int32_t bn = std::min<int32_t>(LORA_GEMV_BATCH, gr.n_tok - b0);
+            for (int32_t c = 0; c < 1024; c += nc) ge.push_back(make_item(gr.tok_off + b0, bn, gr.slot, gr.rank, c, nc));
+        }
     }
     tile_tok.insert(tile_tok.end(), group_tok.begin(), group_tok.end());
 

@@ -62,6 +62,7 @@ struct lora_plan {
     bool upload_pending = false, use_pending = false;
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
+    unsigned tile_classes = 0;  // which rank classes the tiles fall in (see launch_mfma_shrink)
     size_t off_tiles = 0, off_gs = 0, off_ge = 0;
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
@@ -78,9 +79,11 @@ struct lora_cache {
     char *pool = nullptr;
     size_t pool_bytes = 0;
     size_t layer_stride = 0;
-    std::vector<int64_t> slot_off;  // [n_proj][n_slots], relative to the layer base
-    std::vector<size_t> slab_bytes;  // [n_proj][n_classes]
-    size_t off_table = 0, off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
+    std::vector<int32_t> slot_row;  // [n_slots] first storage row of the slot (same in every projection)
+    std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
+    std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
+    int64_t total_rows = 0;
+    size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
 
     std::vector<Slot> slots;
     std::unordered_map<int64_t, int32_t> id2slot;
@@ -95,6 +98,15 @@ struct lora_cache {
     int64_t apply_ev_seq[N_APPLY_EVENTS] = {};
 
     lora_cache_stats_t stats = {};
+
+    // benchmark aid: event pairs around kernels
+    bool timing = false;
+    struct Timed {
+        int kind;
+        hipEvent_t start, stop;
+    };
+    std::vector<Timed> timed;
+    std::vector<hipEvent_t> free_events;
 };
 
 namespace {
@@ -115,7 +127,7 @@ bool config_ok(const lora_cache_config_t *cfg)
         if (c && cfg->class_rank[c] <= cfg->class_rank[c - 1]) return false;
         total_slots += cfg->class_slots[c];
     }
-    return total_slots >= 1 && total_slots < (1 << 24);
+    return total_slots >= 1 && total_slots * (int64_t)LORA_MAX_RANK < (int64_t)1 << 31;
 }
 
 // Fills every layout field of `c` from the config; used by bytes_required and create alike.
@@ -141,32 +153,34 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
         c.class_first[k] = c.n_slots;
         c.n_slots += c.class_slots[k];
     }
-    c.slab_bytes.assign((size_t)n_proj * n_cls, 0);
-    c.slot_off.assign((size_t)n_proj * c.n_slots, 0);
+    c.slot_row.assign(c.n_slots, 0);
+    c.total_rows = 0;
+    for (int k = 0; k < n_cls; ++k)
+        for (int s = 0; s < c.class_slots[k]; ++s) {
+            c.slot_row[c.class_first[k] + s] = (int32_t)c.total_rows;
+            c.total_rows += lora::rank_storage(c.class_rank[k]);
+        }
+    c.proj_off.assign(n_proj, 0);
+    c.row_bytes.assign(n_proj, 0);
     size_t off = 0, max_part = 0;
     for (int p = 0; p < n_proj; ++p) {
         const size_t width = (size_t)c.proj[p].h_in + (size_t)c.proj[p].h_out;
-        for (int k = 0; k < n_cls; ++k) {
-            const size_t sb = align_up((size_t)lora::rank_storage(c.class_rank[k]) * width * c.esize);
-            c.slab_bytes[(size_t)p * n_cls + k] = sb;
-            for (int s = 0; s < c.class_slots[k]; ++s) {
-                c.slot_off[(size_t)p * c.n_slots + c.class_first[k] + s] = (int64_t)off;
-                off += sb;
-            }
-        }
+        c.proj_off[p] = off;
+        c.row_bytes[p] = width * c.esize;  // a multiple of 256 bytes: h_in, h_out are multiples of 64
+        off += (size_t)c.total_rows * c.row_bytes[p];
         max_part = std::max(max_part, (size_t)c.class_rank[n_cls - 1] * width * c.esize);
     }
     c.layer_stride = off;
     c.v_stride = (c.class_rank[n_cls - 1] + 31) / 32 * 32;
 
     const size_t max_tiles = (size_t)c.max_tokens / LORA_TILE_TOKENS + 2 * (size_t)c.max_segments + 2;
-    const size_t max_items = max_tiles + (size_t)c.max_segments * (LORA_MAX_RANK / 4 + 16);
+    // GEMV items: per token batch up to 32 shrink + 16 expand items; batches <= groups + tokens/4
+    const size_t max_batches = (size_t)c.max_segments + (size_t)c.max_tokens / LORA_GEMV_BATCH + 1;
+    const size_t max_items = max_tiles + max_batches * (LORA_MAX_RANK / 4 + 16);
     c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) + 3 * ALIGN;
     c.stage_cap = align_up(max_part) + ALIGN;
 
-    size_t cur = c.layer_stride * (size_t)c.n_layers;
-    c.off_table = cur = align_up(cur);
-    cur += align_up(sizeof(int64_t) * c.slot_off.size());
+    size_t cur = align_up(c.layer_stride * (size_t)c.n_layers);
     c.off_v = cur;
     cur += align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
     c.off_plans = cur;
@@ -174,6 +188,11 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.off_stage = cur;
     cur += c.stage_cap * N_STAGES;
     c.total = cur;
+}
+
+char *slab_ptr(const lora_cache &c, int32_t layer, int32_t proj, int32_t slot)
+{
+    return c.pool + (size_t)layer * c.layer_stride + c.proj_off[proj] + (size_t)c.slot_row[slot] * c.row_bytes[proj];
 }
 
 int class_of_slot(const lora_cache &c, int32_t slot)
@@ -254,12 +273,45 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     p.slots.erase(std::unique(p.slots.begin(), p.slots.end()), p.slots.end());
     for (int32_t s : p.slots) p.generations.push_back(c.slots[s].generation);
 
+    // resolve slots: the device copy of an item carries the slot's first storage row, the
+    // entry's alpha and the item's first token
     auto stamp = [&](lora_item_t *items, int n) {
-        for (int i = 0; i < n; ++i) std::memcpy(&items[i].c, &c.slots[items[i].slot].alpha, sizeof(float));
+        for (int i = 0; i < n; ++i) {
+            const Slot &s = c.slots[items[i].slot];
+            lora::DevItem d;
+            d.tok_off = items[i].tok_off;
+            d.n_tok = items[i].n_tok;
+            d.row = c.slot_row[items[i].slot];
+            d.rank = items[i].rank;
+            d.a = items[i].a;
+            d.b = items[i].b;
+            d.alpha = s.alpha;
+            d.tok0 = w.tok_list[items[i].tok_off];
+            std::memcpy(&items[i], &d, sizeof(d));
+        }
+    };
+    p.tile_classes = 0;
+    for (int i = 0; i < w.n_tiles; ++i) {
+        const int nb = (w.tiles[i].rank + 15) / 16;
+        p.tile_classes |= nb <= 1 ? 1u : nb <= 2 ? 2u : nb <= 4 ? 4u : 8u;
+    }
+    auto stamp_gemv = [&](lora_item_t *items, int n, bool expand) {
+        for (int i = 0; i < n; ++i) {
+            const Slot &s = c.slots[items[i].slot];
+            lora::GemvItem d;
+            for (int t = 0; t < LORA_GEMV_BATCH; ++t)
+                d.tok[t] = t < items[i].n_tok ? w.tok_list[items[i].tok_off + t] : -1;
+            d.row = c.slot_row[items[i].slot];
+            d.rank = items[i].rank;
+            d.a = items[i].a;
+            if (expand) d.alpha = s.alpha;
+            else d.n_rows = items[i].b;
+            std::memcpy(&items[i], &d, sizeof(d));
+        }
     };
     stamp(w.tiles, w.n_tiles);
-    stamp(w.gs_items, w.n_gs_items);
-    stamp(w.ge_items, w.n_ge_items);
+    stamp_gemv(w.gs_items, w.n_gs_items, false);
+    stamp_gemv(w.ge_items, w.n_ge_items, true);
 
     p.T = T;
     p.n_tok_list = w.n_tok_list;
@@ -307,15 +359,36 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     return LORA_OK;
 }
 
+hipEvent_t take_event(lora_cache &c)
+{
+    if (!c.free_events.empty()) {
+        hipEvent_t e = c.free_events.back();
+        c.free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Runs `launch` and, when timing is on, brackets it with an event pair.
+template <typename F> hipError_t timed_launch(lora_cache &c, int kind, hipStream_t st, bool active, F launch)
+{
+    if (!c.timing || !active) return launch();
+    lora_cache::Timed t{kind, take_event(c), take_event(c)};
+    if (!t.start || !t.stop) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(t.start, st);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(t.stop, st);
+    c.timed.push_back(t);
+    return e;
+}
+
 int choose_k_splits(int n_tiles, int h_in)
 {
-    // enough blocks to cover the chip twice, k ranges of at least 256
-    int want = (512 + n_tiles - 1) / n_tiles;
-    const int cap = std::max(1, h_in / 256);
-    want = std::max(1, std::min(want, cap));
-    int k_len = (h_in + want - 1) / want;
-    k_len = (k_len + 63) / 64 * 64;
-    return (h_in + k_len - 1) / k_len;
+    // enough blocks to cover the chip about twice; the launch rounds k ranges up to 512 elements
+    const int want = std::max(1, (512 + n_tiles - 1) / n_tiles);
+    return lora::mfma_shrink_splits(h_in, want);
 }
 
 }  // namespace
@@ -389,7 +462,6 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
             rc = LORA_E_HIP;
         }
     };
-    fail(hipMemcpy(c->pool + c->off_table, c->slot_off.data(), sizeof(int64_t) * c->slot_off.size(), hipMemcpyHostToDevice));
     for (size_t i = 0; i < c->plans.size() && rc == LORA_OK; ++i) {
         lora_plan &p = c->plans[i];
         p.dev = c->pool + c->off_plans + c->plan_cap * i;
@@ -425,6 +497,11 @@ int lora_cache_destroy(lora_cache_t *c)
             if (e) (void)hipEventDestroy(e);
         for (auto &s : c->slots)
             if (s.fill_ev) (void)hipEventDestroy(s.fill_ev);
+        for (auto &t : c->timed) {
+            (void)hipEventDestroy(t.start);
+            (void)hipEventDestroy(t.stop);
+        }
+        for (auto &e : c->free_events) (void)hipEventDestroy(e);
     }
     delete c;
     return LORA_OK;
@@ -469,7 +546,7 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
         char *stage_b = sg.dev + align_up(bytes_a);
         HIP_TRY(hipMemcpyAsync(sg.dev, host_A, bytes_a, hipMemcpyHostToDevice, st));
         HIP_TRY(hipMemcpyAsync(stage_b, host_B, bytes_b, hipMemcpyHostToDevice, st));
-        char *slab = c->pool + (size_t)layer * c->layer_stride + c->slot_off[(size_t)proj * c->n_slots + slot];
+        char *slab = slab_ptr(*c, layer, proj, slot);
         HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, st));
         HIP_TRY(hipEventRecord(sg.ev, st));
         sg.pending = true;
@@ -563,9 +640,8 @@ int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t 
         slot >= c->n_slots)
         return LORA_E_INVAL;
     if (dev_ptr)
-        *dev_ptr = c->pool ? c->pool + (size_t)layer * c->layer_stride + c->slot_off[(size_t)proj * c->n_slots + slot]
-                           : nullptr;
-    if (bytes) *bytes = c->slab_bytes[(size_t)proj * c->class_rank.size() + c->slots[slot].cls];
+        *dev_ptr = c->pool ? slab_ptr(*c, layer, proj, slot) : nullptr;
+    if (bytes) *bytes = (size_t)lora::rank_storage(c->class_rank[c->slots[slot].cls]) * c->row_bytes[proj];
     return LORA_OK;
 }
 
@@ -574,6 +650,39 @@ int lora_cache_set_fencing(lora_cache_t *c, int32_t on)
     if (!c) return LORA_E_INVAL;
     c->fencing = on != 0;
     return LORA_OK;
+}
+
+int lora_cache_set_timing(lora_cache_t *c, int32_t on)
+{
+    if (!c || c->host_only) return LORA_E_INVAL;
+    c->timing = on != 0;
+    return LORA_OK;
+}
+
+int lora_cache_read_timing(lora_cache_t *c, double ms[LORA_K_COUNT], int64_t launches[LORA_K_COUNT])
+{
+    if (!c || !ms || !launches) return LORA_E_INVAL;
+    for (int k = 0; k < LORA_K_COUNT; ++k) {
+        ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    int rc = LORA_OK;
+    for (auto &t : c->timed) {
+        float el = 0.f;
+        hipError_t e = hipEventSynchronize(t.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&el, t.start, t.stop);
+        if (e == hipSuccess) {
+            ms[t.kind] += el;
+            ++launches[t.kind];
+        } else {
+            g_last_hip = (int)e;
+            rc = LORA_E_HIP;
+        }
+        c->free_events.push_back(t.start);
+        c->free_events.push_back(t.stop);
+    }
+    c->timed.clear();
+    return rc;
 }
 
 int lora_plan_create(lora_cache_t *c, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
@@ -603,19 +712,21 @@ int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p)
     return LORA_OK;
 }
 
-int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
-                    float scale, void *stream)
+static int validate_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out)
 {
-    if (!c || !p || !p->in_use || c->host_only) return LORA_E_INVAL;
     if (layer < 0 || layer >= c->n_layers || proj < 0 || proj >= (int32_t)c->proj.size()) return LORA_E_INVAL;
     if (p->T > 0 && (!x || !base_out || !aligned16(x) || !aligned16(base_out))) return LORA_E_INVAL;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t part = (size_t)layer * c->proj.size() + proj;
-
     for (size_t i = 0; i < p->slots.size(); ++i) {
-        Slot &s = c->slots[p->slots[i]];
+        const Slot &s = c->slots[p->slots[i]];
         if (!s.bound || s.generation != p->generations[i] || !s.part[part]) return LORA_E_STATE;
     }
+    return LORA_OK;
+}
+
+static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
+                         float scale, hipStream_t st)
+{
     for (int32_t sl : p->slots) {
         Slot &s = c->slots[sl];
         if (s.fill_pending) {
@@ -625,8 +736,8 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
     }
 
     lora::ApplyArgs a;
-    a.layer_base = c->pool + (size_t)layer * c->layer_stride;
-    a.slot_off = reinterpret_cast<const int64_t *>(c->pool + c->off_table) + (size_t)proj * c->n_slots;
+    a.proj_base = c->pool + (size_t)layer * c->layer_stride + c->proj_off[proj];
+    a.row_bytes = (int64_t)c->row_bytes[proj];
     a.tok_list = reinterpret_cast<const int32_t *>(p->dev);
     a.x = x;
     a.y = base_out;
@@ -635,18 +746,21 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
     a.h_out = c->proj[proj].h_out;
     a.v_stride = c->v_stride;
     a.scale = scale;
-    const lora_item_t *tiles = reinterpret_cast<const lora_item_t *>(p->dev + p->off_tiles);
-    const lora_item_t *gs = reinterpret_cast<const lora_item_t *>(p->dev + p->off_gs);
-    const lora_item_t *ge = reinterpret_cast<const lora_item_t *>(p->dev + p->off_ge);
+    const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(p->dev + p->off_tiles);
+    const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
+    const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
 
-    if (p->n_tiles > 0) {
-        const int splits = choose_k_splits(p->n_tiles, a.h_in);
-        if (splits > 1) HIP_TRY(lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st));
-        HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, st));
-    }
-    HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st));
-    HIP_TRY(lora::launch_mfma_expand(a, tiles, p->n_tiles, st));
-    HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st));
+    const int splits = p->n_tiles > 0 ? choose_k_splits(p->n_tiles, a.h_in) : 1;
+    HIP_TRY(timed_launch(*c, LORA_K_ZERO, st, splits > 1,
+                         [&] { return splits > 1 ? lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st) : hipSuccess; }));
+    HIP_TRY(timed_launch(*c, LORA_K_MFMA_SHRINK, st, p->n_tiles > 0,
+                         [&] { return lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, p->tile_classes, st); }));
+    HIP_TRY(timed_launch(*c, LORA_K_GEMV_SHRINK, st, p->n_gs > 0,
+                         [&] { return lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st); }));
+    HIP_TRY(timed_launch(*c, LORA_K_MFMA_EXPAND, st, p->n_tiles > 0,
+                         [&] { return lora::launch_mfma_expand(a, tiles, p->n_tiles, st); }));
+    HIP_TRY(timed_launch(*c, LORA_K_GEMV_EXPAND, st, p->n_ge > 0,
+                         [&] { return lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st); }));
 
     const int64_t seq = ++c->apply_seq;
     ++c->stats.applies;
@@ -654,13 +768,47 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
         c->slots[sl].last_used = seq;
         ++c->slots[sl].use_count;
     }
-    if (c->fencing && !is_capturing(st)) {
-        HIP_TRY(hipEventRecord(c->apply_ev[seq % N_APPLY_EVENTS], st));
-        c->apply_ev_seq[seq % N_APPLY_EVENTS] = seq;
-        HIP_TRY(hipEventRecord(p->ev_last_use, st));
-        p->use_pending = true;
-    }
     return LORA_OK;
+}
+
+// One event pair per call (not per apply): fills that come later wait for it.
+static int fence_applies(lora_cache_t *c, lora_plan_t *p, hipStream_t st)
+{
+    if (!c->fencing || is_capturing(st)) return LORA_OK;
+    const int64_t seq = c->apply_seq;
+    HIP_TRY(hipEventRecord(c->apply_ev[seq % N_APPLY_EVENTS], st));
+    c->apply_ev_seq[seq % N_APPLY_EVENTS] = seq;
+    HIP_TRY(hipEventRecord(p->ev_last_use, st));
+    p->use_pending = true;
+    return LORA_OK;
+}
+
+int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
+                    float scale, void *stream)
+{
+    if (!c || !p || !p->in_use || c->host_only) return LORA_E_INVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = validate_apply(c, p, layer, proj, x, base_out);
+    if (rc != LORA_OK) return rc;
+    rc = enqueue_apply(c, p, layer, proj, x, base_out, scale, st);
+    if (rc != LORA_OK) return rc;
+    return fence_applies(c, p, st);
+}
+
+int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int32_t n, float scale,
+                          void *stream)
+{
+    if (!c || !p || !p->in_use || c->host_only || n < 0 || (n > 0 && !descs)) return LORA_E_INVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int32_t i = 0; i < n; ++i) {
+        const int rc = validate_apply(c, p, descs[i].layer, descs[i].proj, descs[i].x, descs[i].base_out);
+        if (rc != LORA_OK) return rc;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        const int rc = enqueue_apply(c, p, descs[i].layer, descs[i].proj, descs[i].x, descs[i].base_out, scale, st);
+        if (rc != LORA_OK) return rc;
+    }
+    return n > 0 ? fence_applies(c, p, st) : LORA_OK;
 }
 
 int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void *base_out, int32_t T,

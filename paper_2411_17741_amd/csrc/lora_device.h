@@ -65,6 +65,22 @@ template <typename E> __device__ __forceinline__ float dot_chunk(const Chunk<E> 
     return s;
 }
 
+// acc + dot(a, b) over the 8 elements; bf16 pairs go through the packed dot instruction
+// (products are exact in fp32, accumulation is fp32)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot_chunk_acc(float acc, const Chunk<__bf16> &a, const Chunk<__bf16> &b)
+{
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.v.x), __builtin_bit_cast(bf16x2, b.v.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.v.y), __builtin_bit_cast(bf16x2, b.v.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.v.z), __builtin_bit_cast(bf16x2, b.v.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.v.w), __builtin_bit_cast(bf16x2, b.v.w), acc, false);
+    return acc;
+}
+__device__ __forceinline__ float dot_chunk_acc(float acc, const Chunk<float> &a, const Chunk<float> &b)
+{
+    return acc + dot_chunk(a, b);
+}
+
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(__bf16 v) { return (float)v; }
 template <typename E> __device__ __forceinline__ E from_float(float v);

@@ -8,10 +8,46 @@
 
 namespace lora {
 
-// Arguments common to the four apply kernels of one (layer, projection).
+// Pool layout.  Every slot owns `rs_class` consecutive *storage rows* (rs = rank rounded up
+// to a multiple of 8); a slot's first row is the same number in every projection, so a slab
+// is found without a table:
+//     slab(layer, proj, slot) = pool + layer*layer_stride + proj_off[proj] + row(slot) * row_bytes(proj)
+//     row_bytes(proj) = (h_in + h_out) * element size
+// Inside a slab of an adapter of rank r (rs = rank_storage(r)):
+//   At [rs][h_in]          rank-major: row j holds column j of A, contiguous along h_in
+//   Bp [rs/8][h_out][8]    rank-packed: the 8 ranks of a granule are contiguous per output column
+// Rows r..rs-1 are zero.  Only rs*(h_in+h_out) elements are ever read, whatever the slot's class.
+inline __host__ __device__ int32_t rank_storage(int32_t r) { return (r + 7) & ~7; }
+
+// Work item as the kernels read it (the public lora_item_t with the slot resolved).
+struct DevItem {
+    int32_t tok_off, n_tok;  // tokens: tok_list[tok_off .. tok_off+n_tok)
+    int32_t row;             // first storage row of the slot
+    int32_t rank;
+    int32_t a, b;            // as in lora_item_t
+    float alpha;             // the cache entry's own factor
+    int32_t tok0;            // tok_list[tok_off], so one-token items need no second lookup
+};
+static_assert(sizeof(DevItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
+
+// GEMV work item: a batch of up to LORA_GEMV_BATCH tokens of one slot, named directly so that
+// the kernels reach their data with one lookup.
+struct GemvItem {
+    int32_t tok[LORA_GEMV_BATCH];  // token ids, -1 = unused
+    int32_t row;                   // first storage row of the slot
+    int32_t rank;
+    int32_t a;                     // shrink: first rank row; expand: column offset in the super-chunk
+    union {
+        int32_t n_rows;            // shrink: rank rows of the item (<= 4)
+        float alpha;               // expand: the cache entry's own factor (columns follow from rank)
+    };
+};
+static_assert(sizeof(GemvItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
+
+// Arguments common to the apply kernels of one (layer, projection).
 struct ApplyArgs {
-    const char *layer_base;   // device: first slab of this layer
-    const int64_t *slot_off;  // device: [n_slots] byte offset of the slot's slab of this projection
+    const char *proj_base;    // device: first slab of this (layer, projection)
+    int64_t row_bytes;        // (h_in + h_out) * element size
     const int32_t *tok_list;  // device
     const void *x;            // device [T][h_in]
     void *y;                  // device [T][h_out], in/out
@@ -20,17 +56,14 @@ struct ApplyArgs {
     float scale;
 };
 
-// Pool layout of one slab (adapter of rank r, rs = r rounded up to a multiple of 8):
-//   At [rs][h_in]          rank-major: row j holds column j of A, contiguous along h_in
-//   Bp [rs/8][h_out][8]    rank-packed: the 8 ranks of a granule are contiguous per output column
-// Rows r..rs-1 are zero.  Only rs*(h_in+h_out) elements are ever read, whatever the slot's class.
-inline __host__ __device__ int32_t rank_storage(int32_t r) { return (r + 7) & ~7; }
-
 // launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16
-hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const lora_item_t *items, int n_items, hipStream_t st);
-hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const lora_item_t *items, int n_items, hipStream_t st);
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const lora_item_t *tiles, int n_tiles, int k_splits, hipStream_t st);
-hipError_t launch_mfma_expand(const ApplyArgs &a, const lora_item_t *tiles, int n_tiles, hipStream_t st);
+hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
+hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
+// class_mask: bit k set = some tile has ceil(rank/16) in (2^(k-1), 2^k] (k = 0: rank <= 16)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
+                              hipStream_t st);
+int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
+hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st);
 hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st);
 // staged [h_in][r] / [r][h_out] -> slab layout
 hipError_t launch_repack(int dtype, const void *stage_A, const void *stage_B, void *slab, int32_t h_in, int32_t h_out,

@@ -17,122 +17,151 @@
 namespace lora {
 
 namespace {
-constexpr int KT = 64;                 // shrink: k elements per LDS tile
-constexpr int AT_ROW = KT * 2 + 16;    // bytes per At row in LDS (padded: rows land in distinct banks)
-constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the staged V tile
-constexpr int EXPAND_PASSES = 2;       // expand: column passes of 256 per block
+constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the staged V tile (padded)
+constexpr int EXPAND_COLS = 512;                // expand: columns per block, in passes of 128
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
-// shrink.  Block = 4 wavefronts; wavefront w owns tokens 16w..16w+15 of the tile and all
-// rank blocks (up to 8 of 16 ranks).  x is loaded straight into A-operand registers (each x
-// element is used by exactly one wavefront); the At tile is shared through LDS, double
-// buffered, one barrier per K tile.  Lane group g covers k = kt + 16g .. +15 (32 contiguous
-// bytes per lane), MFMA step i uses the i-th 8 of them.
+// shrink.  Block = 4 wavefronts on one tile and one k range; the range is cut in four and
+// every wavefront works alone on its quarter: all (up to 4) token blocks x all (up to NBMAX)
+// rank blocks, both operands loaded straight from global memory into MFMA registers -- x from
+// HBM, At from L2 -- with the next step's loads in flight while the current step multiplies.
+// No LDS and no barrier in the loop.  Per step a lane group g covers k = k0 + (KS/4)*g .. and
+// MFMA i of the step uses the i-th 8 of them.  The four partial results are summed through
+// LDS at the end.  NBMAX (1, 2, 4, 8 rank blocks of 16) is a template parameter so that small
+// ranks do not pay for the accumulators of large ones; a block leaves at once if its tile
+// belongs to another class.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const lora_item_t *__restrict__ tiles,
-                                                          int k_len, int use_atomic)
+template <int NBMAX, int KS>
+__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int k_len,
+                                                          int use_atomic)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char at_lds[2][LORA_MAX_RANK * AT_ROW];
+    constexpr int NI = KS / 32;   // MFMA k steps per loop step
+    constexpr int LB = KS / 4;    // elements per lane per operand row per step
+    __shared__ __attribute__((aligned(16))) float red[2][4 * NBMAX * 4][64];
 
-    const lora_item_t it = tiles[blockIdx.x];
+    const DevItem it = tiles[blockIdx.x];
+    const int NB = (it.rank + 15) >> 4;
+    if (NB > NBMAX || (NBMAX > 1 && NB <= NBMAX / 2)) return;  // another class (uniform)
+
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int rs = rank_storage(it.rank);
-    const int NB = (it.rank + 15) >> 4;
-    const int k_begin = blockIdx.y * k_len;
-    const int k_end = min(a.h_in, k_begin + k_len);
-    const int n_kt = (k_end - k_begin + KT - 1) / KT;
-    if (n_kt <= 0) return;
+    const int n_mb = (it.n_tok + 15) >> 4;
+    const int kq = k_len >> 2;  // k_len is a multiple of 4*KS
+    const int k_lo = blockIdx.y * k_len + w * kq;
+    const int k_hi = min(a.h_in, k_lo + kq);
+    const int n_steps = k_hi > k_lo ? (k_hi - k_lo + KS - 1) / KS : 0;
 
-    const __bf16 *At = reinterpret_cast<const __bf16 *>(a.layer_base + a.slot_off[it.slot]);
+    const __bf16 *At = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes);
     const __bf16 *x = static_cast<const __bf16 *>(a.x);
 
-    const bool wave_live = 16 * w < it.n_tok;
-    const int ti_a = 16 * w + m;  // token row this lane feeds as A operand
-    const bool a_ok = ti_a < it.n_tok;
-    const __bf16 *xrow = x + (size_t)(a_ok ? a.tok_list[it.tok_off + ti_a] : 0) * a.h_in + 16 * g;
-
-    // At tile loader: 8 lanes per row (128 bytes), 32 rows per pass
-    const int lp = tid & 7, lr = tid >> 3;
-    const int n_pass = (16 * NB + 31) >> 5;
-
-    uint4 xa[2], xn[2], tn[4];
-    auto load_x = [&](int kt, uint4(&dst)[2]) {
-        if (a_ok) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(xrow + kt);
-            dst[0] = p[0];
-            dst[1] = p[1];
-        } else {
-            dst[0] = dst[1] = make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto load_at = [&](int kt) {
+    const __bf16 *xp[4];
+    bool x_ok[4];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int row = p * 32 + lr;
-            if (p < n_pass && row < rs)
-                tn[p] = *reinterpret_cast<const uint4 *>(At + (size_t)row * a.h_in + kt + lp * 8);
-            else
-                tn[p] = make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_at = [&](int buf) {
+    for (int mb = 0; mb < 4; ++mb) {
+        const int ti = 16 * mb + m;
+        x_ok[mb] = ti < it.n_tok;
+        const int tok = x_ok[mb] ? (ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) : 0;
+        xp[mb] = x + (size_t)tok * a.h_in + LB * g;
+    }
+    const __bf16 *ap[NBMAX];
+    bool a_ok[NBMAX];
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
-            if (p < n_pass) *reinterpret_cast<uint4 *>(&at_lds[buf][(p * 32 + lr) * AT_ROW + lp * 16]) = tn[p];
-    };
-
-    floatx4 acc[8];
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    load_x(k_begin, xa);
-    load_at(k_begin);
-    store_at(0);
-    __syncthreads();
-
-    for (int kt_i = 0; kt_i < n_kt; ++kt_i) {
-        const int cur = kt_i & 1;
-        const bool more = kt_i + 1 < n_kt;
-        if (more) {
-            load_x(k_begin + (kt_i + 1) * KT, xn);
-            load_at(k_begin + (kt_i + 1) * KT);
-        }
-        if (wave_live) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const bf16x8 av = __builtin_bit_cast(bf16x8, xa[i]);
-#pragma unroll
-                for (int nb = 0; nb < 8; ++nb) {
-                    if (nb < NB) {
-                        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(
-                            &at_lds[cur][(16 * nb + m) * AT_ROW + (16 * g + 8 * i) * 2]);
-                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[nb], 0, 0, 0);
-                    }
-                }
-            }
-        }
-        if (more) {
-            store_at(cur ^ 1);
-            xa[0] = xn[0];
-            xa[1] = xn[1];
-        }
-        __syncthreads();
+    for (int nb = 0; nb < NBMAX; ++nb) {
+        const int row = 16 * nb + m;
+        a_ok[nb] = row < rs;
+        ap[nb] = At + (size_t)(a_ok[nb] ? row : 0) * a.h_in + LB * g;
     }
 
-    if (!wave_live) return;
+    floatx4 acc[4][NBMAX];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int ti = 16 * w + 4 * g + r;
-        if (ti < it.n_tok) {
-            float *vr = a.v + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < 8; ++nb) {
-                const int jr = 16 * nb + m;
-                if (nb < NB && jr < it.rank) {
-                    if (use_atomic) unsafeAtomicAdd(vr + jr, acc[nb][r]);
-                    else vr[jr] = acc[nb][r];
+        for (int nb = 0; nb < NBMAX; ++nb) acc[mb][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 xr[2][4][NI], ar[2][NBMAX][NI];
+    auto load_step = [&](int k, uint4(&xd)[4][NI], uint4(&ad)[NBMAX][NI]) {
+        // a step may stick out of the range by 64 elements when KS = 128: pieces are predicated
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                xd[mb][i] = (x_ok[mb] && mb < n_mb && k + LB * g + 8 * i < k_hi)
+                                ? *reinterpret_cast<const uint4 *>(xp[mb] + k + 8 * i)
+                                : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < NBMAX; ++nb)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                ad[nb][i] = (a_ok[nb] && nb < NB && k + LB * g + 8 * i < k_hi)
+                                ? *reinterpret_cast<const uint4 *>(ap[nb] + k + 8 * i)
+                                : make_uint4(0, 0, 0, 0);
+    };
+    auto mul_step = [&](uint4(&xd)[4][NI], uint4(&ad)[NBMAX][NI]) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                if (mb < n_mb) {
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, xd[mb][i]);
+#pragma unroll
+                    for (int nb = 0; nb < NBMAX; ++nb)
+                        if (nb < NB)
+                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                av, __builtin_bit_cast(bf16x8, ad[nb][i]), acc[mb][nb], 0, 0, 0);
+                }
+            }
+    };
+
+    if (n_steps > 0) load_step(k_lo, xr[0], ar[0]);
+    for (int sidx = 0; sidx < n_steps; sidx += 2) {
+        if (sidx + 1 < n_steps) load_step(k_lo + (sidx + 1) * KS, xr[1], ar[1]);
+        mul_step(xr[0], ar[0]);
+        if (sidx + 2 < n_steps) load_step(k_lo + (sidx + 2) * KS, xr[0], ar[0]);
+        if (sidx + 1 < n_steps) mul_step(xr[1], ar[1]);
+    }
+
+    // sum the four wavefronts' partials: 2,3 -> LDS -> 0,1 add; 1 -> LDS -> 0 adds and writes
+    auto spill = [&](int slot) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBMAX; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) red[slot][(mb * NBMAX + nb) * 4 + r][lane] = acc[mb][nb][r];
+    };
+    auto absorb = [&](int slot) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBMAX; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[mb][nb][r] += red[slot][(mb * NBMAX + nb) * 4 + r][lane];
+    };
+    if (w >= 2) spill(w - 2);
+    __syncthreads();
+    if (w < 2) absorb(w);
+    __syncthreads();
+    if (w == 1) spill(0);
+    __syncthreads();
+    if (w != 0) return;
+    absorb(0);
+
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ti = 16 * mb + 4 * g + r;
+            if (ti < it.n_tok) {
+                float *vr = a.v + (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride;
+#pragma unroll
+                for (int nb = 0; nb < NBMAX; ++nb) {
+                    const int jr = 16 * nb + m;
+                    if (nb < NB && jr < it.rank) {
+                        if (use_atomic) unsafeAtomicAdd(vr + jr, acc[mb][nb][r]);
+                        else vr[jr] = acc[mb][nb][r];
+                    }
                 }
             }
         }
@@ -140,26 +169,27 @@ __global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const lor
 }
 
 // ---------------------------------------------------------------------------------------
-// expand.  Block = 4 wavefronts, tile of up to 64 tokens x 256*EXPAND_PASSES columns.  The
-// scaled V tile is staged once in LDS as bf16.  The product is formed transposed (rows =
-// output columns, columns = tokens) so that a lane ends up with runs of 8 consecutive
-// output columns of one token: block b of the 4 column blocks of a wavefront maps MFMA row
+// expand.  Block = 4 wavefronts, tile of up to 64 tokens x EXPAND_COLS columns in passes of
+// 128 columns; wavefront w owns token half w&1 and column half w>>1 of a pass (32 tokens x 64
+// columns).  The scaled V tile is staged once in LDS as bf16.  The product is formed
+// transposed (rows = output columns, columns = tokens) so that a lane ends up with runs of 8
+// consecutive output columns of one token: block b of the 4 column blocks maps MFMA row
 // 4q+r to column 8q + 4(b&1) + r + 32(b>>1), which makes the read-modify-write of base_out a
-// pair of 16-byte accesses per lane, 64 contiguous bytes per token row across a lane group.
+// pair of 16-byte accesses per lane and token, 64 contiguous bytes per row across a lane group.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const lora_item_t *__restrict__ tiles)
+__global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles)
 {
     __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
 
-    const lora_item_t it = tiles[blockIdx.x];
+    const DevItem it = tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int rs8 = rank_storage(it.rank) >> 3;
+    const int th = w & 1, ch = w >> 1;
+    const int rs = rank_storage(it.rank), rs8 = rs >> 3;
     const int KS = (it.rank + 31) >> 5;  // MFMA k steps of 32 ranks
     const int c8 = KS * 4;               // staged chunks (8 ranks) per token
-    const float s = a.scale * __int_as_float(it.c);
-    const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.layer_base + a.slot_off[it.slot]) +
-                       (size_t)rank_storage(it.rank) * a.h_in;
+    const float s = a.scale * it.alpha;
+    const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
 
     // stage s.V as bf16: vs[token][rank]
@@ -167,9 +197,12 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const lor
         const int ti = idx / c8, j8 = idx - ti * c8;
         bf16x8 o;
         if (ti < it.n_tok) {
-            const float *vr = a.v + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride + j8 * 8;
+            const float4 *vr = reinterpret_cast<const float4 *>(
+                a.v + (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride + j8 * 8);
+            const float4 lo = vr[0], hi = vr[1];
+            const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)((j8 * 8 + e < it.rank) ? s * vr[e] : 0.f);
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)((j8 * 8 + e < it.rank) ? s * f[e] : 0.f);
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
@@ -178,37 +211,40 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const lor
     }
     __syncthreads();
 
-    // token rows this lane reads/writes in the epilogue: 16*tb + m
-    size_t yoff[4];
-    bool yok[4];
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const int ti = 16 * tb + m;
-        yok[tb] = ti < it.n_tok;
-        yoff[tb] = yok[tb] ? (size_t)a.tok_list[it.tok_off + ti] * a.h_out : 0;
-    }
-    const int n_tb = (it.n_tok + 15) >> 4;
+    if (32 * th >= it.n_tok) return;  // this token half is empty (no barrier follows)
 
-    for (int cp = 0; cp < EXPAND_PASSES; ++cp) {
-        const int nw0 = (blockIdx.y * EXPAND_PASSES + cp) * 256 + 64 * w;
+    // token rows this lane reads/writes in the epilogue: 32*th + 16*tb + m
+    size_t yoff[2];
+    bool yok[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int ti = 32 * th + 16 * tb + m;
+        yok[tb] = ti < it.n_tok;
+        yoff[tb] = yok[tb] ? (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.h_out : 0;
+    }
+    const bool tb1_live = 32 * th + 16 < it.n_tok;
+
+    for (int cp = 0; cp < EXPAND_COLS / 128; ++cp) {
+        const int nw0 = blockIdx.y * EXPAND_COLS + cp * 128 + 64 * ch;
         if (nw0 >= a.h_out) break;
 
-        uint4 yr[4][2];
+        uint4 yr[2][2];
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                if (yok[tb]) yr[tb][h] = *reinterpret_cast<const uint4 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h);
+                yr[tb][h] = yok[tb] ? *reinterpret_cast<const uint4 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h)
+                                    : make_uint4(0, 0, 0, 0);
 
-        floatx4 acc[4][4];
+        floatx4 acc[4][2];
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) acc[b][tb] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int tb = 0; tb < 2; ++tb) acc[b][tb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
         for (int ks = 0; ks < KS; ++ks) {
             const int j8 = 4 * ks + g;
-            bf16x8 aop[4], bop[4];
+            bf16x8 aop[4], bop[2];
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int n = nw0 + 8 * (m >> 2) + 4 * (b & 1) + (m & 3) + 32 * (b >> 1);
@@ -217,17 +253,17 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const lor
                 aop[b] = __builtin_bit_cast(bf16x8, raw);
             }
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                if (tb < n_tb) bop[tb] = *reinterpret_cast<const bf16x8 *>(&vs[(16 * tb + m) * VS_ROW + j8 * 16]);
+            for (int tb = 0; tb < 2; ++tb)
+                bop[tb] = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + 16 * tb + m) * VS_ROW + j8 * 16]);
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-#pragma unroll
-                for (int tb = 0; tb < 4; ++tb)
-                    if (tb < n_tb) acc[b][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[b], bop[tb], acc[b][tb], 0, 0, 0);
+            for (int b = 0; b < 4; ++b) {
+                acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[b], bop[0], acc[b][0], 0, 0, 0);
+                if (tb1_live) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[b], bop[1], acc[b][1], 0, 0, 0);
+            }
         }
 
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
+        for (int tb = 0; tb < 2; ++tb) {
             if (yok[tb]) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -263,22 +299,40 @@ hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const lora_item_t *tiles, int n_tiles, int k_splits, hipStream_t st)
+// k ranges are multiples of 512 elements: four wavefronts x one 128-element step.
+static int shrink_k_len(int h_in, int want)
+{
+    int k_len = (h_in + want - 1) / want;
+    return (k_len + 511) / 512 * 512;
+}
+
+int mfma_shrink_splits(int h_in, int want)
+{
+    if (want < 1) want = 1;
+    const int k_len = shrink_k_len(h_in, want);
+    return (h_in + k_len - 1) / k_len;
+}
+
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
+                              hipStream_t st)
 {
     if (n_tiles <= 0) return hipSuccess;
-    int k_len = (a.h_in + k_splits - 1) / k_splits;
-    k_len = (k_len + KT - 1) / KT * KT;
+    const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
     const int splits = (a.h_in + k_len - 1) / k_len;
-    hipLaunchKernelGGL(mfma_shrink_kernel, dim3(n_tiles, splits), dim3(256), 0, st, a, tiles, k_len, splits > 1 ? 1 : 0);
+    const dim3 grid(n_tiles, splits), block(256);
+    const int at = splits > 1 ? 1 : 0;
+    if (class_mask & 1u) hipLaunchKernelGGL((mfma_shrink_kernel<1, 128>), grid, block, 0, st, a, tiles, k_len, at);
+    if (class_mask & 2u) hipLaunchKernelGGL((mfma_shrink_kernel<2, 128>), grid, block, 0, st, a, tiles, k_len, at);
+    if (class_mask & 4u) hipLaunchKernelGGL((mfma_shrink_kernel<4, 64>), grid, block, 0, st, a, tiles, k_len, at);
+    if (class_mask & 8u) hipLaunchKernelGGL((mfma_shrink_kernel<8, 64>), grid, block, 0, st, a, tiles, k_len, at);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_expand(const ApplyArgs &a, const lora_item_t *tiles, int n_tiles, hipStream_t st)
+hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st)
 {
     if (n_tiles <= 0) return hipSuccess;
-    const int cols_per_block = 256 * EXPAND_PASSES;
-    hipLaunchKernelGGL(mfma_expand_kernel, dim3(n_tiles, (a.h_out + cols_per_block - 1) / cols_per_block), dim3(256), 0,
-                       st, a, tiles);
+    hipLaunchKernelGGL(mfma_expand_kernel, dim3(n_tiles, (a.h_out + EXPAND_COLS - 1) / EXPAND_COLS), dim3(256), 0, st, a,
+                       tiles);
     return hipGetLastError();
 }
 
