@@ -53,6 +53,7 @@ def algorithmic_bytes(inst, w, esize=2):
             "mfma_expand": esize * (sum(t.values()) * pr.h_out + 2 * nt * pr.h_out),
             "zero": 0,
         })
+        out[-1]["gemv_fused"] = out[-1]["gemv_shrink"] + out[-1]["gemv_expand"]
     return out
 
 
@@ -130,7 +131,7 @@ def main() -> int:
     rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS)
     B.check(rc)
     per_proj = algorithmic_bytes(inst, w)
-    step_bytes = sum(sum(v.values()) for v in per_proj)
+    step_bytes = sum(sum(b for k, b in v.items() if k != "gemv_fused") for v in per_proj)
     step_flops = sum(2 * it[1] * it[3] * (p.h_in + p.h_out) for p in inst.projs for it in (w["tiles"] + w["groups"]))
 
     roofline = None

@@ -54,7 +54,11 @@ typedef enum {
 
 enum { LORA_F32 = 0, LORA_BF16 = 1 };                               /* element type of x, base_out, A, B */
 enum { LORA_SLOT_EMPTY = 0, LORA_SLOT_FILLING = 1, LORA_SLOT_READY = 2 };
-enum { LORA_CACHE_HOST_ONLY = 1 };                                  /* flags: slot table only, no device work */
+enum {
+    LORA_CACHE_HOST_ONLY = 1,     /* flags: slot table only, no device work */
+    LORA_CACHE_FUSED_GEMV = 2     /* run GEMV shrink and expand as one launch with an in-kernel hand-over
+                                     (slower than two launches on MI355X: see the kernel's header) */
+};
 
 #define LORA_MAX_RANK 128
 #define LORA_TILE_TOKENS 64      /* tokens per matrix-core tile */
@@ -229,9 +233,18 @@ int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
  * costs a few microseconds each, so time whole steps with timing off).
  * lora_cache_read_timing waits for the recorded events, adds up the elapsed milliseconds and
  * launch counts per kernel kind since the last read, and forgets them. */
-enum { LORA_K_ZERO = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4, LORA_K_COUNT = 5 };
+enum {
+    LORA_K_ZERO = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4,
+    LORA_K_GEMV_FUSED = 5, LORA_K_COUNT = 6
+};
 int lora_cache_set_timing(lora_cache_t *c, int32_t on);
 int lora_cache_read_timing(lora_cache_t *c, double ms[LORA_K_COUNT], int64_t launches[LORA_K_COUNT]);
+
+/* Blocks until `stream` is idle, then reports whether any kernel of this cache gave up a
+ * bounded wait since the last call (*fault = 1; the outputs of that apply are then invalid)
+ * and clears the flag.  The fused GEMV launch is the only kernel that waits; with a working
+ * device the flag never rises. */
+int lora_cache_check_fault(lora_cache_t *c, void *stream, int32_t *fault);
 
 const char *lora_strerror(int status);
 int lora_last_hip_error(void);

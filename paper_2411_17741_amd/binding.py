@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "liblora_cache.so")
 LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND = 0, -1, -2, -3, -4, -5
 LORA_F32, LORA_BF16 = 0, 1
 LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
-LORA_CACHE_HOST_ONLY = 1
+LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV = 1, 2
 LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS = 128, 64, 16
 
 
@@ -102,6 +102,7 @@ _SIGS = {
     "lora_cache_set_fencing": (c_int, [c_void_p, c_int32]),
     "lora_cache_set_timing": (c_int, [c_void_p, c_int32]),
     "lora_cache_read_timing": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
+    "lora_cache_check_fault": (c_int, [c_void_p, c_void_p, _i32p]),
     "lora_strerror": (c_char_p, [c_int]),
     "lora_last_hip_error": (c_int, []),
 }
@@ -270,7 +271,7 @@ def lora_apply(cache, layer: int, proj: int, x: int, base_out: int, T: int, seg_
                            _ptr(sr), len(ss), scale, c_void_p(stream or None))
 
 
-KERNEL_KINDS = ("zero", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand")
+KERNEL_KINDS = ("zero", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand", "gemv_fused")
 
 
 def lora_cache_set_timing(cache, on: int) -> int:
@@ -283,6 +284,13 @@ def lora_cache_read_timing(cache):
     n = (c_int64 * len(KERNEL_KINDS))()
     rc = _lib.lora_cache_read_timing(cache, ms, n)
     return rc, {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_KINDS)}
+
+
+def lora_cache_check_fault(cache, stream: int = 0):
+    """-> (status, fault)"""
+    f = c_int32(0)
+    rc = _lib.lora_cache_check_fault(cache, c_void_p(stream or None), ctypes.byref(f))
+    return rc, f.value
 
 
 def lora_cache_set_fencing(cache, on: int) -> int:

@@ -63,7 +63,9 @@ struct lora_plan {
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
     unsigned tile_classes = 0;  // which rank classes the tiles fall in (see launch_mfma_shrink)
-    size_t off_tiles = 0, off_gs = 0, off_ge = 0;
+    size_t off_tiles = 0, off_gs = 0, off_ge = 0, off_counters = 0;
+    int32_t n_batches = 0;
+    int32_t epoch = 0;  // applies since the upload; the fused GEMV counters stand at epoch * rank
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
 };
@@ -83,6 +85,8 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
+    size_t off_fault = 0;
+    bool fused_gemv = false;
     size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
 
     std::vector<Slot> slots;
@@ -145,6 +149,7 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.mfma_min = cfg->dtype == LORA_BF16 ? (cfg->mfma_min_tokens ? cfg->mfma_min_tokens : LORA_MFMA_MIN_TOKENS) : 0;
     c.flags = cfg->flags;
     c.host_only = (cfg->flags & LORA_CACHE_HOST_ONLY) != 0;
+    c.fused_gemv = (cfg->flags & LORA_CACHE_FUSED_GEMV) != 0;
 
     const int n_proj = cfg->n_proj, n_cls = cfg->n_classes;
     c.class_first.resize(n_cls);
@@ -177,10 +182,13 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     // GEMV items: per token batch up to 32 shrink + 16 expand items; batches <= groups + tokens/4
     const size_t max_batches = (size_t)c.max_segments + (size_t)c.max_tokens / LORA_GEMV_BATCH + 1;
     const size_t max_items = max_tiles + max_batches * (LORA_MAX_RANK / 4 + 16);
-    c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) + 3 * ALIGN;
+    c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) +
+                 align_up(sizeof(int32_t) * max_batches) + 4 * ALIGN;
     c.stage_cap = align_up(max_part) + ALIGN;
 
     size_t cur = align_up(c.layer_stride * (size_t)c.n_layers);
+    c.off_fault = cur;
+    cur += ALIGN;
     c.off_v = cur;
     cur += align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
     c.off_plans = cur;
@@ -295,17 +303,21 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         const int nb = (w.tiles[i].rank + 15) / 16;
         p.tile_classes |= nb <= 1 ? 1u : nb <= 2 ? 2u : nb <= 4 ? 4u : 8u;
     }
+    // token batches are runs of items with the same tok_off, in the same order in both lists
+    std::unordered_map<int32_t, int32_t> batch_of;
+    for (int i = 0; i < w.n_gs_items; ++i) batch_of.emplace(w.gs_items[i].tok_off, (int32_t)batch_of.size());
+    p.n_batches = (int32_t)batch_of.size();
     auto stamp_gemv = [&](lora_item_t *items, int n, bool expand) {
         for (int i = 0; i < n; ++i) {
             const Slot &s = c.slots[items[i].slot];
+            const int32_t batch = batch_of[items[i].tok_off];
             lora::GemvItem d;
             for (int t = 0; t < LORA_GEMV_BATCH; ++t)
                 d.tok[t] = t < items[i].n_tok ? w.tok_list[items[i].tok_off + t] : -1;
             d.row = c.slot_row[items[i].slot];
             d.rank = items[i].rank;
-            d.a = items[i].a;
-            if (expand) d.alpha = s.alpha;
-            else d.n_rows = items[i].b;
+            d.a = expand ? ((items[i].a / 64) | (batch << 4)) : (items[i].a | (items[i].b << 8) | (batch << 12));
+            d.alpha = s.alpha;
             std::memcpy(&items[i], &d, sizeof(d));
         }
     };
@@ -321,7 +333,9 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     p.off_tiles = align_up(sizeof(int32_t) * (size_t)w.n_tok_list);
     p.off_gs = p.off_tiles + align_up(sizeof(lora_item_t) * (size_t)w.n_tiles);
     p.off_ge = p.off_gs + align_up(sizeof(lora_item_t) * (size_t)w.n_gs_items);
-    const size_t bytes = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    p.off_counters = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    const size_t bytes = p.off_counters + align_up(sizeof(int32_t) * (size_t)p.n_batches);
+    p.epoch = 0;
     if (bytes > c.plan_cap) {
         lora_worklists_free(&w);
         return LORA_E_NOMEM;
@@ -347,6 +361,7 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
         std::memcpy(p.pinned + p.off_gs, w.gs_items, sizeof(lora_item_t) * (size_t)w.n_gs_items);
         std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
+        std::memset(p.pinned + p.off_counters, 0, bytes - p.off_counters);  // ready counters start at zero
         lora_worklists_free(&w);
         if (bytes) {
             HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
@@ -456,6 +471,11 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
     c->pool_bytes = dev_pool_bytes;
 
     int rc = LORA_OK;
+    if (hipMemset(c->pool + c->off_fault, 0, ALIGN) != hipSuccess) {
+        g_last_hip = (int)hipGetLastError();
+        delete c;
+        return LORA_E_HIP;
+    }
     auto fail = [&](hipError_t e) {
         if (e != hipSuccess && rc == LORA_OK) {
             g_last_hip = (int)e;
@@ -652,6 +672,18 @@ int lora_cache_set_fencing(lora_cache_t *c, int32_t on)
     return LORA_OK;
 }
 
+int lora_cache_check_fault(lora_cache_t *c, void *stream, int32_t *fault)
+{
+    if (!c || !fault || c->host_only) return LORA_E_INVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipStreamSynchronize(st));
+    int32_t v = 0;
+    HIP_TRY(hipMemcpy(&v, c->pool + c->off_fault, sizeof(v), hipMemcpyDeviceToHost));
+    if (v) HIP_TRY(hipMemset(c->pool + c->off_fault, 0, sizeof(v)));
+    *fault = v ? 1 : 0;
+    return LORA_OK;
+}
+
 int lora_cache_set_timing(lora_cache_t *c, int32_t on)
 {
     if (!c || c->host_only) return LORA_E_INVAL;
@@ -755,12 +787,24 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
                          [&] { return splits > 1 ? lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st) : hipSuccess; }));
     HIP_TRY(timed_launch(*c, LORA_K_MFMA_SHRINK, st, p->n_tiles > 0,
                          [&] { return lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, p->tile_classes, st); }));
-    HIP_TRY(timed_launch(*c, LORA_K_GEMV_SHRINK, st, p->n_gs > 0,
-                         [&] { return lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st); }));
+    const bool fused = c->fused_gemv && p->n_gs > 0 && p->epoch < (1 << 23);
+    if (fused) {
+        ++p->epoch;
+        HIP_TRY(timed_launch(*c, LORA_K_GEMV_FUSED, st, true, [&] {
+            return lora::launch_gemv_fused(c->dtype, a, gs, p->n_gs, ge, p->n_ge,
+                                           reinterpret_cast<int32_t *>(p->dev + p->off_counters), p->epoch,
+                                           reinterpret_cast<int32_t *>(c->pool + c->off_fault), st);
+        }));
+    } else {
+        HIP_TRY(timed_launch(*c, LORA_K_GEMV_SHRINK, st, p->n_gs > 0,
+                             [&] { return lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st); }));
+    }
     HIP_TRY(timed_launch(*c, LORA_K_MFMA_EXPAND, st, p->n_tiles > 0,
                          [&] { return lora::launch_mfma_expand(a, tiles, p->n_tiles, st); }));
-    HIP_TRY(timed_launch(*c, LORA_K_GEMV_EXPAND, st, p->n_ge > 0,
-                         [&] { return lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st); }));
+    if (!fused) {
+        HIP_TRY(timed_launch(*c, LORA_K_GEMV_EXPAND, st, p->n_ge > 0,
+                             [&] { return lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st); }));
+    }
 
     const int64_t seq = ++c->apply_seq;
     ++c->stats.applies;

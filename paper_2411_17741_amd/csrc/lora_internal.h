@@ -31,16 +31,16 @@ struct DevItem {
 static_assert(sizeof(DevItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
 
 // GEMV work item: a batch of up to LORA_GEMV_BATCH tokens of one slot, named directly so that
-// the kernels reach their data with one lookup.
+// the kernels reach their data with one lookup.  `a` packs, for a shrink item, the first rank
+// row (bits 0-7), the number of rows (bits 8-11) and the batch number (bits 12+); for an expand
+// item the column offset in the super-chunk divided by 64 (bits 0-3) and the batch number
+// (bits 4+).  The batch number indexes the ready counters of the fused kernel.
 struct GemvItem {
     int32_t tok[LORA_GEMV_BATCH];  // token ids, -1 = unused
     int32_t row;                   // first storage row of the slot
     int32_t rank;
-    int32_t a;                     // shrink: first rank row; expand: column offset in the super-chunk
-    union {
-        int32_t n_rows;            // shrink: rank rows of the item (<= 4)
-        float alpha;               // expand: the cache entry's own factor (columns follow from rank)
-    };
+    int32_t a;
+    float alpha;                   // expand: the cache entry's own factor
 };
 static_assert(sizeof(GemvItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
 
@@ -59,6 +59,11 @@ struct ApplyArgs {
 // launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16
 hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
 hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
+// shrink and expand in one launch: expand wavefronts load their slab part at once and then wait
+// for the batch's counter (device, one int32 per batch, only ever incremented) to reach
+// epoch * rank; `fault` (device int32) is set if a wait gives up
+hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
+                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st);
 // class_mask: bit k set = some tile has ceil(rank/16) in (2^(k-1), 2^k] (k = 0: rank <= 16)
 hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
                               hipStream_t st);

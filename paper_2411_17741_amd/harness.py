@@ -45,14 +45,14 @@ class PooledInstance:
 
     def __init__(self, inst, n_layers: Optional[int] = None, fill_layers: Optional[Iterable[int]] = None,
                  adapters: Optional[Iterable[int]] = None, extra_tokens: int = 0, n_plans: int = 2,
-                 mfma_min_tokens: int = 0, class_rank: Sequence[int] = CLASS_RANKS):
+                 mfma_min_tokens: int = 0, class_rank: Sequence[int] = CLASS_RANKS, flags: int = 0):
         self.inst = inst
         self.dtype = B.LORA_BF16 if inst.dtype == "bf16" else B.LORA_F32
         self.n_layers = int(n_layers or inst.n_layers)
         self.class_slots, self.slot_of = slot_layout(inst.ranks, class_rank)
         self.pool = LoraPool([(p.h_in, p.h_out) for p in inst.projs], self.n_layers, class_rank, self.class_slots, self.dtype,
                              max_tokens=max(1, inst.T + extra_tokens), max_segments=max(1, inst.n_seg + 8), n_plans=n_plans,
-                             mfma_min_tokens=mfma_min_tokens)
+                             mfma_min_tokens=mfma_min_tokens, flags=flags)
         self.seg_slot = np.where(inst.seg_adapter >= 0, self.slot_of[np.maximum(inst.seg_adapter, 0)], -1).astype(np.int32)
         self.seg_rank = inst.seg_rank
         self.filled: Dict[int, bool] = {}

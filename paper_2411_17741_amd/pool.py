@@ -30,13 +30,13 @@ class LoraPool:
 
     def __init__(self, proj: Sequence[Sequence[int]], n_layers: int, class_rank: Sequence[int], class_slots: Sequence[int],
                  dtype: int, max_tokens: int, max_segments: int, n_plans: int = 2, mfma_min_tokens: int = 0,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", flags: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("LoraPool needs a GPU: the library has no CPU path")
         self.proj = [tuple(p) for p in proj]
         self.dtype = dtype
         self.device = torch.device(device)
-        self.cfg = B.make_config(proj, n_layers, class_rank, class_slots, dtype, max_tokens, max_segments, n_plans, mfma_min_tokens)
+        self.cfg = B.make_config(proj, n_layers, class_rank, class_slots, dtype, max_tokens, max_segments, n_plans, mfma_min_tokens, flags)
         self.bytes = B.lora_cache_bytes_required(self.cfg)
         if self.bytes == 0:
             raise B.LoraError(B.LORA_E_INVAL, "lora_cache_bytes_required")
@@ -94,6 +94,13 @@ class LoraPool:
         assert x.is_cuda and base_out.is_cuda and x.is_contiguous() and base_out.is_contiguous()
         B.check(B.lora_apply_plan(self.handle, plan, layer, proj, x.data_ptr(), base_out.data_ptr(), scale, self._stream(stream)),
                 "lora_apply_plan")
+
+    def check_fault(self, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Synchronizes the stream and raises if a kernel gave up a bounded wait."""
+        rc, fault = B.lora_cache_check_fault(self.handle, self._stream(stream))
+        B.check(rc, "lora_cache_check_fault")
+        if fault:
+            raise RuntimeError("a LoRA apply kernel gave up waiting for its intermediate; outputs are invalid")
 
     def plan_destroy(self, plan) -> None:
         B.check(B.lora_plan_destroy(self.handle, plan), "lora_plan_destroy")

@@ -38,16 +38,16 @@ def _check(m, dtype, what):
         assert m[k] <= lim, f"{what}: {k} = {m[k]:.3e} > {lim}"
 
 
-def _full_parity(inst, p=0, layer=0, pi=None, mfma_min_tokens=0):
+def _full_parity(inst, p=0, layer=0, pi=None, mfma_min_tokens=0, flags=0):
     B, H = _mods()
     own = pi is None
     if own:
-        pi = H.PooledInstance(inst, mfma_min_tokens=mfma_min_tokens)
+        pi = H.PooledInstance(inst, mfma_min_tokens=mfma_min_tokens, flags=flags)
     try:
         x, base = inst.x(p), inst.base_out(p)
         xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
         pi.apply(layer, p, xd, yd)
-        torch.cuda.synchronize()
+        pi.pool.check_fault()
         y = yd.float().cpu().numpy()
         ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, p, inst.used_adapters()), inst.scale)
         m = H.error_metrics(y, ref, base, EPS[inst.dtype])
@@ -89,6 +89,34 @@ def test_small_mixed_all_paths(dtype, seed):
 
 def test_decode_config():
     _full_parity(wl.decode())
+
+
+def test_fused_gemv_option_gives_the_same_results():
+    """The GEMV phases as one launch with an in-kernel hand-over (opt-in flag)."""
+    B, H = _mods()
+    _full_parity(wl.decode(), flags=B.LORA_CACHE_FUSED_GEMV)
+    _full_parity(wl.small_mixed(seed=4), p=1, flags=B.LORA_CACHE_FUSED_GEMV)
+    _full_parity(wl.small_mixed(seed=4, dtype="f32"), p=0, flags=B.LORA_CACHE_FUSED_GEMV)
+
+
+def test_fused_gemv_repeated_applies_of_one_plan():
+    """The ready counters of the fused launch only ever grow: apply one plan many times (as the
+    layers of an iteration do) and check the last result."""
+    B, H = _mods()
+    inst = wl.decode(seed=3)
+    pi = H.PooledInstance(inst, flags=B.LORA_CACHE_FUSED_GEMV)
+    try:
+        x, base = inst.x(0), inst.base_out(0)
+        xd = H.to_device(x, pi.dtype)
+        plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+        for rep in range(40):
+            yd = H.to_device(base, pi.dtype)
+            pi.pool.apply_plan(plan, 0, 0, xd, yd, inst.scale)
+        pi.pool.check_fault()
+        ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
+        _check(H.error_metrics(yd.float().cpu().numpy(), ref, base), "bf16", "40th apply of one plan")
+    finally:
+        pi.close()
 
 
 def test_prefill_config():
