@@ -228,9 +228,8 @@ int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void
  * Default on (1).  Turn off while capturing applies into a HIP graph. */
 int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
 
-/* Per-kernel timing for benchmarks.  While on (1), every kernel an apply launches is
- * bracketed by a pair of HIP events on the apply's stream (this serialises the kernels and
- * costs a few microseconds each, so time whole steps with timing off).
+/* Per-kernel timing for benchmarks.  While on (1), every kernel an apply launches carries a
+ * pair of HIP events that the runtime stamps with the kernel's own start and end.
  * lora_cache_read_timing waits for the recorded events, adds up the elapsed milliseconds and
  * launch counts per kernel kind since the last read, and forgets them. */
 enum {

@@ -353,34 +353,36 @@ static int rows_split(int h_in)
     return h_in <= 4096 ? 1 : (h_in <= 8192 ? 2 : 4);
 }
 
-hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st)
+hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
+                              const KernelTimer *tm)
 {
     if (n_items <= 0) return hipSuccess;
     const int w = rows_split(a.h_in);
     const dim3 grid(n_items * w), block(256);
     if (dtype == LORA_BF16) {
-        if (w == 1) hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 4>), grid, block, 0, st, a, items);
-        else if (w == 2) hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 2>), grid, block, 0, st, a, items);
-        else hipLaunchKernelGGL((gemv_shrink_kernel<__bf16, 1>), grid, block, 0, st, a, items);
+        if (w == 1) launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<__bf16, 4>, grid, block, st, a, items);
+        else if (w == 2) launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<__bf16, 2>, grid, block, st, a, items);
+        else launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<__bf16, 1>, grid, block, st, a, items);
     } else {
-        if (w == 1) hipLaunchKernelGGL((gemv_shrink_kernel<float, 4>), grid, block, 0, st, a, items);
-        else if (w == 2) hipLaunchKernelGGL((gemv_shrink_kernel<float, 2>), grid, block, 0, st, a, items);
-        else hipLaunchKernelGGL((gemv_shrink_kernel<float, 1>), grid, block, 0, st, a, items);
+        if (w == 1) launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<float, 4>, grid, block, st, a, items);
+        else if (w == 2) launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<float, 2>, grid, block, st, a, items);
+        else launch_k(tm, LORA_K_GEMV_SHRINK, gemv_shrink_kernel<float, 1>, grid, block, st, a, items);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st)
+hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
+                              const KernelTimer *tm)
 {
     if (n_items <= 0) return hipSuccess;
     const dim3 grid(n_items, (a.h_out + 1023) / 1024);
-    if (dtype == LORA_BF16) hipLaunchKernelGGL((gemv_expand_kernel<__bf16>), grid, dim3(64), 0, st, a, items);
-    else hipLaunchKernelGGL((gemv_expand_kernel<float>), grid, dim3(64), 0, st, a, items);
+    if (dtype == LORA_BF16) launch_k(tm, LORA_K_GEMV_EXPAND, gemv_expand_kernel<__bf16>, grid, dim3(64), st, a, items);
+    else launch_k(tm, LORA_K_GEMV_EXPAND, gemv_expand_kernel<float>, grid, dim3(64), st, a, items);
     return hipGetLastError();
 }
 
 hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
-                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st)
+                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm)
 {
     if (n_gs <= 0 || n_ge <= 0) return hipSuccess;
     const int w = rows_split(a.h_in);
@@ -390,7 +392,7 @@ hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, 
     const dim3 grid(n_shrink_blocks + n_expand_blocks), block(256);
     const Handover ho{counters, epoch, fault};
 #define LORA_FUSED(E, R) \
-    hipLaunchKernelGGL((gemv_fused_kernel<E, R>), grid, block, 0, st, a, gs, ge, n_shrink_blocks, n_ge, n_super, ho)
+    launch_k(tm, LORA_K_GEMV_FUSED, gemv_fused_kernel<E, R>, grid, block, st, a, gs, ge, n_shrink_blocks, n_ge, n_super, ho)
     if (dtype == LORA_BF16) {
         if (w == 1) LORA_FUSED(__bf16, 4);
         else if (w == 2) LORA_FUSED(__bf16, 2);

@@ -386,17 +386,15 @@ hipEvent_t take_event(lora_cache &c)
     return e;
 }
 
-// Runs `launch` and, when timing is on, brackets it with an event pair.
-template <typename F> hipError_t timed_launch(lora_cache &c, int kind, hipStream_t st, bool active, F launch)
+// KernelTimer callback: two events from the pool, remembered with the kernel kind.
+void timer_pair(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop)
 {
-    if (!c.timing || !active) return launch();
+    lora_cache &c = *static_cast<lora_cache *>(ctx);
     lora_cache::Timed t{kind, take_event(c), take_event(c)};
-    if (!t.start || !t.stop) return hipErrorOutOfMemory;
-    hipError_t e = hipEventRecord(t.start, st);
-    if (e == hipSuccess) e = launch();
-    if (e == hipSuccess) e = hipEventRecord(t.stop, st);
+    if (!t.start || !t.stop) return;  // the launch then goes untimed
     c.timed.push_back(t);
-    return e;
+    *start = t.start;
+    *stop = t.stop;
 }
 
 int choose_k_splits(int n_tiles, int h_in)
@@ -782,29 +780,22 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
     const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
     const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
 
+    const lora::KernelTimer timer{c, timer_pair};
+    const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
     const int splits = p->n_tiles > 0 ? choose_k_splits(p->n_tiles, a.h_in) : 1;
-    HIP_TRY(timed_launch(*c, LORA_K_ZERO, st, splits > 1,
-                         [&] { return splits > 1 ? lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st) : hipSuccess; }));
-    HIP_TRY(timed_launch(*c, LORA_K_MFMA_SHRINK, st, p->n_tiles > 0,
-                         [&] { return lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, p->tile_classes, st); }));
+    if (splits > 1) HIP_TRY(lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st, tm));
+    HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, p->tile_classes, st, tm));
     const bool fused = c->fused_gemv && p->n_gs > 0 && p->epoch < (1 << 23);
     if (fused) {
         ++p->epoch;
-        HIP_TRY(timed_launch(*c, LORA_K_GEMV_FUSED, st, true, [&] {
-            return lora::launch_gemv_fused(c->dtype, a, gs, p->n_gs, ge, p->n_ge,
-                                           reinterpret_cast<int32_t *>(p->dev + p->off_counters), p->epoch,
-                                           reinterpret_cast<int32_t *>(c->pool + c->off_fault), st);
-        }));
+        HIP_TRY(lora::launch_gemv_fused(c->dtype, a, gs, p->n_gs, ge, p->n_ge,
+                                        reinterpret_cast<int32_t *>(p->dev + p->off_counters), p->epoch,
+                                        reinterpret_cast<int32_t *>(c->pool + c->off_fault), st, tm));
     } else {
-        HIP_TRY(timed_launch(*c, LORA_K_GEMV_SHRINK, st, p->n_gs > 0,
-                             [&] { return lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st); }));
+        HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));
     }
-    HIP_TRY(timed_launch(*c, LORA_K_MFMA_EXPAND, st, p->n_tiles > 0,
-                         [&] { return lora::launch_mfma_expand(a, tiles, p->n_tiles, st); }));
-    if (!fused) {
-        HIP_TRY(timed_launch(*c, LORA_K_GEMV_EXPAND, st, p->n_ge > 0,
-                             [&] { return lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st); }));
-    }
+    HIP_TRY(lora::launch_mfma_expand(a, tiles, p->n_tiles, st, tm));
+    if (!fused) HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st, tm));
 
     const int64_t seq = ++c->apply_seq;
     ++c->stats.applies;

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "lora_cache.h"
@@ -56,20 +57,39 @@ struct ApplyArgs {
     float scale;
 };
 
-// launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16
-hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
-hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st);
+// Optional per-kernel timing: when a launch gets a KernelTimer it asks it for an event pair and
+// launches through hipExtLaunchKernelGGL, which stamps the pair with the kernel's own start and
+// end (no bracketing commands in the stream, so kernels are neither serialised nor padded).
+struct KernelTimer {
+    void *ctx;
+    void (*pair)(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop);
+};
+
+template <typename K, typename... A>
+inline void launch_k(const KernelTimer *tm, int kind, K kernel, dim3 grid, dim3 block, hipStream_t st, A... args)
+{
+    hipEvent_t s = nullptr, e = nullptr;
+    if (tm) tm->pair(tm->ctx, kind, &s, &e);
+    if (s && e) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, s, e, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+}
+
+// launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16; tm may be null
+hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
+                              const KernelTimer *tm);
+hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
+                              const KernelTimer *tm);
 // shrink and expand in one launch: expand wavefronts load their slab part at once and then wait
 // for the batch's counter (device, one int32 per batch, only ever incremented) to reach
 // epoch * rank; `fault` (device int32) is set if a wait gives up
 hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
-                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st);
+                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
 // class_mask: bit k set = some tile has ceil(rank/16) in (2^(k-1), 2^k] (k = 0: rank <= 16)
 hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
-                              hipStream_t st);
+                              hipStream_t st, const KernelTimer *tm);
 int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
-hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st);
-hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st);
+hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
+hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st, const KernelTimer *tm);
 // staged [h_in][r] / [r][h_out] -> slab layout
 hipError_t launch_repack(int dtype, const void *stage_A, const void *stage_B, void *slab, int32_t h_in, int32_t h_out,
                          int32_t rank, hipStream_t st);

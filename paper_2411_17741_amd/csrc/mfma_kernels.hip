@@ -290,12 +290,12 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float4 *p, size_t n4)
         p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st)
+hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st, const KernelTimer *tm)
 {
     if (n == 0) return hipSuccess;
     const size_t n4 = n / 4;  // callers pass multiples of 4
     const int blocks = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
-    hipLaunchKernelGGL(zero_f32_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<float4 *>(p), n4);
+    launch_k(tm, LORA_K_ZERO, zero_f32_kernel, dim3(blocks), dim3(256), st, reinterpret_cast<float4 *>(p), n4);
     return hipGetLastError();
 }
 
@@ -314,25 +314,25 @@ int mfma_shrink_splits(int h_in, int want)
 }
 
 hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
-                              hipStream_t st)
+                              hipStream_t st, const KernelTimer *tm)
 {
     if (n_tiles <= 0) return hipSuccess;
     const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
     const int splits = (a.h_in + k_len - 1) / k_len;
     const dim3 grid(n_tiles, splits), block(256);
     const int at = splits > 1 ? 1 : 0;
-    if (class_mask & 1u) hipLaunchKernelGGL((mfma_shrink_kernel<1, 128>), grid, block, 0, st, a, tiles, k_len, at);
-    if (class_mask & 2u) hipLaunchKernelGGL((mfma_shrink_kernel<2, 128>), grid, block, 0, st, a, tiles, k_len, at);
-    if (class_mask & 4u) hipLaunchKernelGGL((mfma_shrink_kernel<4, 64>), grid, block, 0, st, a, tiles, k_len, at);
-    if (class_mask & 8u) hipLaunchKernelGGL((mfma_shrink_kernel<8, 64>), grid, block, 0, st, a, tiles, k_len, at);
+    if (class_mask & 1u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<1, 128>, grid, block, st, a, tiles, k_len, at);
+    if (class_mask & 2u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<2, 128>, grid, block, st, a, tiles, k_len, at);
+    if (class_mask & 4u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<4, 64>, grid, block, st, a, tiles, k_len, at);
+    if (class_mask & 8u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<8, 64>, grid, block, st, a, tiles, k_len, at);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st)
+hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm)
 {
     if (n_tiles <= 0) return hipSuccess;
-    hipLaunchKernelGGL(mfma_expand_kernel, dim3(n_tiles, (a.h_out + EXPAND_COLS - 1) / EXPAND_COLS), dim3(256), 0, st, a,
-                       tiles);
+    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles, (a.h_out + EXPAND_COLS - 1) / EXPAND_COLS), dim3(256),
+             st, a, tiles);
     return hipGetLastError();
 }
 
