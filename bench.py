@@ -51,7 +51,7 @@ def algorithmic_bytes(inst, w, esize=2):
             "gemv_expand": esize * (sum(g.values()) * pr.h_out + 2 * ng * pr.h_out),
             "mfma_shrink": esize * (sum(t.values()) * pr.h_in + nt * pr.h_in),
             "mfma_expand": esize * (sum(t.values()) * pr.h_out + 2 * nt * pr.h_out),
-            "zero": 0,
+            "mfma_reduce": 0,
         })
         out[-1]["gemv_fused"] = out[-1]["gemv_shrink"] + out[-1]["gemv_expand"]
     return out

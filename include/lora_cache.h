@@ -233,7 +233,7 @@ int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
  * lora_cache_read_timing waits for the recorded events, adds up the elapsed milliseconds and
  * launch counts per kernel kind since the last read, and forgets them. */
 enum {
-    LORA_K_ZERO = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4,
+    LORA_K_MFMA_REDUCE = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4,
     LORA_K_GEMV_FUSED = 5, LORA_K_COUNT = 6
 };
 int lora_cache_set_timing(lora_cache_t *c, int32_t on);

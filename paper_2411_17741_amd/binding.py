@@ -271,7 +271,7 @@ def lora_apply(cache, layer: int, proj: int, x: int, base_out: int, T: int, seg_
                            _ptr(sr), len(ss), scale, c_void_p(stream or None))
 
 
-KERNEL_KINDS = ("zero", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand", "gemv_fused")
+KERNEL_KINDS = ("mfma_reduce", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand", "gemv_fused")
 
 
 def lora_cache_set_timing(cache, on: int) -> int:

@@ -26,6 +26,7 @@ constexpr int N_INTERNAL_PLANS = 4;
 constexpr int N_STAGES = 2;
 constexpr int N_APPLY_EVENTS = 64;
 constexpr size_t ALIGN = 256;
+constexpr int MAX_K_SPLITS = 8;
 
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
 int esize_of(int dtype) { return dtype == LORA_BF16 ? 2 : 4; }
@@ -62,7 +63,7 @@ struct lora_plan {
     bool upload_pending = false, use_pending = false;
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
-    unsigned tile_classes = 0;  // which rank classes the tiles fall in (see launch_mfma_shrink)
+    int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
     size_t off_tiles = 0, off_gs = 0, off_ge = 0, off_counters = 0;
     int32_t n_batches = 0;
     int32_t epoch = 0;  // applies since the upload; the fused GEMV counters stand at epoch * rank
@@ -85,7 +86,8 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
-    size_t off_fault = 0;
+    size_t off_fault = 0, off_vpart = 0;
+    int64_t vpart_rows = 0;  // rows of the k-split partial scratch
     bool fused_gemv = false;
     size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
 
@@ -191,6 +193,10 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     cur += ALIGN;
     c.off_v = cur;
     cur += align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
+    // k-split partials: splits are only used while tiles * splits stays near 512 blocks of 64 tokens
+    c.vpart_rows = c.dtype == LORA_BF16 ? std::min<int64_t>((int64_t)MAX_K_SPLITS * c.max_tokens, 640 * 64 + c.max_tokens) : 0;
+    c.off_vpart = cur;
+    cur += align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
     c.off_plans = cur;
     cur += c.plan_cap * (size_t)(c.n_user_plans + N_INTERNAL_PLANS);
     c.off_stage = cur;
@@ -298,11 +304,8 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
             std::memcpy(&items[i], &d, sizeof(d));
         }
     };
-    p.tile_classes = 0;
-    for (int i = 0; i < w.n_tiles; ++i) {
-        const int nb = (w.tiles[i].rank + 15) / 16;
-        p.tile_classes |= nb <= 1 ? 1u : nb <= 2 ? 2u : nb <= 4 ? 4u : 8u;
-    }
+    p.n_tile_tok = 0;
+    for (int i = 0; i < w.n_tiles; ++i) p.n_tile_tok += w.tiles[i].n_tok;
     // token batches are runs of items with the same tok_off, in the same order in both lists
     std::unordered_map<int32_t, int32_t> batch_of;
     for (int i = 0; i < w.n_gs_items; ++i) batch_of.emplace(w.gs_items[i].tok_off, (int32_t)batch_of.size());
@@ -397,10 +400,12 @@ void timer_pair(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop)
     *stop = t.stop;
 }
 
-int choose_k_splits(int n_tiles, int h_in)
+int choose_k_splits(const lora_cache &c, int n_tiles, int n_tile_tok, int h_in)
 {
-    // enough blocks to cover the chip about twice; the launch rounds k ranges up to 512 elements
-    const int want = std::max(1, (512 + n_tiles - 1) / n_tiles);
+    // One round of blocks (2 per CU) when there are few tiles; k ranges of at least 512 elements;
+    // and the partials of all splits must fit their scratch.
+    int want = std::max(1, std::min({512 / std::max(1, n_tiles), h_in / 512, MAX_K_SPLITS}));
+    while (want > 1 && (int64_t)lora::mfma_shrink_splits(h_in, want) * n_tile_tok > c.vpart_rows) --want;
     return lora::mfma_shrink_splits(h_in, want);
 }
 
@@ -782,9 +787,9 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
 
     const lora::KernelTimer timer{c, timer_pair};
     const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
-    const int splits = p->n_tiles > 0 ? choose_k_splits(p->n_tiles, a.h_in) : 1;
-    if (splits > 1) HIP_TRY(lora::launch_zero_f32(a.v, (size_t)p->T * c->v_stride, st, tm));
-    HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, splits, p->tile_classes, st, tm));
+    const int splits = p->n_tiles > 0 ? choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in) : 1;
+    HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, p->n_tile_tok, splits,
+                                     reinterpret_cast<float *>(c->pool + c->off_vpart), st, tm));
     const bool fused = c->fused_gemv && p->n_gs > 0 && p->epoch < (1 << 23);
     if (fused) {
         ++p->epoch;

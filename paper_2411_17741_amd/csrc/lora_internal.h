@@ -84,12 +84,12 @@ hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *ite
 // epoch * rank; `fault` (device int32) is set if a wait gives up
 hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
                              int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
-// class_mask: bit k set = some tile has ceil(rank/16) in (2^(k-1), 2^k] (k = 0: rank <= 16)
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
-                              hipStream_t st, const KernelTimer *tm);
+// n_tile_tok = tokens of all tiles (the leading part of tok_list); part = scratch for k-split
+// partials, splits * n_tile_tok rows of v_stride floats (unused when the launch does not split)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int n_tile_tok, int k_splits,
+                              float *part, hipStream_t st, const KernelTimer *tm);
 int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
-hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st, const KernelTimer *tm);
 // staged [h_in][r] / [r][h_out] -> slab layout
 hipError_t launch_repack(int dtype, const void *stage_A, const void *stage_B, void *slab, int32_t h_in, int32_t h_out,
                          int32_t rank, hipStream_t st);

@@ -12,6 +12,8 @@
 //   expand:  Y[tile][cols]^T += Bp[cols][rank] . (s.V)^T     (split over column ranges)
 //
 // (paper section 3.1: the two adapter products and the aggregation into the base output.)
+#include <type_traits>
+
 #include "lora_device.h"
 
 namespace lora {
@@ -22,150 +24,219 @@ constexpr int EXPAND_COLS = 512;                // expand: columns per block, in
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
-// shrink.  Block = 4 wavefronts on one tile and one k range; the range is cut in four and
-// every wavefront works alone on its quarter: all (up to 4) token blocks x all (up to NBMAX)
-// rank blocks, both operands loaded straight from global memory into MFMA registers -- x from
-// HBM, At from L2 -- with the next step's loads in flight while the current step multiplies.
-// No LDS and no barrier in the loop.  Per step a lane group g covers k = k0 + (KS/4)*g .. and
-// MFMA i of the step uses the i-th 8 of them.  The four partial results are summed through
-// LDS at the end.  NBMAX (1, 2, 4, 8 rank blocks of 16) is a template parameter so that small
-// ranks do not pay for the accumulators of large ones; a block leaves at once if its tile
-// belongs to another class.
+// shrink.  Block = 4 wavefronts on one tile and one k range, walked in stages of 128 k.
+//  - x, the HBM stream, goes through an LDS ring of three stages: every thread fetches four
+//    16-byte pieces per stage with a wavefront instruction covering 4 token rows x 256
+//    contiguous bytes, two stages ahead of the one being multiplied (so two stages of loads are
+//    in flight in registers while a third waits ready in LDS), one barrier per stage.  Rows are
+//    padded by 16 bytes, which puts the 16 rows of an A-operand read in distinct banks.
+//  - At, which comes out of L2 and is shared by all tiles of a segment, is loaded straight into
+//    B-operand registers one stage ahead.
+//  - From 4 rank blocks (of 16) up, wavefront w owns rank blocks w and w+4 for the whole k range
+//    and writes its part of V itself.  Below that, the wavefronts split the four MFMA k steps of
+//    a stage instead, each covering all rank blocks, and their partials are summed through LDS.
+//  - When a tile's k is split over several blocks (few tiles, many CUs), each block writes its
+//    partial to a scratch row set of its split and mfma_reduce_kernel adds the splits up.
+// Blocks are numbered so that the splits of a tile and neighbouring tiles (same segment, same
+// At) fall on one XCD: block b works on item (b % 8) * ceil(n/8) + b / 8.
 // ---------------------------------------------------------------------------------------
-template <int NBMAX, int KS>
-__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int k_len,
-                                                          int use_atomic)
+namespace {
+constexpr int SK = 128;                 // k elements per stage
+constexpr int XROW = SK * 2 + 16;       // bytes per token row of a stage in LDS
+constexpr int NSTAGE = 3;
+}  // namespace
+
+template <bool NSPLIT>
+__device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevItem &it, int k_begin, int k_end,
+                                                 float *part, unsigned char (*xs)[LORA_TILE_TOKENS * XROW])
 {
-    constexpr int NI = KS / 32;   // MFMA k steps per loop step
-    constexpr int LB = KS / 4;    // elements per lane per operand row per step
-    __shared__ __attribute__((aligned(16))) float red[2][4 * NBMAX * 4][64];
-
-    const DevItem it = tiles[blockIdx.x];
-    const int NB = (it.rank + 15) >> 4;
-    if (NB > NBMAX || (NBMAX > 1 && NB <= NBMAX / 2)) return;  // another class (uniform)
-
+    constexpr int NBW = NSPLIT ? 2 : 3;  // rank blocks a wavefront works on
+    constexpr int NKW = NSPLIT ? 4 : 1;  // MFMA k steps of a stage a wavefront works on
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int rs = rank_storage(it.rank);
+    const int NB = (it.rank + 15) >> 4;
     const int n_mb = (it.n_tok + 15) >> 4;
-    const int kq = k_len >> 2;  // k_len is a multiple of 4*KS
-    const int k_lo = blockIdx.y * k_len + w * kq;
-    const int k_hi = min(a.h_in, k_lo + kq);
-    const int n_steps = k_hi > k_lo ? (k_hi - k_lo + KS - 1) / KS : 0;
+    const int n_st = (k_end - k_begin + SK - 1) / SK;
 
     const __bf16 *At = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes);
     const __bf16 *x = static_cast<const __bf16 *>(a.x);
 
-    const __bf16 *xp[4];
+    // loader: rows 16w + 4i + lane/16, piece lane%16 (8 elements)
+    const int lp = lane & 15;
+    const __bf16 *xg[4];
+    int lds_off[4];
     bool x_ok[4];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-        const int ti = 16 * mb + m;
-        x_ok[mb] = ti < it.n_tok;
-        const int tok = x_ok[mb] ? (ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) : 0;
-        xp[mb] = x + (size_t)tok * a.h_in + LB * g;
+    for (int i = 0; i < 4; ++i) {
+        const int row = 16 * w + 4 * i + (lane >> 4);
+        x_ok[i] = row < it.n_tok;
+        const int tok = x_ok[i] ? (row == 0 ? it.tok0 : a.tok_list[it.tok_off + row]) : it.tok0;
+        xg[i] = x + (size_t)tok * a.h_in + lp * 8;
+        lds_off[i] = row * XROW + lp * 16;
     }
-    const __bf16 *ap[NBMAX];
-    bool a_ok[NBMAX];
+    // At operands: block slot q -> rank block nbq; rows past the stored rank read as zero
+    int nbq[NBW];
+    const __bf16 *ag[NBW];
+    bool a_ok[NBW];
 #pragma unroll
-    for (int nb = 0; nb < NBMAX; ++nb) {
-        const int row = 16 * nb + m;
-        a_ok[nb] = row < rs;
-        ap[nb] = At + (size_t)(a_ok[nb] ? row : 0) * a.h_in + LB * g;
+    for (int q = 0; q < NBW; ++q) {
+        nbq[q] = NSPLIT ? w + 4 * q : q;
+        const int row = 16 * nbq[q] + m;
+        a_ok[q] = nbq[q] < NB && row < rs;
+        ag[q] = At + (size_t)(a_ok[q] ? row : 0) * a.h_in + 8 * g;
     }
+    const int ks0 = NSPLIT ? 0 : w;  // first MFMA k step of a stage for this wavefront
 
-    floatx4 acc[4][NBMAX];
+    uint4 xr[2][4];
+    auto load_x = [&](int st, uint4(&d)[4]) {
+        const int k = k_begin + st * SK;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NBMAX; ++nb) acc[mb][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    uint4 xr[2][4][NI], ar[2][NBMAX][NI];
-    auto load_step = [&](int k, uint4(&xd)[4][NI], uint4(&ad)[NBMAX][NI]) {
-        // a step may stick out of the range by 64 elements when KS = 128: pieces are predicated
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-                xd[mb][i] = (x_ok[mb] && mb < n_mb && k + LB * g + 8 * i < k_hi)
-                                ? *reinterpret_cast<const uint4 *>(xp[mb] + k + 8 * i)
-                                : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int nb = 0; nb < NBMAX; ++nb)
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-                ad[nb][i] = (a_ok[nb] && nb < NB && k + LB * g + 8 * i < k_hi)
-                                ? *reinterpret_cast<const uint4 *>(ap[nb] + k + 8 * i)
-                                : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 4; ++i)
+            d[i] = (st < n_st && k + lp * 8 < k_end) ? *reinterpret_cast<const uint4 *>(xg[i] + k) : make_uint4(0, 0, 0, 0);
     };
-    auto mul_step = [&](uint4(&xd)[4][NI], uint4(&ad)[NBMAX][NI]) {
+    auto store_x = [&](int st, const uint4(&d)[4]) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i)
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<uint4 *>(&xs[st % NSTAGE][lds_off[i]]) = x_ok[i] ? d[i] : make_uint4(0, 0, 0, 0);
+    };
+    uint4 br[2][NBW][NKW];
+    auto load_at = [&](int st, uint4(&d)[NBW][NKW]) {
+        const int k = k_begin + st * SK;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                if (mb < n_mb) {
-                    const bf16x8 av = __builtin_bit_cast(bf16x8, xd[mb][i]);
+        for (int q = 0; q < NBW; ++q)
 #pragma unroll
-                    for (int nb = 0; nb < NBMAX; ++nb)
-                        if (nb < NB)
-                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                av, __builtin_bit_cast(bf16x8, ad[nb][i]), acc[mb][nb], 0, 0, 0);
-                }
+            for (int j = 0; j < NKW; ++j) {
+                const int kk = k + 32 * (ks0 + j);
+                d[q][j] = (a_ok[q] && st < n_st && kk + 8 * g < k_end) ? *reinterpret_cast<const uint4 *>(ag[q] + kk)
+                                                                       : make_uint4(0, 0, 0, 0);
             }
     };
 
-    if (n_steps > 0) load_step(k_lo, xr[0], ar[0]);
-    for (int sidx = 0; sidx < n_steps; sidx += 2) {
-        if (sidx + 1 < n_steps) load_step(k_lo + (sidx + 1) * KS, xr[1], ar[1]);
-        mul_step(xr[0], ar[0]);
-        if (sidx + 2 < n_steps) load_step(k_lo + (sidx + 2) * KS, xr[0], ar[0]);
-        if (sidx + 1 < n_steps) mul_step(xr[1], ar[1]);
+    floatx4 acc[4][NBW];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int q = 0; q < NBW; ++q) acc[mb][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    load_x(0, xr[0]);
+    load_x(1, xr[1]);
+    load_at(0, br[0]);
+    store_x(0, xr[0]);
+    load_x(2, xr[0]);
+    __syncthreads();
+
+    // one stage; CUR = st & 1 is a compile-time constant so that the staging arrays stay in registers
+    auto stage = [&](auto cur_tag, int st) {
+        constexpr int CUR = decltype(cur_tag)::value;
+        load_at(st + 1, br[CUR ^ 1]);  // At of the next stage, then this stage's products
+        const unsigned char *xb = xs[st % NSTAGE];
+#pragma unroll
+        for (int j = 0; j < NKW; ++j) {
+            const int ks = ks0 + j;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                if (mb < n_mb) {
+                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(&xb[(16 * mb + m) * XROW + (4 * ks + g) * 16]);
+#pragma unroll
+                    for (int q = 0; q < NBW; ++q)
+                        if (nbq[q] < NB)
+                            acc[mb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                av, __builtin_bit_cast(bf16x8, br[CUR][q][j]), acc[mb][q], 0, 0, 0);
+                }
+            }
+        }
+        // stage st+1 goes to LDS (its buffer was last read two barriers ago), stage st+3 is requested
+        store_x(st + 1, xr[CUR ^ 1]);
+        load_x(st + 3, xr[CUR ^ 1]);
+        __syncthreads();
+    };
+    for (int st = 0; st < n_st; st += 2) {
+        stage(std::integral_constant<int, 0>{}, st);
+        if (st + 1 < n_st) stage(std::integral_constant<int, 1>{}, st + 1);
     }
 
-    // sum the four wavefronts' partials: 2,3 -> LDS -> 0,1 add; 1 -> LDS -> 0 adds and writes
-    auto spill = [&](int slot) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NBMAX; ++nb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) red[slot][(mb * NBMAX + nb) * 4 + r][lane] = acc[mb][nb][r];
-    };
-    auto absorb = [&](int slot) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NBMAX; ++nb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[mb][nb][r] += red[slot][(mb * NBMAX + nb) * 4 + r][lane];
-    };
-    if (w >= 2) spill(w - 2);
-    __syncthreads();
-    if (w < 2) absorb(w);
-    __syncthreads();
-    if (w == 1) spill(0);
-    __syncthreads();
-    if (w != 0) return;
-    absorb(0);
-
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
+    auto write_v = [&](int mb, int q, const floatx4 &val) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int ti = 16 * mb + 4 * g + r;
-            if (ti < it.n_tok) {
-                float *vr = a.v + (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride;
+            const int ti = 16 * mb + 4 * g + r, jr = 16 * nbq[q] + m;
+            if (ti < it.n_tok && jr < it.rank) {
+                // whole k range in this block: the result itself; else this split's partial, one row
+                // per position in tok_list (mfma_reduce_kernel adds the splits up)
+                if (part) part[(size_t)(it.tok_off + ti) * a.v_stride + jr] = val[r];
+                else a.v[(size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride + jr] = val[r];
+            }
+        }
+    };
+    if (NSPLIT) {
 #pragma unroll
-                for (int nb = 0; nb < NBMAX; ++nb) {
-                    const int jr = 16 * nb + m;
-                    if (nb < NB && jr < it.rank) {
-                        if (use_atomic) unsafeAtomicAdd(vr + jr, acc[mb][nb][r]);
-                        else vr[jr] = acc[mb][nb][r];
-                    }
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int q = 0; q < NBW; ++q)
+                if (mb < n_mb && nbq[q] < NB) write_v(mb, q, acc[mb][q]);
+    } else {
+        // the four wavefronts hold partial sums over k: park them in the (now idle) x ring and let
+        // wavefront w add up and write token block w
+        float *red = reinterpret_cast<float *>(&xs[0][0]);  // [wave][mb][q][r][lane], 4*4*3*4*64*4 B = 48 KB
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int q = 0; q < NBW; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) red[(((w * 4 + mb) * NBW + q) * 4 + r) * 64 + lane] = acc[mb][q][r];
+        __syncthreads();
+        if (w < n_mb) {
+#pragma unroll
+            for (int q = 0; q < NBW; ++q) {
+                if (nbq[q] < NB) {
+                    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int src = 0; src < 4; ++src)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sum[r] += red[(((src * 4 + w) * NBW + q) * 4 + r) * 64 + lane];
+                    write_v(w, q, sum);
                 }
             }
         }
     }
+}
+
+__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_tiles,
+                                                          int splits, int k_len, float *part, int n_tile_tok)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char xs[NSTAGE][LORA_TILE_TOKENS * XROW];
+    static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the k-split reduction reuses the x ring");
+
+    const int n_items = n_tiles * splits;
+    const int per_xcd = (n_items + 7) >> 3;
+    const int item = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (item >= n_items) return;  // uniform
+    const int tile = item / splits, split = item - tile * splits;
+    const DevItem it = tiles[tile];
+    const int k_begin = split * k_len;
+    const int k_end = min(a.h_in, k_begin + k_len);
+    if (k_begin >= k_end) return;
+    float *my_part = splits > 1 ? part + (size_t)split * n_tile_tok * a.v_stride : nullptr;
+    if (it.rank > 48) mfma_shrink_body<true>(a, it, k_begin, k_end, my_part, xs);
+    else mfma_shrink_body<false>(a, it, k_begin, k_end, my_part, xs);
+}
+
+// V[token][0..rank) = sum over the k splits of the partials.  One block per tile.  (Atomic adds
+// into V instead cost about 30 us per launch: device-scope fp32 atomics execute at the memory side.)
+__global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int splits,
+                                                          const float *__restrict__ part, int n_tile_tok)
+{
+    // 8 blocks per tile, 8 tokens each; a thread sums one float4 column of one token
+    const DevItem it = tiles[blockIdx.x >> 3];
+    const int ti = (blockIdx.x & 7) * 8 + (threadIdx.x >> 5), j4 = threadIdx.x & 31;
+    if (ti >= it.n_tok || j4 * 4 >= rank_storage(it.rank)) return;  // entries past the rank are never used
+    const float4 *src = reinterpret_cast<const float4 *>(part + (size_t)(it.tok_off + ti) * a.v_stride) + j4;
+    float4 sum = src[0];
+    for (int sp = 1; sp < splits; ++sp) {
+        const float4 v = src[(size_t)sp * n_tile_tok * (a.v_stride >> 2)];
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    reinterpret_cast<float4 *>(a.v + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride)[j4] = sum;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -192,6 +263,42 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
 
+    // token rows this lane reads/writes in the epilogue: 32*th + 16*tb + m
+    size_t yoff[2];
+    bool yok[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int ti = 32 * th + 16 * tb + m;
+        yok[tb] = ti < it.n_tok;
+        yoff[tb] = (size_t)((yok[tb] && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.h_out;
+    }
+    const bool tb1_live = 32 * th + 16 < it.n_tok;
+    const bool half_live = 32 * th < it.n_tok;
+    constexpr int N_PASS = EXPAND_COLS / 128;
+    const int col0 = blockIdx.y * EXPAND_COLS + 64 * ch;
+
+    // base_out of pass `cp` (unconditional loads from clamped, valid addresses)
+    auto load_y = [&](int cp, uint4(&d)[2][2]) {
+        const int nw0 = min(col0 + cp * 128, a.h_out - 64);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) d[tb][h] = *reinterpret_cast<const uint4 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h);
+    };
+    // Bp operands of k step `ks` of the pass starting at column nw0
+    auto load_b = [&](int nw0, int ks, uint4(&d)[4]) {
+        const int j8 = 4 * ks + g;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int n = nw0 + 8 * (m >> 2) + 4 * (b & 1) + (m & 3) + 32 * (b >> 1);
+            d[b] = (ks < KS && j8 < rs8) ? *reinterpret_cast<const uint4 *>(Bp + ((size_t)j8 * a.h_out + n) * 8)
+                                         : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    uint4 yr[2][2][2];
+    load_y(0, yr[0]);  // the first pass's base_out is on its way while V is staged
+
     // stage s.V as bf16: vs[token][rank]
     for (int idx = tid; idx < LORA_TILE_TOKENS * c8; idx += 256) {
         const int ti = idx / c8, j8 = idx - ti * c8;
@@ -211,30 +318,13 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     }
     __syncthreads();
 
-    if (32 * th >= it.n_tok) return;  // this token half is empty (no barrier follows)
+    if (!half_live) return;  // this token half is empty (no barrier follows)
 
-    // token rows this lane reads/writes in the epilogue: 32*th + 16*tb + m
-    size_t yoff[2];
-    bool yok[2];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int ti = 32 * th + 16 * tb + m;
-        yok[tb] = ti < it.n_tok;
-        yoff[tb] = yok[tb] ? (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.h_out : 0;
-    }
-    const bool tb1_live = 32 * th + 16 < it.n_tok;
-
-    for (int cp = 0; cp < EXPAND_COLS / 128; ++cp) {
-        const int nw0 = blockIdx.y * EXPAND_COLS + cp * 128 + 64 * ch;
+    for (int cp = 0; cp < N_PASS; ++cp) {
+        const int nw0 = col0 + cp * 128;
         if (nw0 >= a.h_out) break;
-
-        uint4 yr[2][2];
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                yr[tb][h] = yok[tb] ? *reinterpret_cast<const uint4 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h)
-                                    : make_uint4(0, 0, 0, 0);
+        if (cp + 1 < N_PASS) load_y(cp + 1, yr[(cp + 1) & 1]);  // next pass's base_out, ahead of this pass's products
 
         floatx4 acc[4][2];
 #pragma unroll
@@ -242,23 +332,22 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) acc[b][tb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-        for (int ks = 0; ks < KS; ++ks) {
-            const int j8 = 4 * ks + g;
-            bf16x8 aop[4], bop[2];
+        uint4 br[2][4];
+        load_b(nw0, 0, br[0]);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int n = nw0 + 8 * (m >> 2) + 4 * (b & 1) + (m & 3) + 32 * (b >> 1);
-                uint4 raw = make_uint4(0, 0, 0, 0);
-                if (j8 < rs8) raw = *reinterpret_cast<const uint4 *>(Bp + ((size_t)j8 * a.h_out + n) * 8);
-                aop[b] = __builtin_bit_cast(bf16x8, raw);
-            }
+        for (int ks = 0; ks < LORA_MAX_RANK / 32; ++ks) {
+            if (ks < KS) {
+                load_b(nw0, ks + 1, br[(ks + 1) & 1]);
+                bf16x8 bop[2];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-                bop[tb] = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + 16 * tb + m) * VS_ROW + j8 * 16]);
+                for (int tb = 0; tb < 2; ++tb)
+                    bop[tb] = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + 16 * tb + m) * VS_ROW + (4 * ks + g) * 16]);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[b], bop[0], acc[b][0], 0, 0, 0);
-                if (tb1_live) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[b], bop[1], acc[b][1], 0, 0, 0);
+                for (int b = 0; b < 4; ++b) {
+                    const bf16x8 aop = __builtin_bit_cast(bf16x8, br[ks & 1][b]);
+                    acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[0], acc[b][0], 0, 0, 0);
+                    if (tb1_live) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[1], acc[b][1], 0, 0, 0);
+                }
             }
         }
 
@@ -269,7 +358,7 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
                 for (int h = 0; h < 2; ++h) {
                     float f[8];
                     Chunk<__bf16> c;
-                    c.v = yr[tb][h];
+                    c.v = yr[cp & 1][tb][h];
                     unpack_chunk(c, f);
                     bf16x8 o;
 #pragma unroll
@@ -284,26 +373,11 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     }
 }
 
-__global__ __launch_bounds__(256) void zero_f32_kernel(float4 *p, size_t n4)
-{
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256)
-        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
-hipError_t launch_zero_f32(float *p, size_t n, hipStream_t st, const KernelTimer *tm)
-{
-    if (n == 0) return hipSuccess;
-    const size_t n4 = n / 4;  // callers pass multiples of 4
-    const int blocks = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
-    launch_k(tm, LORA_K_ZERO, zero_f32_kernel, dim3(blocks), dim3(256), st, reinterpret_cast<float4 *>(p), n4);
-    return hipGetLastError();
-}
-
-// k ranges are multiples of 512 elements: four wavefronts x one 128-element step.
+// k ranges are multiples of the 128-element stage.
 static int shrink_k_len(int h_in, int want)
 {
     int k_len = (h_in + want - 1) / want;
-    return (k_len + 511) / 512 * 512;
+    return (k_len + SK - 1) / SK * SK;
 }
 
 int mfma_shrink_splits(int h_in, int want)
@@ -313,18 +387,19 @@ int mfma_shrink_splits(int h_in, int want)
     return (h_in + k_len - 1) / k_len;
 }
 
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int k_splits, unsigned class_mask,
-                              hipStream_t st, const KernelTimer *tm)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int n_tile_tok, int k_splits,
+                              float *part, hipStream_t st, const KernelTimer *tm)
 {
     if (n_tiles <= 0) return hipSuccess;
     const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
     const int splits = (a.h_in + k_len - 1) / k_len;
-    const dim3 grid(n_tiles, splits), block(256);
-    const int at = splits > 1 ? 1 : 0;
-    if (class_mask & 1u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<1, 128>, grid, block, st, a, tiles, k_len, at);
-    if (class_mask & 2u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<2, 128>, grid, block, st, a, tiles, k_len, at);
-    if (class_mask & 4u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<4, 64>, grid, block, st, a, tiles, k_len, at);
-    if (class_mask & 8u) launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel<8, 64>, grid, block, st, a, tiles, k_len, at);
+    const int n_items = n_tiles * splits;
+    const int blocks = ((n_items + 7) / 8) * 8;  // 8 equal XCD shares
+    launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(blocks), dim3(256), st, a, tiles, n_tiles, splits, k_len,
+             part, n_tile_tok);
+    if (splits > 1)
+        launch_k(tm, LORA_K_MFMA_REDUCE, mfma_reduce_kernel, dim3(n_tiles * 8), dim3(256), st, a, tiles, splits, (const float *)part,
+                 n_tile_tok);
     return hipGetLastError();
 }
 
