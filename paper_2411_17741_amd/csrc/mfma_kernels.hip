@@ -243,14 +243,22 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, const Dev
 // expand.  Block = 4 wavefronts, tile of up to 64 tokens x EXPAND_COLS columns in passes of
 // 128 columns; wavefront w owns token half w&1 and column half w>>1 of a pass (32 tokens x 64
 // columns).  The scaled V tile is staged once in LDS as bf16.  The product is formed
-// transposed (rows = output columns, columns = tokens) so that a lane ends up with runs of 8
-// consecutive output columns of one token: block b of the 4 column blocks maps MFMA row
-// 4q+r to column 8q + 4(b&1) + r + 32(b>>1), which makes the read-modify-write of base_out a
-// pair of 16-byte accesses per lane and token, 64 contiguous bytes per row across a lane group.
+// transposed (rows = output columns, columns = tokens): MFMA row r of column block b is column
+// 16b + r, so the 16 lanes of a Bp operand load read 256 contiguous bytes.
+// The read-modify-write of base_out does not use the MFMA register layout (a lane would touch
+// 16 bytes of each of many rows, and every 128-byte line would be fetched by two instructions,
+// which stalls L1 on the second): the wavefront parks its fp32 products in LDS and goes over
+// base_out with 8 lanes per token row, whole 128-byte lines per instruction, for the load (issued
+// one pass ahead), the add and the store.
 // ---------------------------------------------------------------------------------------
+namespace {
+constexpr int CS_ROW = 64 * 4 + 16;  // bytes per token row of a wavefront's parked products (padded)
+}
+
 __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles)
 {
     __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
+    __shared__ __attribute__((aligned(16))) unsigned char cs[4][32 * CS_ROW];
 
     const DevItem it = tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -263,14 +271,15 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
 
-    // token rows this lane reads/writes in the epilogue: 32*th + 16*tb + m
-    size_t yoff[2];
-    bool yok[2];
+    // read-modify-write layout: instruction i covers token rows 32*th + 8*i + lane/8, 8 columns at 8*(lane%8)
+    const int rt = lane >> 3, rc = lane & 7;
+    size_t yoff[4];
+    bool yok[4];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int ti = 32 * th + 16 * tb + m;
-        yok[tb] = ti < it.n_tok;
-        yoff[tb] = (size_t)((yok[tb] && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.h_out;
+    for (int i = 0; i < 4; ++i) {
+        const int ti = 32 * th + 8 * i + rt;
+        yok[i] = ti < it.n_tok;
+        yoff[i] = (size_t)((yok[i] && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.h_out + rc * 8;
     }
     const bool tb1_live = 32 * th + 16 < it.n_tok;
     const bool half_live = 32 * th < it.n_tok;
@@ -278,25 +287,21 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     const int col0 = blockIdx.y * EXPAND_COLS + 64 * ch;
 
     // base_out of pass `cp` (unconditional loads from clamped, valid addresses)
-    auto load_y = [&](int cp, uint4(&d)[2][2]) {
+    auto load_y = [&](int cp, uint4(&d)[4]) {
         const int nw0 = min(col0 + cp * 128, a.h_out - 64);
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) d[tb][h] = *reinterpret_cast<const uint4 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h);
+        for (int i = 0; i < 4; ++i) d[i] = *reinterpret_cast<const uint4 *>(y + yoff[i] + nw0);
     };
-    // Bp operands of k step `ks` of the pass starting at column nw0
+    // Bp operands of k step `ks` of the pass starting at column nw0: block b = columns nw0 + 16b ..
     auto load_b = [&](int nw0, int ks, uint4(&d)[4]) {
         const int j8 = 4 * ks + g;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int n = nw0 + 8 * (m >> 2) + 4 * (b & 1) + (m & 3) + 32 * (b >> 1);
-            d[b] = (ks < KS && j8 < rs8) ? *reinterpret_cast<const uint4 *>(Bp + ((size_t)j8 * a.h_out + n) * 8)
+        for (int b = 0; b < 4; ++b)
+            d[b] = (ks < KS && j8 < rs8) ? *reinterpret_cast<const uint4 *>(Bp + ((size_t)j8 * a.h_out + nw0 + 16 * b + m) * 8)
                                          : make_uint4(0, 0, 0, 0);
-        }
     };
 
-    uint4 yr[2][2][2];
+    uint4 yr[2][4];
     load_y(0, yr[0]);  // the first pass's base_out is on its way while V is staged
 
     // stage s.V as bf16: vs[token][rank]
@@ -319,6 +324,7 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     __syncthreads();
 
     if (!half_live) return;  // this token half is empty (no barrier follows)
+    unsigned char *my_cs = cs[w];
 
 #pragma unroll
     for (int cp = 0; cp < N_PASS; ++cp) {
@@ -351,25 +357,31 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
             }
         }
 
+        // park the products: lane (g, m) holds, for block b and token block tb, columns 16b + 4g .. +3 of token 16tb + m
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            if (yok[tb]) {
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    float f[8];
-                    Chunk<__bf16> c;
-                    c.v = yr[cp & 1][tb][h];
-                    unpack_chunk(c, f);
-                    bf16x8 o;
+            for (int tb = 0; tb < 2; ++tb)
+                *reinterpret_cast<floatx4 *>(&my_cs[(16 * tb + m) * CS_ROW + (16 * b + 4 * g) * 4]) = acc[b][tb];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // a wavefront's LDS operations execute in order
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        o[r] = (__bf16)(f[r] + acc[2 * h][tb][r]);
-                        o[4 + r] = (__bf16)(f[4 + r] + acc[2 * h + 1][tb][r]);
-                    }
-                    *reinterpret_cast<bf16x8 *>(y + yoff[tb] + nw0 + 8 * g + 32 * h) = o;
-                }
+        for (int i = 0; i < 4; ++i) {
+            if (yok[i]) {
+                const float4 p0 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32]);
+                const float4 p1 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32 + 16]);
+                float f[8];
+                Chunk<__bf16> c;
+                c.v = yr[cp & 1][i];
+                unpack_chunk(c, f);
+                bf16x8 o;
+                o[0] = (__bf16)(f[0] + p0.x); o[1] = (__bf16)(f[1] + p0.y); o[2] = (__bf16)(f[2] + p0.z); o[3] = (__bf16)(f[3] + p0.w);
+                o[4] = (__bf16)(f[4] + p1.x); o[5] = (__bf16)(f[5] + p1.y); o[6] = (__bf16)(f[6] + p1.z); o[7] = (__bf16)(f[7] + p1.w);
+                *reinterpret_cast<bf16x8 *>(y + yoff[i] + nw0) = o;
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the next pass overwrites the parked products
     }
 }
 
