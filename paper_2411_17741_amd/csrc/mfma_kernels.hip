@@ -20,7 +20,6 @@ namespace lora {
 
 namespace {
 constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the staged V tile (padded)
-constexpr int EXPAND_COLS = 512;                // expand: columns per block, in passes of 128
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
@@ -46,21 +45,33 @@ constexpr int XROW = SK * 2 + 16;       // bytes per token row of a stage in LDS
 constexpr int NSTAGE = 3;
 }  // namespace
 
-template <bool NSPLIT>
-__device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevItem &it, int k_begin, int k_end,
+// Every global load below is unconditional, from an address clamped into the tensor, and what
+// must not count is zeroed where x is written to LDS (zero x rows and zero x tail columns make
+// whatever At held there irrelevant).  Loads under a condition would be compiled into branches,
+// and the wait counters cannot be tracked across those: every stage would then wait for all
+// outstanding loads and the prefetch distance would collapse to nothing.
+template <bool NSPLIT, int NBW>  // NBW: rank blocks (of 16) a wavefront works on
+__device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevItem &it, int k_begin, int k_end, int phase,
                                                  float *part, unsigned char (*xs)[LORA_TILE_TOKENS * XROW])
 {
-    constexpr int NBW = NSPLIT ? 2 : 3;  // rank blocks a wavefront works on
     constexpr int NKW = NSPLIT ? 4 : 1;  // MFMA k steps of a stage a wavefront works on
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int rs = rank_storage(it.rank);
-    const int NB = (it.rank + 15) >> 4;
-    const int n_mb = (it.n_tok + 15) >> 4;
     const int n_st = (k_end - k_begin + SK - 1) / SK;
+    const int k_last = a.h_in - 8;  // last 16-byte piece of a row
 
     const __bf16 *At = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes);
     const __bf16 *x = static_cast<const __bf16 *>(a.x);
+
+    // k offset of stage st.  The walk over k starts at a different stage in every block, so that
+    // blocks running side by side do not all pull the same column window (rows lie h_in apart)
+    auto stage_k = [&](int st) {
+        int s = st + phase;
+        s -= s >= n_st ? n_st : 0;
+        s -= s >= n_st ? n_st : 0;  // st runs up to n_st + 2 for the prefetches past the end
+        return k_begin + s * SK;
+    };
 
     // loader: rows 16w + 4i + lane/16, piece lane%16 (8 elements)
     const int lp = lane & 15;
@@ -72,45 +83,39 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
         const int row = 16 * w + 4 * i + (lane >> 4);
         x_ok[i] = row < it.n_tok;
         const int tok = x_ok[i] ? (row == 0 ? it.tok0 : a.tok_list[it.tok_off + row]) : it.tok0;
-        xg[i] = x + (size_t)tok * a.h_in + lp * 8;
+        xg[i] = x + (size_t)tok * a.h_in;
         lds_off[i] = row * XROW + lp * 16;
     }
-    // At operands: block slot q -> rank block nbq; rows past the stored rank read as zero
+    // At operands: block slot q -> rank block nbq; rows past the stored rank are clamped (their
+    // results are never written)
     int nbq[NBW];
     const __bf16 *ag[NBW];
-    bool a_ok[NBW];
 #pragma unroll
     for (int q = 0; q < NBW; ++q) {
         nbq[q] = NSPLIT ? w + 4 * q : q;
-        const int row = 16 * nbq[q] + m;
-        a_ok[q] = nbq[q] < NB && row < rs;
-        ag[q] = At + (size_t)(a_ok[q] ? row : 0) * a.h_in + 8 * g;
+        ag[q] = At + (size_t)min(16 * nbq[q] + m, rs - 1) * a.h_in;
     }
     const int ks0 = NSPLIT ? 0 : w;  // first MFMA k step of a stage for this wavefront
 
     uint4 xr[2][4];
     auto load_x = [&](int st, uint4(&d)[4]) {
-        const int k = k_begin + st * SK;
+        const int k = min(stage_k(st) + lp * 8, k_last);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            d[i] = (st < n_st && k + lp * 8 < k_end) ? *reinterpret_cast<const uint4 *>(xg[i] + k) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 4; ++i) d[i] = *reinterpret_cast<const uint4 *>(xg[i] + k);
     };
-    auto store_x = [&](int st, const uint4(&d)[4]) {
+    auto store_x = [&](int slot, int st, const uint4(&d)[4]) {
+        const bool k_ok = stage_k(st) + lp * 8 < k_end;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4 *>(&xs[st % NSTAGE][lds_off[i]]) = x_ok[i] ? d[i] : make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(&xs[slot][lds_off[i]]) = (x_ok[i] && k_ok) ? d[i] : make_uint4(0, 0, 0, 0);
     };
     uint4 br[2][NBW][NKW];
     auto load_at = [&](int st, uint4(&d)[NBW][NKW]) {
-        const int k = k_begin + st * SK;
+        const int k = stage_k(st) + 8 * g;
 #pragma unroll
         for (int q = 0; q < NBW; ++q)
 #pragma unroll
-            for (int j = 0; j < NKW; ++j) {
-                const int kk = k + 32 * (ks0 + j);
-                d[q][j] = (a_ok[q] && st < n_st && kk + 8 * g < k_end) ? *reinterpret_cast<const uint4 *>(ag[q] + kk)
-                                                                       : make_uint4(0, 0, 0, 0);
-            }
+            for (int j = 0; j < NKW; ++j) d[q][j] = *reinterpret_cast<const uint4 *>(ag[q] + min(k + 32 * (ks0 + j), k_last));
     };
 
     floatx4 acc[4][NBW];
@@ -122,38 +127,41 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     load_x(0, xr[0]);
     load_x(1, xr[1]);
     load_at(0, br[0]);
-    store_x(0, xr[0]);
+    store_x(0, 0, xr[0]);
     load_x(2, xr[0]);
     __syncthreads();
 
-    // one stage; CUR = st & 1 is a compile-time constant so that the staging arrays stay in registers
-    auto stage = [&](auto cur_tag, int st) {
+    // one stage; CUR = st % 2 and SLOT = st % 3 are compile-time constants so that the staging
+    // arrays stay in registers and the ring slots are fixed addresses
+    auto stage = [&](auto cur_tag, auto slot_tag, int st) {
         constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int SLOT = decltype(slot_tag)::value;
         load_at(st + 1, br[CUR ^ 1]);  // At of the next stage, then this stage's products
-        const unsigned char *xb = xs[st % NSTAGE];
+        const unsigned char *xb = xs[SLOT];
 #pragma unroll
         for (int j = 0; j < NKW; ++j) {
             const int ks = ks0 + j;
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
-                if (mb < n_mb) {
-                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(&xb[(16 * mb + m) * XROW + (4 * ks + g) * 16]);
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(&xb[(16 * mb + m) * XROW + (4 * ks + g) * 16]);
 #pragma unroll
-                    for (int q = 0; q < NBW; ++q)
-                        if (nbq[q] < NB)
-                            acc[mb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                av, __builtin_bit_cast(bf16x8, br[CUR][q][j]), acc[mb][q], 0, 0, 0);
-                }
+                for (int q = 0; q < NBW; ++q)
+                    acc[mb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, br[CUR][q][j]),
+                                                                         acc[mb][q], 0, 0, 0);
             }
         }
         // stage st+1 goes to LDS (its buffer was last read two barriers ago), stage st+3 is requested
-        store_x(st + 1, xr[CUR ^ 1]);
+        store_x((SLOT + 1) % NSTAGE, st + 1, xr[CUR ^ 1]);
         load_x(st + 3, xr[CUR ^ 1]);
         __syncthreads();
     };
-    for (int st = 0; st < n_st; st += 2) {
-        stage(std::integral_constant<int, 0>{}, st);
-        if (st + 1 < n_st) stage(std::integral_constant<int, 1>{}, st + 1);
+    for (int st = 0; st < n_st; st += 6) {
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, st);
+        if (st + 1 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, st + 1);
+        if (st + 2 < n_st) stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{}, st + 2);
+        if (st + 3 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, st + 3);
+        if (st + 4 < n_st) stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, st + 4);
+        if (st + 5 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, st + 5);
     }
 
     auto write_v = [&](int mb, int q, const floatx4 &val) {
@@ -172,12 +180,11 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int q = 0; q < NBW; ++q)
-                if (mb < n_mb && nbq[q] < NB) write_v(mb, q, acc[mb][q]);
+            for (int q = 0; q < NBW; ++q) write_v(mb, q, acc[mb][q]);
     } else {
         // the four wavefronts hold partial sums over k: park them in the (now idle) x ring and let
         // wavefront w add up and write token block w
-        float *red = reinterpret_cast<float *>(&xs[0][0]);  // [wave][mb][q][r][lane], 4*4*3*4*64*4 B = 48 KB
+        float *red = reinterpret_cast<float *>(&xs[0][0]);  // [wave][mb][q][r][lane], at most 4*4*3*4*64*4 B = 48 KB
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -185,18 +192,14 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
 #pragma unroll
                 for (int r = 0; r < 4; ++r) red[(((w * 4 + mb) * NBW + q) * 4 + r) * 64 + lane] = acc[mb][q][r];
         __syncthreads();
-        if (w < n_mb) {
 #pragma unroll
-            for (int q = 0; q < NBW; ++q) {
-                if (nbq[q] < NB) {
-                    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < NBW; ++q) {
+            floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int src = 0; src < 4; ++src)
+            for (int src = 0; src < 4; ++src)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) sum[r] += red[(((src * 4 + w) * NBW + q) * 4 + r) * 64 + lane];
-                    write_v(w, q, sum);
-                }
-            }
+                for (int r = 0; r < 4; ++r) sum[r] += red[(((src * 4 + w) * NBW + q) * 4 + r) * 64 + lane];
+            write_v(w, q, sum);
         }
     }
 }
@@ -216,9 +219,15 @@ __global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const Dev
     const int k_begin = split * k_len;
     const int k_end = min(a.h_in, k_begin + k_len);
     if (k_begin >= k_end) return;
+    const int n_st = (k_end - k_begin + SK - 1) / SK;
+    const int phase = (int)(((unsigned)item * 5u) % (unsigned)n_st);
     float *my_part = splits > 1 ? part + (size_t)split * n_tile_tok * a.v_stride : nullptr;
-    if (it.rank > 48) mfma_shrink_body<true>(a, it, k_begin, k_end, my_part, xs);
-    else mfma_shrink_body<false>(a, it, k_begin, k_end, my_part, xs);
+    const int NB = (it.rank + 15) >> 4;
+    if (NB > 4) mfma_shrink_body<true, 2>(a, it, k_begin, k_end, phase, my_part, xs);
+    else if (NB == 4) mfma_shrink_body<true, 1>(a, it, k_begin, k_end, phase, my_part, xs);
+    else if (NB == 3) mfma_shrink_body<false, 3>(a, it, k_begin, k_end, phase, my_part, xs);
+    else if (NB == 2) mfma_shrink_body<false, 2>(a, it, k_begin, k_end, phase, my_part, xs);
+    else mfma_shrink_body<false, 1>(a, it, k_begin, k_end, phase, my_part, xs);
 }
 
 // V[token][0..rank) = sum over the k splits of the partials.  One block per tile.  (Atomic adds
@@ -240,8 +249,9 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, const Dev
 }
 
 // ---------------------------------------------------------------------------------------
-// expand.  Block = 4 wavefronts, tile of up to 64 tokens x EXPAND_COLS columns in passes of
-// 128 columns; wavefront w owns token half w&1 and column half w>>1 of a pass (32 tokens x 64
+// expand.  Block = 4 wavefronts, tile of up to 64 tokens x (128 * n_pass) columns in passes of
+// 128 columns (the launcher picks n_pass: long column runs per block amortise the staging of V
+// when there are many tiles, short ones keep the chip full when there are few); wavefront w owns token half w&1 and column half w>>1 of a pass (32 tokens x 64
 // columns).  The scaled V tile is staged once in LDS as bf16.  The product is formed
 // transposed (rows = output columns, columns = tokens): MFMA row r of column block b is column
 // 16b + r, so the 16 lanes of a Bp operand load read 256 contiguous bytes.
@@ -250,23 +260,24 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, const Dev
 // which stalls L1 on the second): the wavefront parks its fp32 products in LDS and goes over
 // base_out with 8 lanes per token row, whole 128-byte lines per instruction, for the load (issued
 // one pass ahead), the add and the store.
+// Register use is held to three blocks per CU (the V operands are re-read from LDS in every pass
+// rather than kept): with two, short launches of a few hundred blocks leave CUs idle at the end.
 // ---------------------------------------------------------------------------------------
 namespace {
 constexpr int CS_ROW = 64 * 4 + 16;  // bytes per token row of a wavefront's parked products (padded)
 }
 
-__global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles)
+// KS: MFMA k steps of 32 ranks.  As in the shrink, global loads are unconditional from clamped
+// addresses: rank chunks past the stored rank re-read the last stored chunk and meet zeros in V.
+template <int KS>
+__device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevItem &it, int n_pass, unsigned char *vs,
+                                                 unsigned char (*cs)[32 * CS_ROW])
 {
-    __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
-    __shared__ __attribute__((aligned(16))) unsigned char cs[4][32 * CS_ROW];
-
-    const DevItem it = tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int th = w & 1, ch = w >> 1;
     const int rs = rank_storage(it.rank), rs8 = rs >> 3;
-    const int KS = (it.rank + 31) >> 5;  // MFMA k steps of 32 ranks
-    const int c8 = KS * 4;               // staged chunks (8 ranks) per token
+    constexpr int c8 = KS * 4;  // staged chunks (8 ranks) per token
     const float s = a.scale * it.alpha;
     const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
@@ -281,44 +292,42 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
         yok[i] = ti < it.n_tok;
         yoff[i] = (size_t)((yok[i] && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.h_out + rc * 8;
     }
-    const bool tb1_live = 32 * th + 16 < it.n_tok;
     const bool half_live = 32 * th < it.n_tok;
-    constexpr int N_PASS = EXPAND_COLS / 128;
-    const int col0 = blockIdx.y * EXPAND_COLS + 64 * ch;
+    const int col0 = blockIdx.y * n_pass * 128 + 64 * ch;
 
-    // base_out of pass `cp` (unconditional loads from clamped, valid addresses)
+    // base_out of pass `cp`
     auto load_y = [&](int cp, uint4(&d)[4]) {
         const int nw0 = min(col0 + cp * 128, a.h_out - 64);
 #pragma unroll
         for (int i = 0; i < 4; ++i) d[i] = *reinterpret_cast<const uint4 *>(y + yoff[i] + nw0);
     };
-    // Bp operands of k step `ks` of the pass starting at column nw0: block b = columns nw0 + 16b ..
-    auto load_b = [&](int nw0, int ks, uint4(&d)[4]) {
-        const int j8 = 4 * ks + g;
+    // Bp operands of the pass starting at column nw0: block b = columns nw0 + 16b .. +15, k step ks
+    const __bf16 *bg[KS];
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-            d[b] = (ks < KS && j8 < rs8) ? *reinterpret_cast<const uint4 *>(Bp + ((size_t)j8 * a.h_out + nw0 + 16 * b + m) * 8)
-                                         : make_uint4(0, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) bg[ks] = Bp + ((size_t)min(4 * ks + g, rs8 - 1) * a.h_out + m) * 8;
+    auto load_b = [&](int nw0, uint4(&d)[KS][4]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) d[ks][b] = *reinterpret_cast<const uint4 *>(bg[ks] + (size_t)(nw0 + 16 * b) * 8);
     };
 
     uint4 yr[2][4];
-    load_y(0, yr[0]);  // the first pass's base_out is on its way while V is staged
+    uint4 br[KS][4];
+    load_y(0, yr[0]);  // the first pass's base_out and Bp are on their way while V is staged
+    load_b(min(col0, a.h_out - 64), br);
 
     // stage s.V as bf16: vs[token][rank]
     for (int idx = tid; idx < LORA_TILE_TOKENS * c8; idx += 256) {
         const int ti = idx / c8, j8 = idx - ti * c8;
+        const bool live = ti < it.n_tok;
+        const float4 *vr = reinterpret_cast<const float4 *>(
+            a.v + (size_t)((live && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.v_stride + j8 * 8);
+        const float4 lo = vr[0], hi = vr[1];
+        const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         bf16x8 o;
-        if (ti < it.n_tok) {
-            const float4 *vr = reinterpret_cast<const float4 *>(
-                a.v + (size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride + j8 * 8);
-            const float4 lo = vr[0], hi = vr[1];
-            const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)((j8 * 8 + e < it.rank) ? s * f[e] : 0.f);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
-        }
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)((live && j8 * 8 + e < it.rank) ? s * f[e] : 0.f);
         *reinterpret_cast<bf16x8 *>(&vs[ti * VS_ROW + j8 * 16]) = o;
     }
     __syncthreads();
@@ -326,36 +335,29 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
     if (!half_live) return;  // this token half is empty (no barrier follows)
     unsigned char *my_cs = cs[w];
 
-#pragma unroll
-    for (int cp = 0; cp < N_PASS; ++cp) {
+    // one pass of 128 columns; PAR = cp % 2 is a compile-time constant so that the base_out double
+    // buffer stays in registers
+    auto pass = [&](auto par_tag, int cp) {
+        constexpr int PAR = decltype(par_tag)::value;
         const int nw0 = col0 + cp * 128;
-        if (nw0 >= a.h_out) break;
-        if (cp + 1 < N_PASS) load_y(cp + 1, yr[(cp + 1) & 1]);  // next pass's base_out, ahead of this pass's products
+        load_y(cp + 1, yr[PAR ^ 1]);  // next pass's base_out, ahead of this pass's products
 
         floatx4 acc[4][2];
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) acc[b][tb] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-        uint4 br[2][4];
-        load_b(nw0, 0, br[0]);
 #pragma unroll
-        for (int ks = 0; ks < LORA_MAX_RANK / 32; ++ks) {
-            if (ks < KS) {
-                load_b(nw0, ks + 1, br[(ks + 1) & 1]);
-                bf16x8 bop[2];
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-                    bop[tb] = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + 16 * tb + m) * VS_ROW + (4 * ks + g) * 16]);
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const bf16x8 aop = __builtin_bit_cast(bf16x8, br[ks & 1][b]);
-                    acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[0], acc[b][0], 0, 0, 0);
-                    if (tb1_live) acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[1], acc[b][1], 0, 0, 0);
-                }
+            for (int b = 0; b < 4; ++b) {
+                const bf16x8 aop = __builtin_bit_cast(bf16x8, br[ks][b]);
+                const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + m) * VS_ROW + (4 * ks + g) * 16]);
+                const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&vs[(32 * th + 16 + m) * VS_ROW + (4 * ks + g) * 16]);
+                acc[b][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, b0, acc[b][0], 0, 0, 0);
+                acc[b][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, b1, acc[b][1], 0, 0, 0);
             }
-        }
+        load_b(min(nw0 + 128, a.h_out - 64), br);  // next pass's Bp, into the registers just used
 
         // park the products: lane (g, m) holds, for block b and token block tb, columns 16b + 4g .. +3 of token 16tb + m
 #pragma unroll
@@ -367,21 +369,38 @@ __global__ __launch_bounds__(256) void mfma_expand_kernel(ApplyArgs a, const Dev
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (yok[i]) {
-                const float4 p0 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32]);
-                const float4 p1 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32 + 16]);
-                float f[8];
-                Chunk<__bf16> c;
-                c.v = yr[cp & 1][i];
-                unpack_chunk(c, f);
-                bf16x8 o;
-                o[0] = (__bf16)(f[0] + p0.x); o[1] = (__bf16)(f[1] + p0.y); o[2] = (__bf16)(f[2] + p0.z); o[3] = (__bf16)(f[3] + p0.w);
-                o[4] = (__bf16)(f[4] + p1.x); o[5] = (__bf16)(f[5] + p1.y); o[6] = (__bf16)(f[6] + p1.z); o[7] = (__bf16)(f[7] + p1.w);
-                *reinterpret_cast<bf16x8 *>(y + yoff[i] + nw0) = o;
-            }
+            const float4 p0 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32]);
+            const float4 p1 = *reinterpret_cast<const float4 *>(&my_cs[(8 * i + rt) * CS_ROW + rc * 32 + 16]);
+            float f[8];
+            Chunk<__bf16> c;
+            c.v = yr[PAR][i];
+            unpack_chunk(c, f);
+            bf16x8 o;
+            o[0] = (__bf16)(f[0] + p0.x); o[1] = (__bf16)(f[1] + p0.y); o[2] = (__bf16)(f[2] + p0.z); o[3] = (__bf16)(f[3] + p0.w);
+            o[4] = (__bf16)(f[4] + p1.x); o[5] = (__bf16)(f[5] + p1.y); o[6] = (__bf16)(f[6] + p1.z); o[7] = (__bf16)(f[7] + p1.w);
+            if (yok[i]) *reinterpret_cast<bf16x8 *>(y + yoff[i] + nw0) = o;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();  // the next pass overwrites the parked products
+    };
+    // columns past h_out: this wavefront's share of the block ends (the loads ahead were clamped)
+    const int my_pass = min(n_pass, (a.h_out - col0 + 127) / 128);
+    for (int cp = 0; cp < my_pass; cp += 2) {
+        pass(std::integral_constant<int, 0>{}, cp);
+        if (cp + 1 < my_pass) pass(std::integral_constant<int, 1>{}, cp + 1);
+    }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_pass)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
+    __shared__ __attribute__((aligned(16))) unsigned char cs[4][32 * CS_ROW];
+    const DevItem it = tiles[blockIdx.x];
+    switch ((it.rank + 31) >> 5) {
+    case 1: mfma_expand_body<1>(a, it, n_pass, vs, cs); break;
+    case 2: mfma_expand_body<2>(a, it, n_pass, vs, cs); break;
+    case 3: mfma_expand_body<3>(a, it, n_pass, vs, cs); break;
+    default: mfma_expand_body<4>(a, it, n_pass, vs, cs); break;
     }
 }
 
@@ -418,8 +437,11 @@ hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_ti
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm)
 {
     if (n_tiles <= 0) return hipSuccess;
-    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles, (a.h_out + EXPAND_COLS - 1) / EXPAND_COLS), dim3(256),
-             st, a, tiles);
+    // the widest column run per block that still gives 512 blocks (two per CU), else the narrowest
+    int cols = 1024;
+    while (cols > 256 && (int64_t)n_tiles * ((a.h_out + cols - 1) / cols) < 512) cols >>= 1;
+    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles, (a.h_out + cols - 1) / cols), dim3(256), st, a, tiles,
+             cols / 128);
     return hipGetLastError();
 }
 
