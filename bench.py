@@ -65,6 +65,7 @@ def main() -> int:
     ap.add_argument("--workload", default="decode", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--layers", type=int, default=0, help="layer copies of the pool to rotate over")
     ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
+    ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -85,7 +86,7 @@ def main() -> int:
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
     inst = wl.CONFIGS[args.workload](seed=0)
     t_setup = time.time()
-    pi = H.PooledInstance(inst, n_layers=n_layers)
+    pi = H.PooledInstance(inst, n_layers=n_layers, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv])
     h = pi.pool.handle
     dev = torch.device("cuda:0")
 

@@ -56,8 +56,11 @@ enum { LORA_F32 = 0, LORA_BF16 = 1 };                               /* element t
 enum { LORA_SLOT_EMPTY = 0, LORA_SLOT_FILLING = 1, LORA_SLOT_READY = 2 };
 enum {
     LORA_CACHE_HOST_ONLY = 1,     /* flags: slot table only, no device work */
-    LORA_CACHE_FUSED_GEMV = 2     /* run GEMV shrink and expand as one launch with an in-kernel hand-over
-                                     (slower than two launches on MI355X: see the kernel's header) */
+    /* GEMV shrink and expand run as one launch with an in-kernel hand-over of the intermediate when
+     * the batch's GEMV part is small (the launch in between then costs more than the hand-over),
+     * else as two launches.  These two flags take the choice away: */
+    LORA_CACHE_FUSED_GEMV = 2,    /* always one launch */
+    LORA_CACHE_SPLIT_GEMV = 4     /* always two launches (and no hand-over buffer in the pool) */
 };
 
 #define LORA_MAX_RANK 128

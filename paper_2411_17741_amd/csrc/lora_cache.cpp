@@ -64,9 +64,7 @@ struct lora_plan {
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
-    size_t off_tiles = 0, off_gs = 0, off_ge = 0, off_counters = 0;
-    int32_t n_batches = 0;
-    int32_t epoch = 0;  // applies since the upload; the fused GEMV counters stand at epoch * rank
+    size_t off_tiles = 0, off_gs = 0, off_ge = 0;
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
 };
@@ -86,9 +84,10 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
-    size_t off_fault = 0, off_vpart = 0;
+    size_t off_fault = 0, off_vpart = 0, off_vtag = 0;
+    uint32_t tag_epoch = 0;  // fused GEMV launches so far; the tag of the words of the latest one
     int64_t vpart_rows = 0;  // rows of the k-split partial scratch
-    bool fused_gemv = false;
+    int fused_gemv = 0;  // 0 never, 1 by size, 2 always
     size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
 
     std::vector<Slot> slots;
@@ -151,7 +150,7 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.mfma_min = cfg->dtype == LORA_BF16 ? (cfg->mfma_min_tokens ? cfg->mfma_min_tokens : LORA_MFMA_MIN_TOKENS) : 0;
     c.flags = cfg->flags;
     c.host_only = (cfg->flags & LORA_CACHE_HOST_ONLY) != 0;
-    c.fused_gemv = (cfg->flags & LORA_CACHE_FUSED_GEMV) != 0;
+    c.fused_gemv = (cfg->flags & LORA_CACHE_SPLIT_GEMV) ? 0 : ((cfg->flags & LORA_CACHE_FUSED_GEMV) ? 2 : 1);
 
     const int n_proj = cfg->n_proj, n_cls = cfg->n_classes;
     c.class_first.resize(n_cls);
@@ -197,6 +196,9 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.vpart_rows = c.dtype == LORA_BF16 ? std::min<int64_t>((int64_t)MAX_K_SPLITS * c.max_tokens, 640 * 64 + c.max_tokens) : 0;
     c.off_vpart = cur;
     cur += align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
+    // fused GEMV launches hand v over as tagged 64-bit words, one row per token
+    c.off_vtag = cur;
+    cur += c.fused_gemv ? align_up(sizeof(uint64_t) * (size_t)c.max_tokens * c.v_stride) : 0;
     c.off_plans = cur;
     cur += c.plan_cap * (size_t)(c.n_user_plans + N_INTERNAL_PLANS);
     c.off_stage = cur;
@@ -306,20 +308,15 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     };
     p.n_tile_tok = 0;
     for (int i = 0; i < w.n_tiles; ++i) p.n_tile_tok += w.tiles[i].n_tok;
-    // token batches are runs of items with the same tok_off, in the same order in both lists
-    std::unordered_map<int32_t, int32_t> batch_of;
-    for (int i = 0; i < w.n_gs_items; ++i) batch_of.emplace(w.gs_items[i].tok_off, (int32_t)batch_of.size());
-    p.n_batches = (int32_t)batch_of.size();
     auto stamp_gemv = [&](lora_item_t *items, int n, bool expand) {
         for (int i = 0; i < n; ++i) {
             const Slot &s = c.slots[items[i].slot];
-            const int32_t batch = batch_of[items[i].tok_off];
             lora::GemvItem d;
             for (int t = 0; t < LORA_GEMV_BATCH; ++t)
                 d.tok[t] = t < items[i].n_tok ? w.tok_list[items[i].tok_off + t] : -1;
             d.row = c.slot_row[items[i].slot];
             d.rank = items[i].rank;
-            d.a = expand ? ((items[i].a / 64) | (batch << 4)) : (items[i].a | (items[i].b << 8) | (batch << 12));
+            d.a = expand ? items[i].a / 64 : (items[i].a | (items[i].b << 8));
             d.alpha = s.alpha;
             std::memcpy(&items[i], &d, sizeof(d));
         }
@@ -336,9 +333,7 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     p.off_tiles = align_up(sizeof(int32_t) * (size_t)w.n_tok_list);
     p.off_gs = p.off_tiles + align_up(sizeof(lora_item_t) * (size_t)w.n_tiles);
     p.off_ge = p.off_gs + align_up(sizeof(lora_item_t) * (size_t)w.n_gs_items);
-    p.off_counters = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
-    const size_t bytes = p.off_counters + align_up(sizeof(int32_t) * (size_t)p.n_batches);
-    p.epoch = 0;
+    const size_t bytes = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
     if (bytes > c.plan_cap) {
         lora_worklists_free(&w);
         return LORA_E_NOMEM;
@@ -364,7 +359,6 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
         std::memcpy(p.pinned + p.off_gs, w.gs_items, sizeof(lora_item_t) * (size_t)w.n_gs_items);
         std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
-        std::memset(p.pinned + p.off_counters, 0, bytes - p.off_counters);  // ready counters start at zero
         lora_worklists_free(&w);
         if (bytes) {
             HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
@@ -474,7 +468,10 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
     c->pool_bytes = dev_pool_bytes;
 
     int rc = LORA_OK;
-    if (hipMemset(c->pool + c->off_fault, 0, ALIGN) != hipSuccess) {
+    // the tagged words must not carry a future launch number by accident: numbers start at 1
+    if (hipMemset(c->pool + c->off_fault, 0, ALIGN) != hipSuccess ||
+        (c->fused_gemv &&
+         hipMemset(c->pool + c->off_vtag, 0, sizeof(uint64_t) * (size_t)c->max_tokens * c->v_stride) != hipSuccess)) {
         g_last_hip = (int)hipGetLastError();
         delete c;
         return LORA_E_HIP;
@@ -759,6 +756,9 @@ static int validate_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_
     return LORA_OK;
 }
 
+// shrink items up to which the one-launch GEMV form is chosen (measured: above, two launches win)
+constexpr int FUSED_GEMV_MAX_ITEMS = 2048;
+
 static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
                          float scale, hipStream_t st)
 {
@@ -790,11 +790,14 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
     const int splits = p->n_tiles > 0 ? choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in) : 1;
     HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, p->n_tile_tok, splits,
                                      reinterpret_cast<float *>(c->pool + c->off_vpart), st, tm));
-    const bool fused = c->fused_gemv && p->n_gs > 0 && p->epoch < (1 << 23);
+    // (after 2^32 - 1 fused launches the numbers would repeat: two launches from then on)
+    // one launch pays off while the GEMV part is small enough for the launch gap to matter
+    const bool fused = p->n_gs > 0 && c->tag_epoch != UINT32_MAX &&
+                       (c->fused_gemv == 2 || (c->fused_gemv == 1 && p->n_gs <= FUSED_GEMV_MAX_ITEMS));
     if (fused) {
-        ++p->epoch;
+        ++c->tag_epoch;
         HIP_TRY(lora::launch_gemv_fused(c->dtype, a, gs, p->n_gs, ge, p->n_ge,
-                                        reinterpret_cast<int32_t *>(p->dev + p->off_counters), p->epoch,
+                                        reinterpret_cast<unsigned long long *>(c->pool + c->off_vtag), c->tag_epoch,
                                         reinterpret_cast<int32_t *>(c->pool + c->off_fault), st, tm));
     } else {
         HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));

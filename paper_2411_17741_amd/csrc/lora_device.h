@@ -94,4 +94,31 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Sums N = 2^K values per lane over the 64 lanes with N - 1 + (6 - K) shuffles instead of 6 N:
+// every step folds the wavefront in half and halves the number of values a lane carries (the
+// lower half of the lanes keeps the first half of the values).  On return v[0] of lane l holds
+// the total of value l >> (6 - K).
+template <int N>
+__device__ __forceinline__ void wave_sum_fold(float (&v)[N])
+{
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "power of two up to 16");
+    const int lane = threadIdx.x & 63;
+    auto from = [&](float x, int off) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ off) << 2, __builtin_bit_cast(int, x)));
+    };
+    int off = 32;
+#pragma unroll
+    for (int m = N; m > 1; m >>= 1, off >>= 1) {
+        const bool upper = (lane & off) != 0;
+#pragma unroll
+        for (int i = 0; i < m / 2; ++i) {
+            const float lo = v[i], hi = v[i + m / 2];  // named, so that the selects stay selects of values
+            const float give = upper ? lo : hi;
+            const float keep = upper ? hi : lo;
+            v[i] = keep + from(give, off);
+        }
+    }
+    for (; off > 0; off >>= 1) v[0] += from(v[0], off);
+}
+
 }  // namespace lora

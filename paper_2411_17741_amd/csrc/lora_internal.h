@@ -33,9 +33,8 @@ static_assert(sizeof(DevItem) == sizeof(lora_item_t), "device items are uploaded
 
 // GEMV work item: a batch of up to LORA_GEMV_BATCH tokens of one slot, named directly so that
 // the kernels reach their data with one lookup.  `a` packs, for a shrink item, the first rank
-// row (bits 0-7), the number of rows (bits 8-11) and the batch number (bits 12+); for an expand
-// item the column offset in the super-chunk divided by 64 (bits 0-3) and the batch number
-// (bits 4+).  The batch number indexes the ready counters of the fused kernel.
+// row (bits 0-7) and the number of rows (bits 8+); for an expand item the column offset in the
+// super-chunk divided by 64.
 struct GemvItem {
     int32_t tok[LORA_GEMV_BATCH];  // token ids, -1 = unused
     int32_t row;                   // first storage row of the slot
@@ -79,11 +78,12 @@ hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *ite
                               const KernelTimer *tm);
 hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
                               const KernelTimer *tm);
-// shrink and expand in one launch: expand wavefronts load their slab part at once and then wait
-// for the batch's counter (device, one int32 per batch, only ever incremented) to reach
-// epoch * rank; `fault` (device int32) is set if a wait gives up
+// shrink and expand in one launch: expand wavefronts load their slab part at once and then poll
+// the intermediate, which travels as 64-bit words {epoch, fp32 bits} in vtag (device, max_tokens
+// rows of v_stride words, never holding a number >= epoch on entry); epoch != 0; `fault` (device
+// int32) is set if a wait gives up
 hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
-                             int32_t *counters, int32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
+                             unsigned long long *vtag, uint32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
 // n_tile_tok = tokens of all tiles (the leading part of tok_list); part = scratch for k-split
 // partials, splits * n_tile_tok rows of v_stride floats (unused when the launch does not split)
 hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int n_tile_tok, int k_splits,

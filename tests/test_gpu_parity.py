@@ -91,27 +91,31 @@ def test_decode_config():
     _full_parity(wl.decode())
 
 
-def test_fused_gemv_option_gives_the_same_results():
-    """The GEMV phases as one launch with an in-kernel hand-over (opt-in flag)."""
+def test_gemv_as_one_launch_or_two_gives_the_same_results():
+    """The GEMV phases run as one launch with an in-kernel hand-over or as two launches; by
+    default the library picks by size.  Force each form."""
     B, H = _mods()
-    _full_parity(wl.decode(), flags=B.LORA_CACHE_FUSED_GEMV)
-    _full_parity(wl.small_mixed(seed=4), p=1, flags=B.LORA_CACHE_FUSED_GEMV)
-    _full_parity(wl.small_mixed(seed=4, dtype="f32"), p=0, flags=B.LORA_CACHE_FUSED_GEMV)
+    for flags in (B.LORA_CACHE_FUSED_GEMV, B.LORA_CACHE_SPLIT_GEMV):
+        _full_parity(wl.decode(), flags=flags)
+        _full_parity(wl.small_mixed(seed=4), p=1, flags=flags)
+        _full_parity(wl.small_mixed(seed=4, dtype="f32"), p=0, flags=flags)
 
 
 def test_fused_gemv_repeated_applies_of_one_plan():
-    """The ready counters of the fused launch only ever grow: apply one plan many times (as the
-    layers of an iteration do) and check the last result."""
+    """The fused launch tells this apply's intermediate from older ones by its number: apply one
+    plan many times (as the layers of an iteration do) with activations that change from apply to
+    apply, and check the last result."""
     B, H = _mods()
     inst = wl.decode(seed=3)
     pi = H.PooledInstance(inst, flags=B.LORA_CACHE_FUSED_GEMV)
     try:
         x, base = inst.x(0), inst.base_out(0)
         xd = H.to_device(x, pi.dtype)
+        others = [H.to_device(wl.bf16_round(x * f), pi.dtype) for f in (-1.0, 0.5, 3.0)]
         plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
         for rep in range(40):
             yd = H.to_device(base, pi.dtype)
-            pi.pool.apply_plan(plan, 0, 0, xd, yd, inst.scale)
+            pi.pool.apply_plan(plan, 0, 0, xd if rep == 39 else others[rep % 3], yd, inst.scale)
         pi.pool.check_fault()
         ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
         _check(H.error_metrics(yd.float().cpu().numpy(), ref, base), "bf16", "40th apply of one plan")
