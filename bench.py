@@ -66,6 +66,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="layer copies of the pool to rotate over")
     ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
     ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
+    ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -86,7 +87,7 @@ def main() -> int:
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
     inst = wl.CONFIGS[args.workload](seed=0)
     t_setup = time.time()
-    pi = H.PooledInstance(inst, n_layers=n_layers, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv])
+    pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv])
     h = pi.pool.handle
     dev = torch.device("cuda:0")
 
@@ -129,8 +130,12 @@ def main() -> int:
     ms_per_layer = ms_per_step / n_layers
     tokens_per_s = inst.T / (ms_per_layer * 1e-3)
 
-    rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS)
+    # the work lists the library's plan holds (for the byte counts): same indexer, same thresholds
+    rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, args.mfma_min_tokens or B.LORA_MFMA_MIN_TOKENS)
     B.check(rc)
+    if not args.mfma_min_tokens and w["tiles"]:
+        rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS_MIXED)
+        B.check(rc)
     per_proj = algorithmic_bytes(inst, w)
     step_bytes = sum(sum(b for k, b in v.items() if k != "gemv_fused") for v in per_proj)
     step_flops = sum(2 * it[1] * it[3] * (p.h_in + p.h_out) for p in inst.projs for it in (w["tiles"] + w["groups"]))
@@ -190,7 +195,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD_TEXT[args.workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
                    "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer,
-                   "tiles": len(w["tiles"]), "gemv_groups": len(w["groups"])},
+                   "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "layer": {"algorithmic_bytes": step_bytes, "flops": step_flops, "achieved_GBs": step_bytes / (ms_per_layer * 1e-3) / 1e9,

@@ -65,7 +65,8 @@ enum {
 
 #define LORA_MAX_RANK 128
 #define LORA_TILE_TOKENS 64      /* tokens per matrix-core tile */
-#define LORA_MFMA_MIN_TOKENS 16  /* default: segments / pooled slots with fewer tokens take the GEMV path */
+#define LORA_MFMA_MIN_TOKENS 16  /* default: segments / pooled slots with fewer tokens take the GEMV path ... */
+#define LORA_MFMA_MIN_TOKENS_MIXED 8 /* ... and, with the default, this is the threshold once a batch has any tile at 16 */
 #define LORA_GEMV_BATCH 4        /* tokens one GEMV work item handles */
 
 typedef struct lora_cache lora_cache_t; /* opaque */
@@ -86,7 +87,8 @@ typedef struct {
     int32_t max_tokens;         /* largest T of any apply */
     int32_t max_segments;       /* largest n_seg of any apply */
     int32_t n_plans;            /* plans that may be alive at once (>= 0; 4 more are kept for lora_apply) */
-    int32_t mfma_min_tokens;    /* 0 = LORA_MFMA_MIN_TOKENS; ignored (no tile path) for LORA_F32 */
+    int32_t mfma_min_tokens;    /* 0 = default: LORA_MFMA_MIN_TOKENS, lowered to LORA_MFMA_MIN_TOKENS_MIXED for a batch
+                                   that has tiles at the former; ignored (no tile path) for LORA_F32 */
     int32_t flags;
 } lora_cache_config_t;
 

@@ -22,7 +22,7 @@ LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND =
 LORA_F32, LORA_BF16 = 0, 1
 LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
 LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV = 1, 2, 4
-LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS = 128, 64, 16
+LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS, LORA_MFMA_MIN_TOKENS_MIXED = 128, 64, 16, 8
 
 
 class LoraError(RuntimeError):

@@ -74,6 +74,7 @@ struct lora_cache {
     std::vector<int32_t> class_rank, class_slots, class_first;
     int32_t n_layers = 0, n_slots = 0, dtype = 0, esize = 0;
     int32_t max_tokens = 0, max_segments = 0, n_user_plans = 0, mfma_min = 0, flags = 0;
+    bool mfma_min_auto = false;  // the configuration left the threshold to the library
     int32_t v_stride = 0;
     bool host_only = false;
 
@@ -148,6 +149,7 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.max_segments = cfg->max_segments;
     c.n_user_plans = cfg->n_plans;
     c.mfma_min = cfg->dtype == LORA_BF16 ? (cfg->mfma_min_tokens ? cfg->mfma_min_tokens : LORA_MFMA_MIN_TOKENS) : 0;
+    c.mfma_min_auto = cfg->dtype == LORA_BF16 && cfg->mfma_min_tokens == 0;
     c.flags = cfg->flags;
     c.host_only = (cfg->flags & LORA_CACHE_HOST_ONLY) != 0;
     c.fused_gemv = (cfg->flags & LORA_CACHE_SPLIT_GEMV) ? 0 : ((cfg->flags & LORA_CACHE_FUSED_GEMV) ? 2 : 1);
@@ -266,6 +268,14 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     lora_worklists_t w;
     int rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, c.mfma_min, &w);
     if (rc != LORA_OK) return rc;
+    // A batch that has tiles anyway pays for the tile launches already: then smaller pools of
+    // tokens are tiles too (one pass over the slab instead of one per token batch).  A batch
+    // without any stays one GEMV launch.
+    if (c.mfma_min_auto && w.n_tiles > 0) {
+        lora_worklists_free(&w);
+        rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, LORA_MFMA_MIN_TOKENS_MIXED, &w);
+        if (rc != LORA_OK) return rc;
+    }
 
     p.slots.clear();
     p.generations.clear();
