@@ -32,6 +32,10 @@ WORKLOAD_TEXT = {
     "mixed": "mixed: 224 decode + 32 prompts, 7B-shaped layer (q,k,v,o,gate,up,down) bf16, pool of 500, Zipf(1.2)",
     "stress": "stress: 512 decode + 4x512 prompt tokens, 13B-shaped layer bf16, pool of 1000 in 4 layer copies, Zipf(1.2)",
 }
+# HBM bytes per launch of a workload's dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs, scaled
+# by what the same counters read for a plain copy; figures and commands in profiles/gemv_fused_decode_traffic.txt).
+# A counter run cannot happen inside this process, so the figure measured for the same command is carried here.
+MEASURED_TRAFFIC = {("decode", "gemv_fused"): 28.15e6}
 DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4}
 DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20}
 
@@ -161,7 +165,8 @@ def main() -> int:
         dom = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
         roofline = {
             "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+            "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get((args.workload, dom)) if args.gemv == "auto" and not args.mfma_min_tokens else None,
             "avg_launch_us": kernels[dom]["avg_us"], "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
         }
 
