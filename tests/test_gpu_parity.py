@@ -206,6 +206,38 @@ def test_ragged_lengths_and_odd_ranks(dtype):
     _full_parity(_custom_instance(lens, adapters, ranks, dtype=dtype))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("form", ["fused", "split"])
+def test_gemv_path_every_rank_shape_and_batch_size(dtype, form):
+    """No tiles at all: every adapter has 1..7 tokens (token batches of 1, 2, 3, 4 and 4+k), ranks
+    cover every body of the GEMV kernels (vector-ALU bodies below 32 stored ranks and for fp32,
+    matrix-core bodies with 1, 2 (both unit widths), 3 and 4 k steps, ranks that are no multiple
+    of 8), rows end in a ragged run of chunks, and the last column unit of a super-chunk is cut."""
+    B, H = _mods()
+    ranks = [1, 4, 8, 12, 16, 24, 32, 37, 40, 48, 56, 64, 72, 96, 100, 128]
+    n_tok = [1, 2, 3, 4, 5, 6, 7, 1, 2, 3, 4, 5, 6, 7, 3, 5]
+    lens, adapters = [], []
+    for rnd in range(7):  # interleave the requests as a decode batch would
+        for a, n in enumerate(n_tok):
+            if rnd < n:
+                lens.append(1)
+                adapters.append(a)
+    inst = _custom_instance(lens, adapters, ranks, h_in=4160, h_out=1216, dtype=dtype, seed=5)
+    flags = {"fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[form]
+    _full_parity(inst, flags=flags)
+
+
+@pytest.mark.parametrize("form", ["fused", "split"])
+def test_gemv_path_long_rows(form):
+    """Rows longer than one pass of a 16-wavefront block (h_in > 16384) and the 13B-shaped
+    13824 (14 wavefronts per item in the stand-alone shrink, several passes of 4 in the fused)."""
+    B, H = _mods()
+    flags = {"fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[form]
+    for h_in in (13824, 16448):
+        inst = _custom_instance([1, 1, 1, 2, 1], [0, 1, 0, 2, 1], [16, 64, 128], h_in=h_in, h_out=256, seed=h_in)
+        _full_parity(inst, flags=flags)
+
+
 def test_empty_and_adapterless_batches():
     B, H = _mods()
     inst = _custom_instance([3, 2], [-1, -1], [8])
