@@ -117,7 +117,9 @@ int lora_cache_destroy(lora_cache_t *c);
 /* Enqueue, on `fill_stream`, the copy of one (layer, projection) part of an adapter
  * into `slot`: host_A [h_in][rank] and host_B [rank][h_out], row-major, element type =
  * cfg.dtype.  The host buffers are read asynchronously: keep them unchanged until the
- * stream has passed this call (pinned memory makes the copy truly asynchronous).  The
+ * stream has passed this call.  Pinned (page-locked) host memory, 16-byte aligned, is read by
+ * the device directly, one kernel launch per part; any other host memory is copied through a
+ * staging buffer first (and a copy from pageable memory is not truly asynchronous).  The
  * first part filled into an EMPTY slot binds (adapter_id, rank, alpha) and moves it to
  * FILLING; later parts must repeat the same three.  The slot reports READY once all
  * n_layers * n_proj parts are enqueued and the last copy has completed.  An apply that

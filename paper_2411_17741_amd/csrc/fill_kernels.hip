@@ -6,38 +6,90 @@
 
 namespace lora {
 
-// At[j][k] = A[k][j].  A 64(k) x 8(j) patch per 256-thread block goes through LDS so that
-// both the reads (along j, then k) and the writes (along k) are contiguous runs.
+// One launch per part.  Blocks [0, h_in/64) transpose A, the rest pack B.  The source may be
+// device memory (a staging buffer) or pinned host memory read over PCIe, so it is read exactly
+// once, in 16-byte pieces of contiguous runs, with every load of a thread issued before the
+// first is used.
+//
+// A block: 64 rows k of A = one contiguous run of 64*r elements -> LDS -> At[j][k0 .. k0+63]
+// for every stored rank j, written as 16-byte pieces along k.
+// B block: 256 threads x 8 columns; a thread loads the 8 columns of the 8 ranks of a granule
+// (8 loads, each 1 KB contiguous across a wavefront), transposes them in registers and writes
+// 8 chunks of Bp = 128 contiguous bytes.
 template <typename E>
-__global__ __launch_bounds__(256) void repack_a_kernel(const E *__restrict__ A, E *__restrict__ At, int h_in, int r, int rs)
+__global__ __launch_bounds__(256) void repack_kernel(const E *__restrict__ A, const E *__restrict__ B, E *__restrict__ At,
+                                                     E *__restrict__ Bp, int h_in, int h_out, int r, int rs, int n_a_blocks)
 {
-    __shared__ E tile[64][64 + 1];
-    const int k0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int kk = i >> 6, jj = i & 63;  // consecutive threads walk along j (contiguous in A)
-        const int k = k0 + kk, j = j0 + jj;
-        tile[kk][jj] = (k < h_in && j < r) ? A[(size_t)k * r + j] : from_float<E>(0.f);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int jj = i >> 6, kk = i & 63;  // consecutive threads walk along k (contiguous in At)
-        const int k = k0 + kk, j = j0 + jj;
-        if (k < h_in && j < rs) At[(size_t)j * h_in + k] = tile[kk][jj];
-    }
-}
-
-// Bp[j/8][n][j%8] = B[j][n]: one thread per (granule, column), 8 strided reads (each
-// contiguous across the threads of a wavefront), one contiguous 8-element write.
-template <typename E>
-__global__ __launch_bounds__(256) void repack_b_kernel(const E *__restrict__ B, E *__restrict__ Bp, int h_out, int r, int rs)
-{
-    const int n = blockIdx.x * 256 + threadIdx.x, j8 = blockIdx.y;
-    if (n >= h_out) return;
-    E *o = Bp + ((size_t)j8 * h_out + n) * 8;
+    constexpr int EPV = 16 / sizeof(E);            // elements per 16-byte piece
+    constexpr int TROW = LORA_MAX_RANK + 2;        // LDS row stride in elements (breaks the power of two)
+    __shared__ E tile[64 * TROW];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x < n_a_blocks) {
+        const int k0 = blockIdx.x * 64;
+        const uint4 *src = reinterpret_cast<const uint4 *>(A + (size_t)k0 * r);
+        const int n_piece = 64 * r / EPV;              // 64 * r elements, a multiple of EPV
+        constexpr int MAXP = 64 * LORA_MAX_RANK / EPV / 256;  // pieces per thread at most
+        uint4 buf[MAXP];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int j = j8 * 8 + e;
-        o[e] = j < r ? B[(size_t)j * h_out + n] : from_float<E>(0.f);
+        for (int it = 0; it < MAXP; ++it) {
+            const int q = tid + 256 * it;
+            buf[it] = src[q < n_piece ? q : 0];
+        }
+#pragma unroll
+        for (int it = 0; it < MAXP; ++it) {
+            const int q = tid + 256 * it;
+            if (q < n_piece) {
+                const E *e = reinterpret_cast<const E *>(&buf[it]);
+                int kk = (q * EPV) / r, jj = (q * EPV) - kk * r;
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) {
+                    tile[kk * TROW + jj] = e[i];
+                    if (++jj == r) { jj = 0; ++kk; }
+                }
+            }
+        }
+        __syncthreads();
+        // At[j][k0 + 8*kq .. +7]: thread = (j, kq), 64 / EPV pieces per rank row
+        constexpr int PPR = 64 / EPV;
+        for (int idx = tid; idx < rs * PPR; idx += 256) {
+            const int j = idx / PPR, kq = idx - j * PPR;
+            E out[EPV];
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) out[i] = j < r ? tile[(kq * EPV + i) * TROW + j] : from_float<E>(0.f);
+            *reinterpret_cast<uint4 *>(At + (size_t)j * h_in + k0 + kq * EPV) = *reinterpret_cast<const uint4 *>(out);
+        }
+    } else {
+        // columns n0 .. n0+7 of granule j8
+        const int cols_per_block = 256 * 8;
+        const int nb = (h_out + cols_per_block - 1) / cols_per_block;
+        const int bb = (int)blockIdx.x - n_a_blocks;
+        const int j8 = bb / nb, n0 = ((bb - j8 * nb) * 256 + tid) * 8;
+        if (n0 >= h_out) return;  // h_out is a multiple of 64, so a thread's 8 columns are all in or all out
+        E in[8][8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = min(j8 * 8 + e, r - 1);
+            const E *row = B + (size_t)j * h_out + n0;
+            if constexpr (sizeof(E) == 2) {
+                *reinterpret_cast<uint4 *>(in[e]) = *reinterpret_cast<const uint4 *>(row);
+            } else {
+                *reinterpret_cast<uint4 *>(in[e]) = *reinterpret_cast<const uint4 *>(row);
+                *reinterpret_cast<uint4 *>(in[e] + 4) = *reinterpret_cast<const uint4 *>(row + 4);
+            }
+        }
+        E *o = Bp + ((size_t)j8 * h_out + n0) * 8;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            E chunk[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) chunk[e] = j8 * 8 + e < r ? in[e][c] : from_float<E>(0.f);
+            if constexpr (sizeof(E) == 2) {
+                *reinterpret_cast<uint4 *>(o + c * 8) = *reinterpret_cast<const uint4 *>(chunk);
+            } else {
+                *reinterpret_cast<uint4 *>(o + c * 8) = *reinterpret_cast<const uint4 *>(chunk);
+                *reinterpret_cast<uint4 *>(o + c * 8 + 4) = *reinterpret_cast<const uint4 *>(chunk + 4);
+            }
+        }
     }
 }
 
@@ -47,13 +99,13 @@ static hipError_t repack_t(const void *sa, const void *sb, void *slab, int h_in,
     const int rs = rank_storage(r);
     E *At = static_cast<E *>(slab);
     E *Bp = At + (size_t)rs * h_in;
-    hipLaunchKernelGGL((repack_a_kernel<E>), dim3((h_in + 63) / 64, (rs + 63) / 64), dim3(256), 0, st,
-                       static_cast<const E *>(sa), At, h_in, r, rs);
-    hipLaunchKernelGGL((repack_b_kernel<E>), dim3((h_out + 255) / 256, rs / 8), dim3(256), 0, st,
-                       static_cast<const E *>(sb), Bp, h_out, r, rs);
+    const int n_a = h_in / 64, n_b = (rs / 8) * ((h_out + 2047) / 2048);
+    hipLaunchKernelGGL((repack_kernel<E>), dim3(n_a + n_b), dim3(256), 0, st, static_cast<const E *>(sa),
+                       static_cast<const E *>(sb), At, Bp, h_in, h_out, r, rs, n_a);
     return hipGetLastError();
 }
 
+// Sources must be 16-byte aligned (device staging buffers and pinned allocations are).
 hipError_t launch_repack(int dtype, const void *stage_A, const void *stage_B, void *slab, int32_t h_in, int32_t h_out,
                          int32_t rank, hipStream_t st)
 {

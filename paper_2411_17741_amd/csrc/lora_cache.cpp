@@ -537,6 +537,18 @@ int lora_cache_destroy(lora_cache_t *c)
     return LORA_OK;
 }
 
+// The address under which the device sees pinned (page-locked, mapped) host memory, or null for
+// any other kind of pointer.
+static const void *device_view_of_pinned(const void *host)
+{
+    hipPointerAttribute_t at;
+    if (hipPointerGetAttributes(&at, host) != hipSuccess) {
+        (void)hipGetLastError();  // pageable memory is reported as an error by some runtimes
+        return nullptr;
+    }
+    return at.type == hipMemoryTypeHost ? at.devicePointer : nullptr;
+}
+
 int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha, int32_t layer,
                          int32_t proj, const void *host_A, const void *host_B, void *fill_stream)
 {
@@ -567,19 +579,28 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
     const size_t bytes_a = (size_t)rank * h_in * c->esize, bytes_b = (size_t)rank * h_out * c->esize;
     if (!c->host_only) {
         hipStream_t st = static_cast<hipStream_t>(fill_stream);
-        Stage &sg = c->stage[c->stage_next++ % N_STAGES];
-        if (sg.pending) HIP_TRY(hipStreamWaitEvent(st, sg.ev, 0));
         if (c->fencing && s.last_used > 0) {
             // applies enqueued earlier may still read this slab
             HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
         }
-        char *stage_b = sg.dev + align_up(bytes_a);
-        HIP_TRY(hipMemcpyAsync(sg.dev, host_A, bytes_a, hipMemcpyHostToDevice, st));
-        HIP_TRY(hipMemcpyAsync(stage_b, host_B, bytes_b, hipMemcpyHostToDevice, st));
         char *slab = slab_ptr(*c, layer, proj, slot);
-        HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, st));
-        HIP_TRY(hipEventRecord(sg.ev, st));
-        sg.pending = true;
+        const void *dev_A = device_view_of_pinned(host_A), *dev_B = device_view_of_pinned(host_B);
+        if (dev_A && dev_B && ((reinterpret_cast<uintptr_t>(dev_A) | reinterpret_cast<uintptr_t>(dev_B)) & 15) == 0) {
+            // pinned host memory is mapped into the device's address space: the repack kernels read
+            // it over PCIe themselves, which saves two copies through a staging buffer and, more
+            // to the point for small parts, the switches between the copy engine and the compute
+            // queue (a part then costs one or two kernel launches)
+            HIP_TRY(lora::launch_repack(c->dtype, dev_A, dev_B, slab, h_in, h_out, rank, st));
+        } else {
+            Stage &sg = c->stage[c->stage_next++ % N_STAGES];
+            if (sg.pending) HIP_TRY(hipStreamWaitEvent(st, sg.ev, 0));
+            char *stage_b = sg.dev + align_up(bytes_a);
+            HIP_TRY(hipMemcpyAsync(sg.dev, host_A, bytes_a, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipMemcpyAsync(stage_b, host_B, bytes_b, hipMemcpyHostToDevice, st));
+            HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, st));
+            HIP_TRY(hipEventRecord(sg.ev, st));
+            sg.pending = true;
+        }
         if (!s.fill_ev) HIP_TRY(hipEventCreateWithFlags(&s.fill_ev, hipEventDisableTiming));
         HIP_TRY(hipEventRecord(s.fill_ev, st));
         s.fill_pending = true;

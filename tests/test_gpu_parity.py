@@ -291,6 +291,38 @@ def test_apply_errors():
         pi.close()
 
 
+def test_fill_from_pageable_memory_gives_the_same_slabs():
+    """Pinned host memory is read by the repack kernel directly over PCIe; any other host
+    memory goes through a staging copy first.  Same bytes in the pool either way."""
+    B, H = _mods()
+    inst = _custom_instance([3, 20, 1, 70], [0, 1, 2, 3], [7, 16, 64, 128], h_in=320, h_out=448, seed=21)
+    outs = []
+    for pinned in (True, False):
+        pi = H.PooledInstance(inst, adapters=[])
+        try:
+            keep = []
+            for a in range(len(inst.ranks)):
+                A, Bm = inst.adapter_weights(a, 0)
+                ta, tb = torch.from_numpy(A).to(torch.bfloat16), torch.from_numpy(Bm).to(torch.bfloat16)
+                if pinned:
+                    ta, tb = ta.pin_memory(), tb.pin_memory()
+                assert ta.is_pinned() == pinned
+                keep += [ta, tb]
+                pi.pool.fill(int(pi.slot_of[a]), int(inst.adapter_ids[a]), int(inst.ranks[a]), float(inst.alpha[a]), 0, 0, ta, tb, pin=False)
+            torch.cuda.synchronize()
+            pi.pool.fills_done()
+            x, base = inst.x(0), inst.base_out(0)
+            xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+            pi.apply(0, 0, xd, yd)
+            pi.pool.check_fault()
+            outs.append(yd.float().cpu().numpy())
+        finally:
+            pi.close()
+    assert np.array_equal(outs[0], outs[1])
+    ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
+    _check(H.error_metrics(outs[0], ref, base), "bf16", "fill paths")
+
+
 def test_plan_reuse_over_projections_and_layers():
     """One plan per iteration, applied to every projection of every layer copy."""
     B, H = _mods()
