@@ -71,6 +71,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
     ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
     ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
+    ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -91,7 +92,7 @@ def main() -> int:
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
     inst = wl.CONFIGS[args.workload](seed=0)
     t_setup = time.time()
-    pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv])
+    pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv] | (B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0))
     h = pi.pool.handle
     dev = torch.device("cuda:0")
 
@@ -122,6 +123,14 @@ def main() -> int:
         B.check(B.lora_apply_plan_multi(h, plan, descs, inst.scale, sh), "lora_apply_plan_multi")
         B.check(B.lora_plan_destroy(h, plan))
 
+    # one cold call of the one-call form (index + upload + apply; first launch of the kernels in this process)
+    torch.cuda.synchronize()
+    t_c = time.perf_counter()
+    B.check(B.lora_apply(h, 0, 0, xs[0][inst.projs[0].x_key].data_ptr(), ys[0][0].data_ptr(), inst.T, inst.seg_offsets,
+                         pi.seg_slot, pi.seg_rank, inst.scale, sh), "lora_apply")
+    torch.cuda.synchronize()
+    cold_call_us = (time.perf_counter() - t_c) * 1e6
+
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
@@ -133,6 +142,36 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / steps
     ms_per_layer = ms_per_step / n_layers
     tokens_per_s = inst.T / (ms_per_layer * 1e-3)
+
+    # the same steps once more, each between two events: spread of the step time
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record(stream)
+    for s in range(steps):
+        step(args.warmup + s)
+        evs[s + 1].record(stream)
+    torch.cuda.synchronize()
+    per_layer_us = np.sort([evs[i].elapsed_time(evs[i + 1]) * 1e3 / n_layers for i in range(steps)])
+    spread = {"p10": float(per_layer_us[int(0.1 * (steps - 1))]), "median": float(np.median(per_layer_us)),
+              "p90": float(per_layer_us[int(0.9 * (steps - 1))])}
+
+    # host side of a step: indexing alone, and plan creation (index + validation + staging + enqueue of the upload)
+    def host_us(fn, n=50):
+        ts = []
+        for _ in range(n):
+            t1 = time.perf_counter()
+            fn()
+            ts.append((time.perf_counter() - t1) * 1e6)
+        return float(np.median(ts))
+
+    index_us = host_us(lambda: B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS, counts_only=True))
+
+    def make_and_drop_plan():
+        rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
+        B.check(rc)
+        B.check(B.lora_plan_destroy(h, plan))
+
+    plan_us = host_us(make_and_drop_plan)
+    torch.cuda.synchronize()
 
     # the work lists the library's plan holds (for the byte counts): same indexer, same thresholds
     rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, args.mfma_min_tokens or B.LORA_MFMA_MIN_TOKENS)
@@ -170,6 +209,54 @@ def main() -> int:
             "avg_launch_us": kernels[dom]["avg_us"], "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
         }
 
+    # stress only: adapters that miss are loaded from pinned host memory on a side stream while the applies run.
+    # Loaded here are pool adapters the batch does not name (no ordering between the two streams), over and over,
+    # for as long as a few steps take; reported: the fill rate alone and overlapped, the step time overlapped.
+    fill_overlap = None
+    if args.workload == "stress":
+        unused = [a for a in range(len(inst.ranks)) if a not in set(int(u) for u in inst.used_adapters())][:6]
+        host = []
+        for a in unused:
+            for p in range(n_proj):
+                A, Bm = inst.adapter_weights(a, p)
+                host.append((a, p, torch.from_numpy(A).to(torch.bfloat16).pin_memory(), torch.from_numpy(Bm).to(torch.bfloat16).pin_memory()))
+        side = torch.cuda.Stream()
+        part_bytes = sum((ta.numel() + tb.numel()) * 2 for _, _, ta, tb in host) * n_layers
+
+        def enqueue_fills(rounds):
+            for _ in range(rounds):
+                for a, p, ta, tb in host:
+                    for l in range(n_layers):
+                        B.check(B.lora_cache_fill_slot(h, int(pi.slot_of[a]), int(inst.adapter_ids[a]), int(inst.ranks[a]),
+                                                       float(inst.alpha[a]), l, p, ta.data_ptr(), tb.data_ptr(), side.cuda_stream))
+
+        def timed(fill_rounds, n_steps):
+            torch.cuda.synchronize()
+            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            f0.record(side)
+            a0.record(stream)
+            enqueue_fills(fill_rounds)
+            f1.record(side)
+            for s_ in range(n_steps):
+                step(s_)
+            a1.record(stream)
+            torch.cuda.synchronize()
+            return f0.elapsed_time(f1), a0.elapsed_time(a1)
+
+        enqueue_fills(1)  # binds the slots, creates their events
+        fill_alone_ms, _ = timed(2, 0)
+        _, apply_alone_ms = timed(0, 6)
+        rounds = max(1, int(round(2 * apply_alone_ms / fill_alone_ms)))  # about as much fill time as 6 steps take
+        fill_ov_ms, apply_ov_ms = timed(rounds, 6)
+        fill_overlap = {
+            "adapters": len(unused), "bytes_per_round": part_bytes,
+            "fill_GBs_alone": 2 * part_bytes / (fill_alone_ms * 1e-3) / 1e9,
+            "fill_GBs_overlapped": rounds * part_bytes / (fill_ov_ms * 1e-3) / 1e9,
+            "ms_per_layer_alone": apply_alone_ms / 6 / n_layers, "ms_per_layer_overlapped": apply_ov_ms / 6 / n_layers,
+            "apply_slowdown": apply_ov_ms / apply_alone_ms,
+        }
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -199,10 +286,12 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
                    "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
-                   "ms_per_layer": ms_per_layer,
+                   "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
+                   "host_index_us": index_us, "host_plan_create_us": plan_us,
                    "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "fill_overlap": fill_overlap,
         "layer": {"algorithmic_bytes": step_bytes, "flops": step_flops, "achieved_GBs": step_bytes / (ms_per_layer * 1e-3) / 1e9,
                   "hbm_frac": step_bytes / (ms_per_layer * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "achieved_TFLOPs": step_flops / (ms_per_layer * 1e-3) / 1e12, "setup_s": t_setup},

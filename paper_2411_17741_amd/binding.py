@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "liblora_cache.so")
 LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND = 0, -1, -2, -3, -4, -5
 LORA_F32, LORA_BF16 = 0, 1
 LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
-LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV = 1, 2, 4
+LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV, LORA_CACHE_DIRECT_FILL = 1, 2, 4, 8
 LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS, LORA_MFMA_MIN_TOKENS_MIXED = 128, 64, 16, 8
 
 
@@ -217,13 +217,19 @@ def _items(ptr, n):
     return [tuple(getattr(ptr[i], f) for f in ("tok_off", "n_tok", "slot", "rank", "a", "b")) for i in range(n)]
 
 
-def lora_index(T: int, seg_offsets, seg_slot, seg_rank, mfma_min_tokens: int):
-    """-> (status, dict of python lists with the same keys as the C struct)"""
+def lora_index(T: int, seg_offsets, seg_slot, seg_rank, mfma_min_tokens: int, counts_only: bool = False):
+    """-> (status, dict of python lists with the same keys as the C struct); with counts_only the
+    lists are not copied out, only their lengths (what a timing of the call itself wants)"""
     so, ss, sr = _i32(seg_offsets), _i32(seg_slot), _i32(seg_rank)
     w = lora_worklists_t()
     rc = _lib.lora_index(T, _ptr(so), _ptr(ss), _ptr(sr), len(ss), mfma_min_tokens, ctypes.byref(w))
     if rc != LORA_OK:
         return rc, None
+    if counts_only:
+        out = {"n_tok_list": w.n_tok_list, "n_tiles": w.n_tiles, "n_groups": w.n_groups, "n_gs_items": w.n_gs_items,
+               "n_ge_items": w.n_ge_items}
+        _lib.lora_worklists_free(ctypes.byref(w))
+        return rc, out
     out = {
         "tok_list": [w.tok_list[i] for i in range(w.n_tok_list)],
         "tiles": _items(w.tiles, w.n_tiles),

@@ -48,7 +48,7 @@ struct Slot {
 
 struct Stage {
     char *dev = nullptr;
-    hipEvent_t ev = nullptr;
+    hipEvent_t ev = nullptr;  // the repack that read this buffer is done: it may be overwritten
     bool pending = false;
 };
 
@@ -96,6 +96,7 @@ struct lora_cache {
     std::vector<lora_plan> plans;  // user plans first, then the internal ring
     uint64_t internal_next = 0;
     Stage stage[N_STAGES];
+    bool direct_fill = false;
     uint64_t stage_next = 0;
 
     bool fencing = true;
@@ -152,6 +153,7 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.mfma_min_auto = cfg->dtype == LORA_BF16 && cfg->mfma_min_tokens == 0;
     c.flags = cfg->flags;
     c.host_only = (cfg->flags & LORA_CACHE_HOST_ONLY) != 0;
+    c.direct_fill = (cfg->flags & LORA_CACHE_DIRECT_FILL) != 0;
     c.fused_gemv = (cfg->flags & LORA_CACHE_SPLIT_GEMV) ? 0 : ((cfg->flags & LORA_CACHE_FUSED_GEMV) ? 2 : 1);
 
     const int n_proj = cfg->n_proj, n_cls = cfg->n_classes;
@@ -584,20 +586,23 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
             HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
         }
         char *slab = slab_ptr(*c, layer, proj, slot);
-        const void *dev_A = device_view_of_pinned(host_A), *dev_B = device_view_of_pinned(host_B);
+        const void *dev_A = c->direct_fill ? device_view_of_pinned(host_A) : nullptr;
+        const void *dev_B = c->direct_fill ? device_view_of_pinned(host_B) : nullptr;
         if (dev_A && dev_B && ((reinterpret_cast<uintptr_t>(dev_A) | reinterpret_cast<uintptr_t>(dev_B)) & 15) == 0) {
-            // pinned host memory is mapped into the device's address space: the repack kernels read
-            // it over PCIe themselves, which saves two copies through a staging buffer and, more
-            // to the point for small parts, the switches between the copy engine and the compute
-            // queue (a part then costs one or two kernel launches)
-            HIP_TRY(lora::launch_repack(c->dtype, dev_A, dev_B, slab, h_in, h_out, rank, st));
+            // pinned host memory is mapped into the device's address space: the repack kernel reads
+            // it over PCIe itself (fastest for a fill that has the device to itself; kernels that
+            // wait on PCIe reads slow concurrent applies down far more than copy engines do)
+            HIP_TRY(lora::launch_repack(c->dtype, dev_A, dev_B, slab, h_in, h_out, rank, true, st));
         } else {
+            // copy engine -> staging buffer -> repack, all on the caller's stream.  (Copies on a
+            // stream of the cache's own, to overlap them with the repack of the part before, made
+            // every call block on the host for ~300 us with this runtime.)
             Stage &sg = c->stage[c->stage_next++ % N_STAGES];
             if (sg.pending) HIP_TRY(hipStreamWaitEvent(st, sg.ev, 0));
             char *stage_b = sg.dev + align_up(bytes_a);
             HIP_TRY(hipMemcpyAsync(sg.dev, host_A, bytes_a, hipMemcpyHostToDevice, st));
             HIP_TRY(hipMemcpyAsync(stage_b, host_B, bytes_b, hipMemcpyHostToDevice, st));
-            HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, st));
+            HIP_TRY(lora::launch_repack(c->dtype, sg.dev, stage_b, slab, h_in, h_out, rank, false, st));
             HIP_TRY(hipEventRecord(sg.ev, st));
             sg.pending = true;
         }

@@ -90,8 +90,9 @@ hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_ti
                               float *part, hipStream_t st, const KernelTimer *tm);
 int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
-// staged [h_in][r] / [r][h_out] -> slab layout
-hipError_t launch_repack(int dtype, const void *stage_A, const void *stage_B, void *slab, int32_t h_in, int32_t h_out,
-                         int32_t rank, hipStream_t st);
+// A [h_in][r] / B [r][h_out] (16-byte aligned; device memory, or pinned host memory as the device
+// sees it: from_host) -> slab layout
+hipError_t launch_repack(int dtype, const void *src_A, const void *src_B, void *slab, int32_t h_in, int32_t h_out,
+                         int32_t rank, bool from_host, hipStream_t st);
 
 }  // namespace lora

@@ -291,14 +291,15 @@ def test_apply_errors():
         pi.close()
 
 
-def test_fill_from_pageable_memory_gives_the_same_slabs():
-    """Pinned host memory is read by the repack kernel directly over PCIe; any other host
-    memory goes through a staging copy first.  Same bytes in the pool either way."""
+def test_fill_paths_give_the_same_slabs():
+    """A part reaches its slot through a staging copy (from pinned or from pageable host memory)
+    or, with LORA_CACHE_DIRECT_FILL, straight from pinned host memory read by the repack kernel.
+    Same bytes in the pool every way; more parts than staging buffers in flight."""
     B, H = _mods()
-    inst = _custom_instance([3, 20, 1, 70], [0, 1, 2, 3], [7, 16, 64, 128], h_in=320, h_out=448, seed=21)
+    inst = _custom_instance([3, 20, 1, 70, 2, 5], [0, 1, 2, 3, 4, 5], [7, 16, 64, 128, 1, 100], h_in=320, h_out=448, seed=21)
     outs = []
-    for pinned in (True, False):
-        pi = H.PooledInstance(inst, adapters=[])
+    for pinned, flags in ((True, 0), (False, 0), (True, B.LORA_CACHE_DIRECT_FILL)):
+        pi = H.PooledInstance(inst, adapters=[], flags=flags)
         try:
             keep = []
             for a in range(len(inst.ranks)):
@@ -318,7 +319,7 @@ def test_fill_from_pageable_memory_gives_the_same_slabs():
             outs.append(yd.float().cpu().numpy())
         finally:
             pi.close()
-    assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
     ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
     _check(H.error_metrics(outs[0], ref, base), "bf16", "fill paths")
 
