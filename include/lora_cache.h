@@ -217,9 +217,11 @@ int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p);
 int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
                     void *base_out, float scale, void *stream);
 
-/* The same for a list of (layer, projection, x, base_out): descs[0..n) are applied in order
- * on `stream`, as n calls of lora_apply_plan would (one iteration's worth of applies with a
- * single trip through the binding).  Nothing is enqueued if any entry fails validation. */
+/* The same for a list of (layer, projection, x, base_out): the result is that of n calls of
+ * lora_apply_plan in order on `stream` (one iteration's worth of applies with a single trip
+ * through the binding).  Up to 4 consecutive entries that read the same x (q, k, v; gate, up) and
+ * do not write into it are run shrink-first -- one pass over x for all of them, then their updates
+ * of base_out.  Nothing is enqueued if any entry fails validation. */
 typedef struct {
     int32_t layer, proj;
     const void *x;  /* device [T][h_in] */

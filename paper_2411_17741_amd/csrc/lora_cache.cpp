@@ -27,6 +27,7 @@ constexpr int N_STAGES = 2;
 constexpr int N_APPLY_EVENTS = 64;
 constexpr size_t ALIGN = 256;
 constexpr int MAX_K_SPLITS = 8;
+constexpr int N_VSETS = lora::MAX_SHRINK_PROJS;  // applies that share their input run shrink-first, each with its own intermediate
 
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
 int esize_of(int dtype) { return dtype == LORA_BF16 ? 2 : 4; }
@@ -85,7 +86,7 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
-    size_t off_fault = 0, off_vpart = 0, off_vtag = 0;
+    size_t off_fault = 0, off_vpart = 0, off_vtag = 0, v_set_bytes = 0, vpart_set_bytes = 0;
     uint32_t tag_epoch = 0;  // fused GEMV launches so far; the tag of the words of the latest one
     int64_t vpart_rows = 0;  // rows of the k-split partial scratch
     int fused_gemv = 0;  // 0 never, 1 by size, 2 always
@@ -195,11 +196,13 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.off_fault = cur;
     cur += ALIGN;
     c.off_v = cur;
-    cur += align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
+    c.v_set_bytes = align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
+    cur += c.v_set_bytes * N_VSETS;
     // k-split partials: splits are only used while tiles * splits stays near 512 blocks of 64 tokens
     c.vpart_rows = c.dtype == LORA_BF16 ? std::min<int64_t>((int64_t)MAX_K_SPLITS * c.max_tokens, 640 * 64 + c.max_tokens) : 0;
     c.off_vpart = cur;
-    cur += align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
+    c.vpart_set_bytes = align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
+    cur += c.vpart_set_bytes * N_VSETS;
     // fused GEMV launches hand v over as tagged 64-bit words, one row per token
     c.off_vtag = cur;
     cur += c.fused_gemv ? align_up(sizeof(uint64_t) * (size_t)c.max_tokens * c.v_stride) : 0;
@@ -795,8 +798,11 @@ static int validate_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_
 // shrink items up to which the one-launch GEMV form is chosen (measured: above, two launches win)
 constexpr int FUSED_GEMV_MAX_ITEMS = 2048;
 
-static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
-                         float scale, hipStream_t st)
+// Applies descs[0 .. n), n <= N_VSETS: one projection, or several that read the same x and do not
+// write to it.  Those run shrink-first, each with its own copy of the intermediate buffers: one
+// tile-shrink launch for all of them (x is then fetched from memory once), their GEMV launches,
+// then their expands.
+static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int n, float scale, hipStream_t st)
 {
     for (int32_t sl : p->slots) {
         Slot &s = c->slots[sl];
@@ -805,49 +811,77 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
             else HIP_TRY(hipStreamWaitEvent(st, s.fill_ev, 0));
         }
     }
-
-    lora::ApplyArgs a;
-    a.proj_base = c->pool + (size_t)layer * c->layer_stride + c->proj_off[proj];
-    a.row_bytes = (int64_t)c->row_bytes[proj];
-    a.tok_list = reinterpret_cast<const int32_t *>(p->dev);
-    a.x = x;
-    a.y = base_out;
-    a.v = reinterpret_cast<float *>(c->pool + c->off_v);
-    a.h_in = c->proj[proj].h_in;
-    a.h_out = c->proj[proj].h_out;
-    a.v_stride = c->v_stride;
-    a.scale = scale;
+    const lora::KernelTimer timer{c, timer_pair};
+    const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
     const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(p->dev + p->off_tiles);
     const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
     const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
 
-    const lora::KernelTimer timer{c, timer_pair};
-    const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
-    const int splits = p->n_tiles > 0 ? choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in) : 1;
-    HIP_TRY(lora::launch_mfma_shrink(a, tiles, p->n_tiles, p->n_tile_tok, splits,
-                                     reinterpret_cast<float *>(c->pool + c->off_vpart), st, tm));
+    lora::ApplyArgs a[N_VSETS];
+    lora::ShrinkProjs ps;
+    ps.n = n;
+    for (int i = 0; i < n; ++i) {
+        const int32_t proj = descs[i].proj;
+        a[i].proj_base = c->pool + (size_t)descs[i].layer * c->layer_stride + c->proj_off[proj];
+        a[i].row_bytes = (int64_t)c->row_bytes[proj];
+        a[i].tok_list = reinterpret_cast<const int32_t *>(p->dev);
+        a[i].x = descs[i].x;
+        a[i].y = descs[i].base_out;
+        a[i].v = reinterpret_cast<float *>(c->pool + c->off_v + (size_t)i * c->v_set_bytes);
+        a[i].h_in = c->proj[proj].h_in;
+        a[i].h_out = c->proj[proj].h_out;
+        a[i].v_stride = c->v_stride;
+        a[i].scale = scale;
+        ps.proj_base[i] = a[i].proj_base;
+        ps.row_bytes[i] = a[i].row_bytes;
+        ps.v[i] = a[i].v;
+        ps.part[i] = reinterpret_cast<float *>(c->pool + c->off_vpart + (size_t)i * c->vpart_set_bytes);
+    }
+    for (int i = n; i < N_VSETS; ++i) {
+        ps.proj_base[i] = nullptr;
+        ps.row_bytes[i] = 0;
+        ps.v[i] = ps.part[i] = nullptr;
+    }
     // (after 2^32 - 1 fused launches the numbers would repeat: two launches from then on)
     // one launch pays off while the GEMV part is small enough for the launch gap to matter
-    const bool fused = p->n_gs > 0 && c->tag_epoch != UINT32_MAX &&
+    const bool fused = p->n_gs > 0 && c->tag_epoch < UINT32_MAX - N_VSETS &&
                        (c->fused_gemv == 2 || (c->fused_gemv == 1 && p->n_gs <= FUSED_GEMV_MAX_ITEMS));
-    if (fused) {
-        ++c->tag_epoch;
-        HIP_TRY(lora::launch_gemv_fused(c->dtype, a, gs, p->n_gs, ge, p->n_ge,
-                                        reinterpret_cast<unsigned long long *>(c->pool + c->off_vtag), c->tag_epoch,
-                                        reinterpret_cast<int32_t *>(c->pool + c->off_fault), st, tm));
-    } else {
-        HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));
-    }
-    HIP_TRY(lora::launch_mfma_expand(a, tiles, p->n_tiles, st, tm));
-    if (!fused) HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st, tm));
 
-    const int64_t seq = ++c->apply_seq;
-    ++c->stats.applies;
-    for (int32_t sl : p->slots) {
-        c->slots[sl].last_used = seq;
-        ++c->slots[sl].use_count;
+    // everything that reads x
+    if (p->n_tiles > 0) {
+        // the scratch of the partials is sized for about 640 blocks of 64 tokens per projection
+        const int splits = choose_k_splits(*c, p->n_tiles * n, p->n_tile_tok, a[0].h_in);
+        HIP_TRY(lora::launch_mfma_shrink(a[0], ps, tiles, p->n_tiles, p->n_tile_tok, splits, st, tm));
+    }
+    for (int i = 0; i < n; ++i) {
+        if (fused) {
+            ++c->tag_epoch;
+            HIP_TRY(lora::launch_gemv_fused(c->dtype, a[i], gs, p->n_gs, ge, p->n_ge,
+                                            reinterpret_cast<unsigned long long *>(c->pool + c->off_vtag), c->tag_epoch,
+                                            reinterpret_cast<int32_t *>(c->pool + c->off_fault), st, tm));
+        } else {
+            HIP_TRY(lora::launch_gemv_shrink(c->dtype, a[i], gs, p->n_gs, st, tm));
+        }
+    }
+    // the updates of base_out
+    for (int i = 0; i < n; ++i) {
+        HIP_TRY(lora::launch_mfma_expand(a[i], tiles, p->n_tiles, st, tm));
+        if (!fused) HIP_TRY(lora::launch_gemv_expand(c->dtype, a[i], ge, p->n_ge, st, tm));
+        const int64_t seq = ++c->apply_seq;
+        ++c->stats.applies;
+        for (int32_t sl : p->slots) {
+            c->slots[sl].last_used = seq;
+            ++c->slots[sl].use_count;
+        }
     }
     return LORA_OK;
+}
+
+static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
+                         float scale, hipStream_t st)
+{
+    const lora_apply_desc_t d{layer, proj, x, base_out};
+    return enqueue_group(c, p, &d, 1, scale, st);
 }
 
 // One event pair per call (not per apply): fills that come later wait for it.
@@ -883,9 +917,24 @@ int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc
         const int rc = validate_apply(c, p, descs[i].layer, descs[i].proj, descs[i].x, descs[i].base_out);
         if (rc != LORA_OK) return rc;
     }
-    for (int32_t i = 0; i < n; ++i) {
-        const int rc = enqueue_apply(c, p, descs[i].layer, descs[i].proj, descs[i].x, descs[i].base_out, scale, st);
+    // runs of applies that read the same x (q, k, v; gate, up) and do not write to it go as a group
+    const size_t e = c->esize;
+    for (int32_t i = 0; i < n;) {
+        int32_t g = 1;
+        const char *x0 = static_cast<const char *>(descs[i].x);
+        const size_t x_bytes = (size_t)p->T * c->proj[descs[i].proj].h_in * e;
+        auto writes_x = [&](const lora_apply_desc_t &d) {
+            const char *y0 = static_cast<const char *>(d.base_out);
+            return y0 < x0 + x_bytes && x0 < y0 + (size_t)p->T * c->proj[d.proj].h_out * e;
+        };
+        if (!writes_x(descs[i])) {
+            while (g < N_VSETS && i + g < n && descs[i + g].x == descs[i].x &&
+                   c->proj[descs[i + g].proj].h_in == c->proj[descs[i].proj].h_in && !writes_x(descs[i + g]))
+                ++g;
+        }
+        const int rc = enqueue_group(c, p, descs + i, g, scale, st);
         if (rc != LORA_OK) return rc;
+        i += g;
     }
     return n > 0 ? fence_applies(c, p, st) : LORA_OK;
 }

@@ -84,10 +84,21 @@ hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *ite
 // int32) is set if a wait gives up
 hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
                              unsigned long long *vtag, uint32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
-// n_tile_tok = tokens of all tiles (the leading part of tok_list); part = scratch for k-split
-// partials, splits * n_tile_tok rows of v_stride floats (unused when the launch does not split)
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int n_tile_tok, int k_splits,
-                              float *part, hipStream_t st, const KernelTimer *tm);
+// The projections one tile-shrink launch serves (they read the same x): slab base and row pitch,
+// destination of the intermediate, scratch for k-split partials (splits * n_tile_tok rows of
+// v_stride floats each, unused when the launch does not split).
+constexpr int MAX_SHRINK_PROJS = 4;
+struct ShrinkProjs {
+    int n;
+    const char *proj_base[MAX_SHRINK_PROJS];
+    int64_t row_bytes[MAX_SHRINK_PROJS];
+    float *v[MAX_SHRINK_PROJS];
+    float *part[MAX_SHRINK_PROJS];
+};
+// n_tile_tok = tokens of all tiles (the leading part of tok_list); proj_base, row_bytes and v of
+// `a` are ignored (taken from ps)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, int n_tile_tok,
+                              int k_splits, hipStream_t st, const KernelTimer *tm);
 int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
 // A [h_in][r] / B [r][h_out] (16-byte aligned; device memory, or pinned host memory as the device

@@ -38,6 +38,7 @@ constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the st
 //    partial to a scratch row set of its split and mfma_reduce_kernel adds the splits up.
 // Blocks are numbered so that the splits of a tile and neighbouring tiles (same segment, same
 // At) fall on one XCD: block b works on item (b % 8) * ceil(n/8) + b / 8.
+// One launch can serve several projections that read the same x (q, k, v; gate, up).
 // ---------------------------------------------------------------------------------------
 namespace {
 constexpr int SK = 128;                 // k elements per stage
@@ -204,24 +205,31 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     }
 }
 
-__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_tiles,
-                                                          int splits, int k_len, float *part, int n_tile_tok)
+__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, ShrinkProjs ps, const DevItem *__restrict__ tiles,
+                                                          int n_tiles, int splits, int k_len, int n_tile_tok)
 {
     __shared__ __attribute__((aligned(16))) unsigned char xs[NSTAGE][LORA_TILE_TOKENS * XROW];
     static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the k-split reduction reuses the x ring");
 
-    const int n_items = n_tiles * splits;
+    // item = ((tile, split), projection), projection innermost: the blocks that read the same part
+    // of x for the projections of a group are neighbours in the dispatch order of one XCD and
+    // walk k in the same order, so that x is fetched from memory once and found in L2 by the others
+    const int n_items = n_tiles * splits * ps.n;
     const int per_xcd = (n_items + 7) >> 3;
     const int item = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (item >= n_items) return;  // uniform
-    const int tile = item / splits, split = item - tile * splits;
+    const int ts = item / ps.n, pj = item - ts * ps.n;
+    const int tile = ts / splits, split = ts - tile * splits;
     const DevItem it = tiles[tile];
     const int k_begin = split * k_len;
     const int k_end = min(a.h_in, k_begin + k_len);
     if (k_begin >= k_end) return;
+    a.proj_base = ps.proj_base[pj];
+    a.row_bytes = ps.row_bytes[pj];
+    a.v = ps.v[pj];
     const int n_st = (k_end - k_begin + SK - 1) / SK;
-    const int phase = (int)(((unsigned)item * 5u) % (unsigned)n_st);
-    float *my_part = splits > 1 ? part + (size_t)split * n_tile_tok * a.v_stride : nullptr;
+    const int phase = (int)(((unsigned)ts * 5u) % (unsigned)n_st);
+    float *my_part = splits > 1 ? ps.part[pj] + (size_t)split * n_tile_tok * a.v_stride : nullptr;
     const int NB = (it.rank + 15) >> 4;
     if (NB > 4) mfma_shrink_body<true, 2>(a, it, k_begin, k_end, phase, my_part, xs);
     else if (NB == 4) mfma_shrink_body<true, 1>(a, it, k_begin, k_end, phase, my_part, xs);
@@ -232,20 +240,21 @@ __global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, const Dev
 
 // V[token][0..rank) = sum over the k splits of the partials.  One block per tile.  (Atomic adds
 // into V instead cost about 30 us per launch: device-scope fp32 atomics execute at the memory side.)
-__global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int splits,
-                                                          const float *__restrict__ part, int n_tile_tok)
+__global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkProjs ps, const DevItem *__restrict__ tiles,
+                                                          int splits, int n_tile_tok)
 {
-    // 8 blocks per tile, 8 tokens each; a thread sums one float4 column of one token
+    // 8 blocks per tile (and projection of the group: blockIdx.y), 8 tokens each; a thread sums one
+    // float4 column of one token
     const DevItem it = tiles[blockIdx.x >> 3];
     const int ti = (blockIdx.x & 7) * 8 + (threadIdx.x >> 5), j4 = threadIdx.x & 31;
     if (ti >= it.n_tok || j4 * 4 >= rank_storage(it.rank)) return;  // entries past the rank are never used
-    const float4 *src = reinterpret_cast<const float4 *>(part + (size_t)(it.tok_off + ti) * a.v_stride) + j4;
+    const float4 *src = reinterpret_cast<const float4 *>(ps.part[blockIdx.y] + (size_t)(it.tok_off + ti) * a.v_stride) + j4;
     float4 sum = src[0];
     for (int sp = 1; sp < splits; ++sp) {
         const float4 v = src[(size_t)sp * n_tile_tok * (a.v_stride >> 2)];
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
-    reinterpret_cast<float4 *>(a.v + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride)[j4] = sum;
+    reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride)[j4] = sum;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -418,18 +427,18 @@ int mfma_shrink_splits(int h_in, int want)
     return (h_in + k_len - 1) / k_len;
 }
 
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const DevItem *tiles, int n_tiles, int n_tile_tok, int k_splits,
-                              float *part, hipStream_t st, const KernelTimer *tm)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, int n_tile_tok,
+                              int k_splits, hipStream_t st, const KernelTimer *tm)
 {
-    if (n_tiles <= 0) return hipSuccess;
+    if (n_tiles <= 0 || ps.n <= 0) return hipSuccess;
     const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
     const int splits = (a.h_in + k_len - 1) / k_len;
-    const int n_items = n_tiles * splits;
+    const int n_items = n_tiles * splits * ps.n;
     const int blocks = ((n_items + 7) / 8) * 8;  // 8 equal XCD shares
-    launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(blocks), dim3(256), st, a, tiles, n_tiles, splits, k_len,
-             part, n_tile_tok);
+    launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(blocks), dim3(256), st, a, ps, tiles, n_tiles, splits, k_len,
+             n_tile_tok);
     if (splits > 1)
-        launch_k(tm, LORA_K_MFMA_REDUCE, mfma_reduce_kernel, dim3(n_tiles * 8), dim3(256), st, a, tiles, splits, (const float *)part,
+        launch_k(tm, LORA_K_MFMA_REDUCE, mfma_reduce_kernel, dim3(n_tiles * 8, ps.n), dim3(256), st, a, ps, tiles, splits,
                  n_tile_tok);
     return hipGetLastError();
 }

@@ -324,6 +324,51 @@ def test_fill_paths_give_the_same_slabs():
     _check(H.error_metrics(outs[0], ref, base), "bf16", "fill paths")
 
 
+def test_multi_apply_groups_projections_that_share_their_input():
+    """q, k, v read one x: the list form runs one tile-shrink launch for all of them, then their
+    expands.  Results must be those of one apply after the other -- also when one of the outputs
+    is the shared input itself (then nothing may be reordered) -- for both GEMV launch forms, with
+    and without k splits."""
+    B, H = _mods()
+    base_inst = wl.small_mixed(seed=9)
+    projs = [wl.Projection("q", 512, 512, 0), wl.Projection("k", 512, 256, 0), wl.Projection("v", 512, 384, 0),
+             wl.Projection("o", 384, 512, 1), wl.Projection("g", 512, 640, 2), wl.Projection("u", 512, 640, 2),
+             wl.Projection("w", 2048, 256, 3), wl.Projection("z", 2048, 320, 3)]
+    inst = wl.Instance(name="qkv", dtype="bf16", seed=9, projs=projs, ranks=base_inst.ranks, adapter_ids=base_inst.adapter_ids,
+                       alpha=base_inst.alpha, scale=base_inst.scale, seg_offsets=base_inst.seg_offsets,
+                       seg_adapter=base_inst.seg_adapter)
+    for flags in (B.LORA_CACHE_FUSED_GEMV, B.LORA_CACHE_SPLIT_GEMV):
+        pi = H.PooledInstance(inst, flags=flags)
+        try:
+            plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+            sh = torch.cuda.current_stream().cuda_stream
+            xs = {pr.x_key: H.to_device(inst.x(p), pi.dtype) for p, pr in enumerate(projs)}
+            ys = [H.to_device(inst.base_out(p), pi.dtype) for p in range(len(projs))]
+            descs = B.make_descs([(0, p, xs[pr.x_key].data_ptr(), ys[p].data_ptr()) for p, pr in enumerate(projs)])
+            B.check(B.lora_apply_plan_multi(pi.pool.handle, plan, descs, inst.scale, sh))
+            pi.pool.check_fault()
+            ads = lambda p: _oracle_adapters(inst, p, inst.used_adapters())
+            for p in range(len(projs)):
+                ref = oracle.lora_apply(inst.x(p), inst.base_out(p), inst.seg_offsets, inst.seg_adapter, ads(p), inst.scale)
+                _check(H.error_metrics(ys[p].float().cpu().numpy(), ref, inst.base_out(p)), "bf16", f"grouped proj {p}")
+
+            # q writes into the shared input: k must then see the updated x, as in sequential order
+            x0 = inst.x(0)
+            xq = H.to_device(x0, pi.dtype)
+            yk = H.to_device(inst.base_out(1), pi.dtype)
+            descs = B.make_descs([(0, 0, xq.data_ptr(), xq.data_ptr()), (0, 1, xq.data_ptr(), yk.data_ptr())])
+            B.check(B.lora_apply_plan_multi(pi.pool.handle, plan, descs, inst.scale, sh))
+            pi.pool.check_fault()
+            x1 = wl.bf16_round(oracle.lora_apply(x0, x0, inst.seg_offsets, inst.seg_adapter, ads(0), inst.scale).astype(np.float32))
+            got_x1 = xq.float().cpu().numpy()
+            _check(H.error_metrics(got_x1, x1, x0), "bf16", "in-place q")
+            ref_k = oracle.lora_apply(got_x1, inst.base_out(1), inst.seg_offsets, inst.seg_adapter, ads(1), inst.scale)
+            _check(H.error_metrics(yk.float().cpu().numpy(), ref_k, inst.base_out(1)), "bf16", "k after in-place q")
+            pi.pool.plan_destroy(plan)
+        finally:
+            pi.close()
+
+
 def test_plan_reuse_over_projections_and_layers():
     """One plan per iteration, applied to every projection of every layer copy."""
     B, H = _mods()
