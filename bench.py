@@ -41,19 +41,23 @@ DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20}
 
 
 def algorithmic_bytes(inst, w, esize=2):
-    """Bytes each kernel kind must move per launch, per projection: every distinct slab it
-    needs once at its true rank, its tokens' x rows once, its tokens' base_out rows read and
-    written once.  The T x rank intermediate is not counted."""
+    """Bytes each kernel kind must move per projection: every distinct slab it needs once at its
+    true rank, its tokens' x rows once, its tokens' base_out rows read and written once.  The
+    T x rank intermediate is not counted.  Consecutive projections that read the same x share one
+    tile-shrink launch (as lora_apply_plan_multi groups them, up to 4): x counts once per group."""
     tok_n = lambda items: sum(it[1] for it in items)
     slabs = lambda items: {it[2]: it[3] for it in items}
     out = []
-    for pr in inst.projs:
+    group_len = 0
+    for i, pr in enumerate(inst.projs):
+        first_of_group = i == 0 or inst.projs[i - 1].x_key != pr.x_key or group_len == 4
+        group_len = 1 if first_of_group else group_len + 1
         g, t = slabs(w["groups"]), slabs(w["tiles"])
         ng, nt = tok_n(w["groups"]), tok_n(w["tiles"])
         out.append({
             "gemv_shrink": esize * (sum(g.values()) * pr.h_in + ng * pr.h_in),
             "gemv_expand": esize * (sum(g.values()) * pr.h_out + 2 * ng * pr.h_out),
-            "mfma_shrink": esize * (sum(t.values()) * pr.h_in + nt * pr.h_in),
+            "mfma_shrink": esize * (sum(t.values()) * pr.h_in + (nt * pr.h_in if first_of_group else 0)),
             "mfma_expand": esize * (sum(t.values()) * pr.h_out + 2 * nt * pr.h_out),
             "mfma_reduce": 0,
         })

@@ -65,6 +65,7 @@ struct lora_plan {
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
+    int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
     size_t off_tiles = 0, off_gs = 0, off_ge = 0;
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
@@ -315,7 +316,9 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
             d.row = c.slot_row[items[i].slot];
             d.rank = items[i].rank;
             d.a = items[i].a;
-            d.b = items[i].b;
+            d.consecutive = 1;
+            for (int t = 1; t < items[i].n_tok; ++t)
+                if (w.tok_list[items[i].tok_off + t] != w.tok_list[items[i].tok_off] + t) d.consecutive = 0;
             d.alpha = s.alpha;
             d.tok0 = w.tok_list[items[i].tok_off];
             std::memcpy(&items[i], &d, sizeof(d));
@@ -323,6 +326,20 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     };
     p.n_tile_tok = 0;
     for (int i = 0; i < w.n_tiles; ++i) p.n_tile_tok += w.tiles[i].n_tok;
+    // the tile shrink's XCD shares: 8 contiguous runs of tiles of about equal cost, where a tile
+    // costs its x rows plus its At rows (measured: rank 128 takes 1.76x as long as rank 16)
+    {
+        std::vector<int64_t> upto(w.n_tiles + 1, 0);
+        for (int i = 0; i < w.n_tiles; ++i) upto[i + 1] = upto[i] + 2 * w.tiles[i].n_tok + w.tiles[i].rank;
+        p.xcd_tile[0] = 0;
+        for (int j = 1; j < 8; ++j) {
+            const int64_t want = upto[w.n_tiles] * j / 8;
+            int t = p.xcd_tile[j - 1];
+            while (t < w.n_tiles && upto[t + 1] - want <= want - upto[t]) ++t;  // the cut nearest to the share
+            p.xcd_tile[j] = t;
+        }
+        p.xcd_tile[8] = w.n_tiles;
+    }
     auto stamp_gemv = [&](lora_item_t *items, int n, bool expand) {
         for (int i = 0; i < n; ++i) {
             const Slot &s = c.slots[items[i].slot];
@@ -820,6 +837,7 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
     lora::ApplyArgs a[N_VSETS];
     lora::ShrinkProjs ps;
     ps.n = n;
+    for (int j = 0; j < 9; ++j) ps.xcd_tile[j] = p->xcd_tile[j];
     for (int i = 0; i < n; ++i) {
         const int32_t proj = descs[i].proj;
         a[i].proj_base = c->pool + (size_t)descs[i].layer * c->layer_stride + c->proj_off[proj];

@@ -25,7 +25,8 @@ struct DevItem {
     int32_t tok_off, n_tok;  // tokens: tok_list[tok_off .. tok_off+n_tok)
     int32_t row;             // first storage row of the slot
     int32_t rank;
-    int32_t a, b;            // as in lora_item_t
+    int32_t a;               // as in lora_item_t
+    int32_t consecutive;     // 1: the tokens are tok0, tok0+1, ... (a prompt's tile): no lookup in tok_list at all
     float alpha;             // the cache entry's own factor
     int32_t tok0;            // tok_list[tok_off], so one-token items need no second lookup
 };
@@ -90,6 +91,11 @@ hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, 
 constexpr int MAX_SHRINK_PROJS = 4;
 struct ShrinkProjs {
     int n;
+    // tiles [xcd_tile[j], xcd_tile[j+1]) are worked on by the blocks of XCD j: contiguous runs (tiles
+    // of a prompt share At, which then stays in that XCD's L2) of about equal cost (a tile of rank
+    // 128 takes twice as long as one of rank 16; with equal counts the XCD that got a long
+    // high-rank prompt finished last by a factor of two)
+    int xcd_tile[9];
     const char *proj_base[MAX_SHRINK_PROJS];
     int64_t row_bytes[MAX_SHRINK_PROJS];
     float *v[MAX_SHRINK_PROJS];

@@ -12,6 +12,7 @@
 //   expand:  Y[tile][cols]^T += Bp[cols][rank] . (s.V)^T     (split over column ranges)
 //
 // (paper section 3.1: the two adapter products and the aggregation into the base output.)
+#include <algorithm>
 #include <type_traits>
 
 #include "lora_device.h"
@@ -37,7 +38,8 @@ constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the st
 //  - When a tile's k is split over several blocks (few tiles, many CUs), each block writes its
 //    partial to a scratch row set of its split and mfma_reduce_kernel adds the splits up.
 // Blocks are numbered so that the splits of a tile and neighbouring tiles (same segment, same
-// At) fall on one XCD: block b works on item (b % 8) * ceil(n/8) + b / 8.
+// At) fall on one XCD (blocks b, b + 8, ... run on XCD b % 8), each XCD taking a contiguous run of
+// tiles of about equal cost.
 // One launch can serve several projections that read the same x (q, k, v; gate, up).
 // ---------------------------------------------------------------------------------------
 namespace {
@@ -51,6 +53,12 @@ constexpr int NSTAGE = 3;
 // whatever At held there irrelevant).  Loads under a condition would be compiled into branches,
 // and the wait counters cannot be tracked across those: every stage would then wait for all
 // outstanding loads and the prefetch distance would collapse to nothing.
+// token id of row ti (>= 0) of a tile
+__device__ __forceinline__ int tile_token(const ApplyArgs &a, const DevItem &it, int ti)
+{
+    return (it.consecutive || ti == 0) ? it.tok0 + ti : a.tok_list[it.tok_off + ti];
+}
+
 template <bool NSPLIT, int NBW>  // NBW: rank blocks (of 16) a wavefront works on
 __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevItem &it, int k_begin, int k_end, int phase,
                                                  float *part, unsigned char (*xs)[LORA_TILE_TOKENS * XROW])
@@ -83,7 +91,7 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     for (int i = 0; i < 4; ++i) {
         const int row = 16 * w + 4 * i + (lane >> 4);
         x_ok[i] = row < it.n_tok;
-        const int tok = x_ok[i] ? (row == 0 ? it.tok0 : a.tok_list[it.tok_off + row]) : it.tok0;
+        const int tok = x_ok[i] ? tile_token(a, it, row) : it.tok0;
         xg[i] = x + (size_t)tok * a.h_in;
         lds_off[i] = row * XROW + lp * 16;
     }
@@ -173,7 +181,7 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
                 // whole k range in this block: the result itself; else this split's partial, one row
                 // per position in tok_list (mfma_reduce_kernel adds the splits up)
                 if (part) part[(size_t)(it.tok_off + ti) * a.v_stride + jr] = val[r];
-                else a.v[(size_t)(ti == 0 ? it.tok0 : a.tok_list[it.tok_off + ti]) * a.v_stride + jr] = val[r];
+                else a.v[(size_t)tile_token(a, it, ti) * a.v_stride + jr] = val[r];
             }
         }
     };
@@ -211,14 +219,14 @@ __global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, ShrinkPro
     __shared__ __attribute__((aligned(16))) unsigned char xs[NSTAGE][LORA_TILE_TOKENS * XROW];
     static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the k-split reduction reuses the x ring");
 
-    // item = ((tile, split), projection), projection innermost: the blocks that read the same part
-    // of x for the projections of a group are neighbours in the dispatch order of one XCD and
-    // walk k in the same order, so that x is fetched from memory once and found in L2 by the others
-    const int n_items = n_tiles * splits * ps.n;
-    const int per_xcd = (n_items + 7) >> 3;
-    const int item = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (item >= n_items) return;  // uniform
-    const int ts = item / ps.n, pj = item - ts * ps.n;
+    // XCD j = blockIdx % 8 works on the tiles [xcd_tile[j], xcd_tile[j+1]); its i-th block on item i of
+    // ((tile, split), projection), projection innermost: the blocks that read the same part of x
+    // for the projections of a group are neighbours in the dispatch order of one XCD and walk k in
+    // the same order, so that x is fetched from memory once and found in L2 by the others
+    const int xcd = (int)blockIdx.x & 7, local = (int)blockIdx.x >> 3;
+    const int per_tile = splits * ps.n;
+    if (local >= (ps.xcd_tile[xcd + 1] - ps.xcd_tile[xcd]) * per_tile) return;  // uniform
+    const int ts = ps.xcd_tile[xcd] * splits + local / ps.n, pj = local % ps.n;
     const int tile = ts / splits, split = ts - tile * splits;
     const DevItem it = tiles[tile];
     const int k_begin = split * k_len;
@@ -254,7 +262,7 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkPro
         const float4 v = src[(size_t)sp * n_tile_tok * (a.v_stride >> 2)];
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
-    reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)a.tok_list[it.tok_off + ti] * a.v_stride)[j4] = sum;
+    reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)tile_token(a, it, ti) * a.v_stride)[j4] = sum;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -299,7 +307,7 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     for (int i = 0; i < 4; ++i) {
         const int ti = 32 * th + 8 * i + rt;
         yok[i] = ti < it.n_tok;
-        yoff[i] = (size_t)((yok[i] && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.h_out + rc * 8;
+        yoff[i] = (size_t)(yok[i] ? tile_token(a, it, ti) : it.tok0) * a.h_out + rc * 8;
     }
     const bool half_live = 32 * th < it.n_tok;
     const int col0 = blockIdx.y * n_pass * 128 + 64 * ch;
@@ -331,7 +339,7 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
         const int ti = idx / c8, j8 = idx - ti * c8;
         const bool live = ti < it.n_tok;
         const float4 *vr = reinterpret_cast<const float4 *>(
-            a.v + (size_t)((live && ti > 0) ? a.tok_list[it.tok_off + ti] : it.tok0) * a.v_stride + j8 * 8);
+            a.v + (size_t)(live ? tile_token(a, it, ti) : it.tok0) * a.v_stride + j8 * 8);
         const float4 lo = vr[0], hi = vr[1];
         const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         bf16x8 o;
@@ -433,8 +441,9 @@ hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const D
     if (n_tiles <= 0 || ps.n <= 0) return hipSuccess;
     const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
     const int splits = (a.h_in + k_len - 1) / k_len;
-    const int n_items = n_tiles * splits * ps.n;
-    const int blocks = ((n_items + 7) / 8) * 8;  // 8 equal XCD shares
+    int most = 0;
+    for (int j = 0; j < 8; ++j) most = std::max(most, ps.xcd_tile[j + 1] - ps.xcd_tile[j]);
+    const int blocks = 8 * most * splits * ps.n;  // XCD j takes the blocks j, j + 8, ...
     launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(blocks), dim3(256), st, a, ps, tiles, n_tiles, splits, k_len,
              n_tile_tok);
     if (splits > 1)
