@@ -31,13 +31,14 @@ WORKLOAD_TEXT = {
     "prefill": "prefill: 8 prompts lognormal(6,0.8) in [32,2048], one 4096->4096 bf16 projection, distinct adapters of rank 16/64/128",
     "mixed": "mixed: 224 decode + 32 prompts, 7B-shaped layer (q,k,v,o,gate,up,down) bf16, pool of 500, Zipf(1.2)",
     "stress": "stress: 512 decode + 4x512 prompt tokens, 13B-shaped layer bf16, pool of 1000 in 4 layer copies, Zipf(1.2)",
+    "decode_heavy": "decode_heavy (extra, not one of the task's configurations): 1024 one-token requests, one 4096->4096 bf16 projection, pool of 500 adapters (ranks 8..128), Zipf(1.0)",
 }
 # HBM bytes per launch of a workload's dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs, scaled
 # by what the same counters read for a plain copy; figures and commands in profiles/gemv_fused_decode_traffic.txt).
 # A counter run cannot happen inside this process, so the figure measured for the same command is carried here.
 MEASURED_TRAFFIC = {("decode", "gemv_fused"): 28.15e6}
-DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4}
-DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20}
+DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8}
+DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40}
 
 
 def algorithmic_bytes(inst, w, esize=2):
@@ -177,12 +178,15 @@ def main() -> int:
     plan_us = host_us(make_and_drop_plan)
     torch.cuda.synchronize()
 
-    # the work lists the library's plan holds (for the byte counts): same indexer, same thresholds
-    rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, args.mfma_min_tokens or B.LORA_MFMA_MIN_TOKENS)
+    # the work lists the library's plan holds (for the byte counts): same indexer, the plan's own threshold
+    rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
     B.check(rc)
-    if not args.mfma_min_tokens and w["tiles"]:
-        rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS_MIXED)
-        B.check(rc)
+    rc, plan_info = B.lora_plan_info(plan)
+    B.check(rc)
+    B.check(B.lora_plan_destroy(h, plan))
+    rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, plan_info.mfma_min_tokens)
+    B.check(rc)
+    assert len(w["tiles"]) == plan_info.n_tiles and len(w["gs_items"]) == plan_info.n_gemv_shrink_items
     per_proj = algorithmic_bytes(inst, w)
     step_bytes = sum(sum(b for k, b in v.items() if k != "gemv_fused") for v in per_proj)
     step_flops = sum(2 * it[1] * it[3] * (p.h_in + p.h_out) for p in inst.projs for it in (w["tiles"] + w["groups"]))
@@ -292,7 +296,7 @@ def main() -> int:
                    "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
                    "host_index_us": index_us, "host_plan_create_us": plan_us,
-                   "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},
+                   "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "fill_overlap": fill_overlap,

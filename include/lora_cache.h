@@ -90,8 +90,9 @@ typedef struct {
     int32_t max_tokens;         /* largest T of any apply */
     int32_t max_segments;       /* largest n_seg of any apply */
     int32_t n_plans;            /* plans that may be alive at once (>= 0; 4 more are kept for lora_apply) */
-    int32_t mfma_min_tokens;    /* 0 = default: LORA_MFMA_MIN_TOKENS, lowered to LORA_MFMA_MIN_TOKENS_MIXED for a batch
-                                   that has tiles at the former; ignored (no tile path) for LORA_F32 */
+    int32_t mfma_min_tokens;    /* 0 = default, chosen per batch: no tiles at all if the batch has none at
+                                   LORA_MFMA_MIN_TOKENS or too few for the tile launches to pay off, else
+                                   LORA_MFMA_MIN_TOKENS_MIXED (see lora_plan_info); ignored (no tile path) for LORA_F32 */
     int32_t flags;
 } lora_cache_config_t;
 
@@ -210,6 +211,13 @@ void lora_worklists_free(lora_worklists_t *w);
 int lora_plan_create(lora_cache_t *c, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
                      const int32_t *seg_rank, int32_t n_seg, void *stream, lora_plan_t **out);
 int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p);
+
+/* What a plan holds: the threshold its work lists were made with (lora_index with the same
+ * arrays and this threshold returns the same lists; 0 = no tiles) and their sizes. */
+typedef struct {
+    int32_t T, mfma_min_tokens, n_tiles, n_tile_tokens, n_gemv_shrink_items, n_gemv_expand_items;
+} lora_plan_info_t;
+int lora_plan_info(const lora_plan_t *p, lora_plan_info_t *out);
 
 /* base_out[t] += scale*alpha*(x[t].A).B for the planned batch; x [T][h_in] and base_out
  * [T][h_out] are device, row-major, contiguous, element type cfg.dtype.  Asynchronous on

@@ -59,6 +59,10 @@ class lora_item_t(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in ("tok_off", "n_tok", "slot", "rank", "a", "b", "c", "d")]
 
 
+class lora_plan_info_t(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("T", "mfma_min_tokens", "n_tiles", "n_tile_tokens", "n_gemv_shrink_items", "n_gemv_expand_items")]
+
+
 class lora_apply_desc_t(ctypes.Structure):
     _fields_ = [("layer", c_int32), ("proj", c_int32), ("x", c_void_p), ("base_out", c_void_p)]
 
@@ -96,6 +100,7 @@ _SIGS = {
     "lora_worklists_free": (None, [POINTER(lora_worklists_t)]),
     "lora_plan_create": (c_int, [c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_void_p, POINTER(c_void_p)]),
     "lora_plan_destroy": (c_int, [c_void_p, c_void_p]),
+    "lora_plan_info": (c_int, [c_void_p, POINTER(lora_plan_info_t)]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
     "lora_apply": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_float, c_void_p]),
@@ -251,6 +256,13 @@ def lora_plan_create(cache, T: int, seg_offsets, seg_slot, seg_rank, stream: int
 
 def lora_plan_destroy(cache, plan) -> int:
     return _lib.lora_plan_destroy(cache, plan)
+
+
+def lora_plan_info(plan):
+    """-> (status, lora_plan_info_t)"""
+    info = lora_plan_info_t()
+    rc = _lib.lora_plan_info(plan, ctypes.byref(info))
+    return rc, info
 
 
 def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, scale: float, stream: int = 0) -> int:

@@ -27,6 +27,8 @@ constexpr int N_STAGES = 2;
 constexpr int N_APPLY_EVENTS = 64;
 constexpr size_t ALIGN = 256;
 constexpr int MAX_K_SPLITS = 8;
+constexpr double TILE_PATH_FIXED_US = 25.0;          // what the three launches of the tile path cost beside their work
+constexpr double TILE_PATH_L2_BYTES_PER_US = 10e6;  // rate at which repeated passes over a slab come out of L2
 constexpr int N_VSETS = lora::MAX_SHRINK_PROJS;  // applies that share their input run shrink-first, each with its own intermediate
 
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
@@ -66,6 +68,7 @@ struct lora_plan {
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
     int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
+    int32_t mfma_min_used = 0;  // the threshold the work lists were made with
     size_t off_tiles = 0, off_gs = 0, off_ge = 0;
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
@@ -274,12 +277,30 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     lora_worklists_t w;
     int rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, c.mfma_min, &w);
     if (rc != LORA_OK) return rc;
-    // A batch that has tiles anyway pays for the tile launches already: then smaller pools of
-    // tokens are tiles too (one pass over the slab instead of one per token batch).  A batch
-    // without any stays one GEMV launch.
+    p.mfma_min_used = c.mfma_min;
+    // With the threshold left to the library: the tile path costs three more launches per apply
+    // (about 25 us), which a batch with only a few hundred tile tokens (the pooled tokens of a few
+    // hot adapters in a decode batch) does not earn back -- as GEMV groups those tokens cost one
+    // more pass over their slab per 4 tokens, out of L2.  So: estimate that cost; below the fixed
+    // cost of the tile launches everything stays GEMV; else the batch pays for the tile launches
+    // anyway and smaller pools of tokens become tiles too.
     if (c.mfma_min_auto && w.n_tiles > 0) {
+        double mean_width = 0;
+        for (const auto &pr : c.proj) mean_width += (double)pr.h_in + pr.h_out;
+        mean_width /= (double)c.proj.size();
+        std::unordered_map<int32_t, std::pair<int64_t, int32_t>> of_slot;  // slot -> (tile tokens, rank)
+        for (int i = 0; i < w.n_tiles; ++i) {
+            auto &e = of_slot[w.tiles[i].slot];
+            e.first += w.tiles[i].n_tok;
+            e.second = w.tiles[i].rank;
+        }
+        double extra_bytes = 0;
+        for (const auto &kv : of_slot)
+            extra_bytes += (double)((kv.second.first + LORA_GEMV_BATCH - 1) / LORA_GEMV_BATCH) * kv.second.second * mean_width * c.esize;
+        const double gemv_us = extra_bytes / TILE_PATH_L2_BYTES_PER_US;
         lora_worklists_free(&w);
-        rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, LORA_MFMA_MIN_TOKENS_MIXED, &w);
+        p.mfma_min_used = gemv_us < TILE_PATH_FIXED_US ? 0 : LORA_MFMA_MIN_TOKENS_MIXED;
+        rc = lora_index(T, seg_offsets, seg_slot, seg_rank, n_seg, p.mfma_min_used, &w);
         if (rc != LORA_OK) return rc;
     }
 
@@ -797,6 +818,18 @@ int lora_plan_destroy(lora_cache_t *c, lora_plan_t *p)
     if (!c || !p || p->internal || !p->in_use) return LORA_E_INVAL;
     if (p < c->plans.data() || p >= c->plans.data() + c->n_user_plans) return LORA_E_INVAL;
     p->in_use = false;
+    return LORA_OK;
+}
+
+int lora_plan_info(const lora_plan_t *p, lora_plan_info_t *out)
+{
+    if (!p || !out || !p->in_use) return LORA_E_INVAL;
+    out->T = p->T;
+    out->mfma_min_tokens = p->mfma_min_used;
+    out->n_tiles = p->n_tiles;
+    out->n_tile_tokens = p->n_tile_tok;
+    out->n_gemv_shrink_items = p->n_gs;
+    out->n_gemv_expand_items = p->n_ge;
     return LORA_OK;
 }
 

@@ -20,6 +20,7 @@ from .gen import (  # noqa: F401
     make_instance,
     tiny,
     decode,
+    decode_heavy,
     prefill,
     mixed,
     stress,

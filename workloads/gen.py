@@ -282,6 +282,16 @@ def decode(seed: int = 0, n_layers: int = 1) -> Instance:
     )
 
 
+def decode_heavy(seed: int = 0, n_layers: int = 1) -> Instance:
+    """Not one of the task's configurations: the decode configuration at the size of a loaded
+    server -- 1024 decode tokens, 4096->4096 bf16, pool of 500, Zipf(1.0) -- where one launch moves
+    enough bytes for the bandwidth roof, not launch latency, to be what binds."""
+    return make_instance(
+        "decode_heavy", dtype="bf16", seed=seed, projs=[Projection("q", 4096, 4096, 0)], n_adapters=500,
+        rank_choices=[8, 16, 32, 64, 128], n_decode=1024, prompt_lens=[], zipf_alpha=1.0, n_layers=n_layers,
+    )
+
+
 def prefill(seed: int = 0, n_layers: int = 1) -> Instance:
     """8 prompts, lognormal(6, 0.8) lengths in [32, 2048], distinct adapters of rank {16,64,128}."""
     lens = _prompt_lengths(_rng(seed, _P_LEN), 8)
@@ -329,4 +339,5 @@ CONFIGS = {
     "mixed": mixed,
     "stress": stress,
     "small_mixed": small_mixed,
+    "decode_heavy": decode_heavy,
 }
