@@ -171,6 +171,31 @@ def test_large_decode_batch_takes_the_two_launch_form():
         pi.close()
 
 
+def test_plans_choose_the_tile_threshold_per_batch():
+    """With the threshold left to the library: a pure decode batch has no tiles; a decode batch
+    whose few hot adapters would make a handful of tiles stays all-GEMV (the tile launches would
+    cost more than they save); a batch with prompts takes the lower threshold.  lora_index with the
+    reported threshold reproduces the plan's list sizes."""
+    B, H = _mods()
+    for make, want in ((lambda: wl.decode(), B.LORA_MFMA_MIN_TOKENS), (lambda: wl.decode_heavy(), 0),
+                       (lambda: wl.prefill(), B.LORA_MFMA_MIN_TOKENS_MIXED)):
+        inst = make()
+        pi = H.PooledInstance(inst, adapters=[])   # plans need bound slots only for the named adapters
+        try:
+            pi.fill(inst.used_adapters(), [0])
+            plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+            rc, info = B.lora_plan_info(plan)
+            assert rc == B.LORA_OK and info.T == inst.T and info.mfma_min_tokens == want, (inst.name, info.mfma_min_tokens)
+            rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, info.mfma_min_tokens, counts_only=True)
+            assert (w["n_tiles"], w["n_gs_items"], w["n_ge_items"]) == (info.n_tiles, info.n_gemv_shrink_items, info.n_gemv_expand_items)
+            if want == 0:
+                rc, w16 = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, 16, counts_only=True)
+                assert w16["n_tiles"] > 0 and info.n_tiles == 0
+            pi.pool.plan_destroy(plan)
+        finally:
+            pi.close()
+
+
 def test_refill_waits_for_applies_that_still_read_the_slot():
     """Evict an adapter and load another one into its slot right behind an apply that reads it,
     without any host synchronisation: the first result must come from the old weights, the

@@ -77,14 +77,17 @@ def test_tiny_fp32():
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_small_mixed_all_paths(dtype, seed):
+    """With the tile threshold fixed at 16 (tiles, gathered tiles and GEMV groups all occur) and
+    left to the library (which keeps a batch this small all-GEMV)."""
     inst = wl.small_mixed(seed=seed, dtype=dtype)
     B, H = _mods()
-    pi = H.PooledInstance(inst)
-    try:
-        for p in range(len(inst.projs)):
-            _full_parity(inst, p, pi=pi)
-    finally:
-        pi.close()
+    for m0 in (B.LORA_MFMA_MIN_TOKENS, 0):
+        pi = H.PooledInstance(inst, mfma_min_tokens=m0)
+        try:
+            for p in range(len(inst.projs)):
+                _full_parity(inst, p, pi=pi)
+        finally:
+            pi.close()
 
 
 def test_decode_config():
@@ -152,7 +155,7 @@ def test_integer_inputs_are_bit_exact():
 
     ii.adapter_weights = adapter_weights
     ii.scale = 1.0
-    pi = H.PooledInstance(ii)
+    pi = H.PooledInstance(ii, mfma_min_tokens=16)  # tiles, gathered tiles and GEMV groups
     try:
         for p in range(len(ii.projs)):
             x = rng.integers(-2, 3, size=(ii.T, ii.projs[p].h_in)).astype(np.float32)
@@ -174,7 +177,7 @@ def test_zero_B_leaves_base_bit_identical():
     inst = wl.small_mixed(seed=3)
     orig = inst.adapter_weights
     inst.adapter_weights = lambda a, p: (orig(a, p)[0], np.zeros_like(orig(a, p)[1]))
-    pi = H.PooledInstance(inst)
+    pi = H.PooledInstance(inst, mfma_min_tokens=16)
     try:
         x, base = inst.x(0), inst.base_out(0)
         xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
@@ -203,7 +206,8 @@ def test_ragged_lengths_and_odd_ranks(dtype):
     lens = [15, 16, 17, 0, 63, 64, 65, 1, 129, 128, 2, 0, 1]
     ranks = [1, 4, 8, 12, 16, 24, 40, 100, 128, 7]
     adapters = [0, 1, 2, 3, 4, 5, 6, -1, 7, 8, 9, 2, 9]
-    _full_parity(_custom_instance(lens, adapters, ranks, dtype=dtype))
+    for m0 in (16, 8, 0):  # fixed thresholds (the tile path at every boundary), and the library's choice
+        _full_parity(_custom_instance(lens, adapters, ranks, dtype=dtype), mfma_min_tokens=m0)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -261,6 +265,7 @@ def test_single_token_max_rank_wide_projection():
     inst = _custom_instance([1], [0], [128], h_in=11008, h_out=4096)
     _full_parity(inst)
     inst = _custom_instance([1, 70], [0, 1], [128, 128], h_in=4096, h_out=11008, seed=1)
+    _full_parity(inst, mfma_min_tokens=16)
     _full_parity(inst)
 
 
@@ -299,7 +304,7 @@ def test_fill_paths_give_the_same_slabs():
     inst = _custom_instance([3, 20, 1, 70, 2, 5], [0, 1, 2, 3, 4, 5], [7, 16, 64, 128, 1, 100], h_in=320, h_out=448, seed=21)
     outs = []
     for pinned, flags in ((True, 0), (False, 0), (True, B.LORA_CACHE_DIRECT_FILL)):
-        pi = H.PooledInstance(inst, adapters=[], flags=flags)
+        pi = H.PooledInstance(inst, adapters=[], mfma_min_tokens=16, flags=flags)
         try:
             keep = []
             for a in range(len(inst.ranks)):
@@ -338,7 +343,7 @@ def test_multi_apply_groups_projections_that_share_their_input():
                        alpha=base_inst.alpha, scale=base_inst.scale, seg_offsets=base_inst.seg_offsets,
                        seg_adapter=base_inst.seg_adapter)
     for flags in (B.LORA_CACHE_FUSED_GEMV, B.LORA_CACHE_SPLIT_GEMV):
-        pi = H.PooledInstance(inst, flags=flags)
+        pi = H.PooledInstance(inst, mfma_min_tokens=16, flags=flags)
         try:
             plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
             sh = torch.cuda.current_stream().cuda_stream
@@ -373,7 +378,7 @@ def test_plan_reuse_over_projections_and_layers():
     """One plan per iteration, applied to every projection of every layer copy."""
     B, H = _mods()
     inst = wl.small_mixed(seed=7)
-    pi = H.PooledInstance(inst, n_layers=2)
+    pi = H.PooledInstance(inst, n_layers=2, mfma_min_tokens=16)
     try:
         plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
         for layer in range(2):
