@@ -59,7 +59,7 @@ enum {
     /* GEMV shrink and expand run as one launch with an in-kernel hand-over of the intermediate when
      * the batch's GEMV part is small (the launch in between then costs more than the hand-over),
      * else as two launches.  These two flags take the choice away: */
-    LORA_CACHE_FUSED_GEMV = 2,    /* always one launch */
+    LORA_CACHE_FUSED_GEMV = 2,    /* always one launch (except under stream capture, where it is always two) */
     LORA_CACHE_SPLIT_GEMV = 4,    /* always two launches (and no hand-over buffer in the pool) */
     LORA_CACHE_DIRECT_FILL = 8    /* fills read pinned host memory from the repack kernel itself instead of copying it
                                      to a staging buffer first: about twice the fill rate on an idle device, but applies

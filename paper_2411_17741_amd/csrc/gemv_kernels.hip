@@ -6,7 +6,7 @@
 // then comes out of L2 for all but the first).
 //
 //   shrink:  v[t][j] = sum_k x[t][k] * A[k][j]        wavefronts own (parts of) rank rows of At
-//   expand:  y[t][n] += s * sum_j v[t][j] * B[j][n]   lanes own output columns of Bp
+//   expand:  y[t][n] += s * sum_j v[t][j] * B[j][n]   a wavefront owns a run of output columns of Bp
 //
 // The two phases run as two launches, or -- as an option -- as one (fused) launch, in which the
 // expand wavefronts fetch their part of Bp and base_out while the shrink blocks are still working
@@ -14,7 +14,8 @@
 // word {apply number, fp32 bits}, written and read with device-scope atomic accesses (which go
 // past the per-XCD L2s, not coherent with each other): a reader polls the words it needs until
 // all carry the number of this apply, so there are no counters, no fences and no resets, and the
-// hand-over costs one store and one load latency.
+// hand-over costs one store and one load latency.  (Not under stream capture: a graph would freeze
+// the number.)
 //
 // (paper section 3.1: the two adapter products and the aggregation into the base output.)
 #include <algorithm>

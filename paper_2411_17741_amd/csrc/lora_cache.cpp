@@ -895,7 +895,9 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
     }
     // (after 2^32 - 1 fused launches the numbers would repeat: two launches from then on)
     // one launch pays off while the GEMV part is small enough for the launch gap to matter
-    const bool fused = p->n_gs > 0 && c->tag_epoch < UINT32_MAX - N_VSETS &&
+    // and never under stream capture: the launch number would be frozen into the graph, and a replay
+    // could take the previous replay's values for its own
+    const bool fused = p->n_gs > 0 && c->tag_epoch < UINT32_MAX - N_VSETS && !is_capturing(st) &&
                        (c->fused_gemv == 2 || (c->fused_gemv == 1 && p->n_gs <= FUSED_GEMV_MAX_ITEMS));
 
     // everything that reads x

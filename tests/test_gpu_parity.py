@@ -374,6 +374,45 @@ def test_multi_apply_groups_projections_that_share_their_input():
             pi.close()
 
 
+def test_applies_captured_in_a_graph_replay_correctly():
+    """An apply of a plan captured into a HIP graph (fencing off, as the header asks) and replayed
+    several times, with the activations changed by eager work between the replays: every replay
+    must give what the eager call gives.  (Under capture the GEMV part always takes the two-launch
+    form: the one-launch form numbers its launches, and a graph would freeze the number.)"""
+    B, H = _mods()
+    for inst, m0 in ((wl.decode(seed=2), 0), (wl.small_mixed(seed=3), 16)):
+        pi = H.PooledInstance(inst, mfma_min_tokens=m0, flags=B.LORA_CACHE_FUSED_GEMV)
+        try:
+            h = pi.pool.handle
+            x, base = inst.x(0), inst.base_out(0)
+            xd, yd = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+            base_d = yd.clone()
+            plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+            pi.pool.apply_plan(plan, 0, 0, xd, yd, inst.scale)  # eager once: fills are seen as done, kernels loaded
+            torch.cuda.synchronize()
+            B.check(B.lora_cache_set_fencing(h, 0))
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, capture_error_mode="thread_local"):
+                pi.pool.apply_plan(plan, 0, 0, xd, yd, inst.scale)
+            B.check(B.lora_cache_set_fencing(h, 1))
+            for rep, f in enumerate((1.0, -0.5, 2.0, 1.0)):
+                xd.copy_(H.to_device(wl.bf16_round(x * f), pi.dtype))   # eager work between the replays
+                yd.copy_(base_d)
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                got = yd.float().cpu().numpy()
+                y_eager = base_d.clone()
+                pi.pool.apply_plan(plan, 0, 0, xd, y_eager, inst.scale)
+                pi.pool.check_fault()
+                assert np.array_equal(got, y_eager.float().cpu().numpy()), f"{inst.name}: replay {rep} differs from the eager apply"
+            ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
+            _check(H.error_metrics(got, ref, base), "bf16", "last replay")
+            pi.pool.plan_destroy(plan)
+        finally:
+            pi.close()
+
+
 def test_plan_reuse_over_projections_and_layers():
     """One plan per iteration, applied to every projection of every layer copy."""
     B, H = _mods()
