@@ -76,9 +76,11 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     // k offset of stage st.  The walk over k starts at a different stage in every block, so that
     // blocks running side by side do not all pull the same column window (rows lie h_in apart)
     auto stage_k = [&](int st) {
-        int s = st + phase;
+        // (the prefetches run up to three stages past the end: they re-read the last stage, which is
+        // still in L1/L2 -- wrapped round to the first stages they came from memory again, +43 % of x
+        // for a block of seven stages)
+        int s = min(st, n_st - 1) + phase;
         s -= s >= n_st ? n_st : 0;
-        s -= s >= n_st ? n_st : 0;  // st runs up to n_st + 2 for the prefetches past the end
         return k_begin + s * SK;
     };
 
