@@ -449,9 +449,14 @@ void timer_pair(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop)
 
 int choose_k_splits(const lora_cache &c, int n_tiles, int n_tile_tok, int h_in)
 {
-    // One round of blocks (2 per CU) when there are few tiles; k ranges of at least 512 elements;
-    // and the partials of all splits must fit their scratch.
-    int want = std::max(1, std::min({512 / std::max(1, n_tiles), h_in / 512, MAX_K_SPLITS}));
+    // One round of blocks (2 per CU) when there are few tiles.  From half a round of whole-row blocks
+    // up, about two rounds of shorter ones: with 330 tiles, three k ranges took 10 % less than one
+    // (short blocks hide each other's start and end; the partials and the reduce launch cost a third
+    // of that back), four or more gained nothing further.  k ranges of at least 512 elements; and the
+    // partials of all splits must fit their scratch.
+    const int n = std::max(1, n_tiles);
+    const int fill = n <= 256 ? 512 / n : (1100 + n / 2) / n;
+    int want = std::max(1, std::min({fill, h_in / 512, MAX_K_SPLITS}));
     while (want > 1 && (int64_t)lora::mfma_shrink_splits(h_in, want) * n_tile_tok > c.vpart_rows) --want;
     return lora::mfma_shrink_splits(h_in, want);
 }
