@@ -162,6 +162,51 @@ typedef struct {
 } lora_cache_stats_t;
 int lora_cache_stats(const lora_cache_t *c, lora_cache_stats_t *out);
 
+/* ---- cache manager (section 4.2: cost-aware eviction, reference counters, queued requests,
+ *      prefetching, dynamic sizing).  Host-side bookkeeping only: nothing here touches the device. */
+
+/* Eviction score of a cached entry = w_freq * frequency + w_recency * recency + w_size * size; the
+ * entry with the LOWEST score goes first.  The paper fixes the coefficients (0.45, 0.10, 0.45: the
+ * defaults) but not the units of the three terms; here each is scaled to [0, 1] over the cached
+ * entries: frequency = requests that used the entry / the largest such count; recency =
+ * 1 - age / largest age, age counted in requests since the entry's last use; size = rank / largest
+ * cached rank (a larger adapter costs more to reload, so it is kept longer).  "Within a specific
+ * time frame": every freq_window requests all frequencies are halved (0 = never).
+ * (0, 1, 0) is LRU; equal weights are the paper's FairShare comparison point. */
+typedef struct {
+    double w_freq, w_recency, w_size;
+    int64_t freq_window;
+} lora_policy_t;
+int lora_cache_set_policy(lora_cache_t *c, const lora_policy_t *p); /* LORA_E_INVAL on negative or NaN values */
+int lora_cache_get_policy(const lora_cache_t *c, lora_policy_t *p);
+
+/* A request for an adapter arrives (pin = 1: it is about to run and holds a reference until
+ * lora_cache_slot_ref(slot, -1); pin = 0: it waits in a queue and the adapter is only prefetched).
+ * Hit: *hit = 1, *slot = its slot (which may still be FILLING).  Miss: *hit = 0 and *slot is bound to
+ * (adapter_id, rank, alpha) in state FILLING with no part loaded -- a free slot of the smallest class
+ * that fits, else the slot of the entry the policy evicts; the caller then loads the parts with
+ * lora_cache_fill_slot.  Never evicted: entries with a reference; entries whose adapter is in
+ * queued_ids (host array, adapters of requests that wait; may be NULL with n_queued = 0) are evicted
+ * only when no other candidate is left.  Either way the request counts for the entry's frequency
+ * and recency.  LORA_E_NOMEM if every entry in a large-enough slot is referenced; LORA_E_INVAL if
+ * rank exceeds the largest class or differs from the cached entry's. */
+int lora_cache_acquire(lora_cache_t *c, int64_t adapter_id, int32_t rank, float alpha, int32_t pin,
+                       const int64_t *queued_ids, int32_t n_queued, int32_t *slot, int32_t *hit);
+
+/* The score of the entry in `slot` (LORA_E_STATE if the slot is empty), and the slot the policy
+ * would evict next for an adapter of `rank` (0: any slot) without evicting it; LORA_E_NOMEM if
+ * there is none. */
+int lora_cache_score(lora_cache_t *c, int32_t slot, double *score);
+int lora_cache_choose_victim(lora_cache_t *c, int32_t rank, const int64_t *queued_ids, int32_t n_queued, int32_t *slot);
+
+/* Dynamic sizing: bytes of pool memory held by cached entries (each entry's storage rows in every
+ * layer and projection), and eviction in score order until at most max_bytes are held -- what the
+ * scheduler asks for when a batch's activations and KV entries need the room.  The pool's memory
+ * stays the caller's allocation: a trimmed cache leaves the slabs past the budget empty for the
+ * caller to plan with.  LORA_E_NOMEM if entries in use keep it above the budget (what could go has gone). */
+int lora_cache_resident_bytes(const lora_cache_t *c, size_t *bytes);
+int lora_cache_trim(lora_cache_t *c, size_t max_bytes, const int64_t *queued_ids, int32_t n_queued, int32_t *n_evicted);
+
 /* Device address and byte size of the slab of (layer, proj, slot) -- for tests and tools. */
 int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t slot, void **dev_ptr, size_t *bytes);
 

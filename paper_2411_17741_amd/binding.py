@@ -51,6 +51,10 @@ class lora_slot_info_t(ctypes.Structure):
     ]
 
 
+class lora_policy_t(ctypes.Structure):
+    _fields_ = [("w_freq", ctypes.c_double), ("w_recency", ctypes.c_double), ("w_size", ctypes.c_double), ("freq_window", c_int64)]
+
+
 class lora_cache_stats_t(ctypes.Structure):
     _fields_ = [(n, c_int64) for n in ("hits", "misses", "fills", "bytes_filled", "applies", "evictions")]
 
@@ -95,6 +99,13 @@ _SIGS = {
     "lora_cache_slot_info": (c_int, [c_void_p, c_int32, POINTER(lora_slot_info_t)]),
     "lora_cache_find_free_slot": (c_int, [c_void_p, c_int32, _i32p]),
     "lora_cache_stats": (c_int, [c_void_p, POINTER(lora_cache_stats_t)]),
+    "lora_cache_set_policy": (c_int, [c_void_p, POINTER(lora_policy_t)]),
+    "lora_cache_get_policy": (c_int, [c_void_p, POINTER(lora_policy_t)]),
+    "lora_cache_acquire": (c_int, [c_void_p, c_int64, c_int32, c_float, c_int32, POINTER(c_int64), c_int32, _i32p, _i32p]),
+    "lora_cache_score": (c_int, [c_void_p, c_int32, POINTER(ctypes.c_double)]),
+    "lora_cache_choose_victim": (c_int, [c_void_p, c_int32, POINTER(c_int64), c_int32, _i32p]),
+    "lora_cache_resident_bytes": (c_int, [c_void_p, POINTER(c_size_t)]),
+    "lora_cache_trim": (c_int, [c_void_p, c_size_t, POINTER(c_int64), c_int32, _i32p]),
     "lora_cache_slab": (c_int, [c_void_p, c_int32, c_int32, c_int32, POINTER(c_void_p), POINTER(c_size_t)]),
     "lora_index": (c_int, [c_int32, _i32p, _i32p, _i32p, c_int32, c_int32, POINTER(lora_worklists_t)]),
     "lora_worklists_free": (None, [POINTER(lora_worklists_t)]),
@@ -209,6 +220,58 @@ def lora_cache_stats(cache):
     st = lora_cache_stats_t()
     rc = _lib.lora_cache_stats(cache, ctypes.byref(st))
     return rc, st
+
+
+def _ids(queued_ids):
+    q = np.ascontiguousarray(np.asarray(queued_ids if queued_ids is not None else [], dtype=np.int64))
+    return q, (q.ctypes.data_as(POINTER(c_int64)) if q.size else None), int(q.size)
+
+
+def lora_cache_set_policy(cache, w_freq: float, w_recency: float, w_size: float, freq_window: int = 0) -> int:
+    pol = lora_policy_t(w_freq, w_recency, w_size, freq_window)
+    return _lib.lora_cache_set_policy(cache, ctypes.byref(pol))
+
+
+def lora_cache_get_policy(cache):
+    """-> (status, (w_freq, w_recency, w_size, freq_window))"""
+    pol = lora_policy_t()
+    rc = _lib.lora_cache_get_policy(cache, ctypes.byref(pol))
+    return rc, (pol.w_freq, pol.w_recency, pol.w_size, pol.freq_window)
+
+
+def lora_cache_acquire(cache, adapter_id: int, rank: int, alpha: float = 1.0, pin: bool = True, queued_ids=None):
+    """-> (status, slot, hit)"""
+    keep, qp, nq = _ids(queued_ids)
+    s, h = c_int32(-1), c_int32(0)
+    rc = _lib.lora_cache_acquire(cache, adapter_id, rank, alpha, 1 if pin else 0, qp, nq, ctypes.byref(s), ctypes.byref(h))
+    return rc, s.value, h.value
+
+
+def lora_cache_score(cache, slot: int):
+    v = ctypes.c_double(0.0)
+    rc = _lib.lora_cache_score(cache, slot, ctypes.byref(v))
+    return rc, v.value
+
+
+def lora_cache_choose_victim(cache, rank: int = 0, queued_ids=None):
+    keep, qp, nq = _ids(queued_ids)
+    s = c_int32(-1)
+    rc = _lib.lora_cache_choose_victim(cache, rank, qp, nq, ctypes.byref(s))
+    return rc, s.value
+
+
+def lora_cache_resident_bytes(cache):
+    n = c_size_t(0)
+    rc = _lib.lora_cache_resident_bytes(cache, ctypes.byref(n))
+    return rc, n.value
+
+
+def lora_cache_trim(cache, max_bytes: int, queued_ids=None):
+    """-> (status, entries evicted)"""
+    keep, qp, nq = _ids(queued_ids)
+    n = c_int32(0)
+    rc = _lib.lora_cache_trim(cache, max_bytes, qp, nq, ctypes.byref(n))
+    return rc, n.value
 
 
 def lora_cache_slab(cache, layer: int, proj: int, slot: int):

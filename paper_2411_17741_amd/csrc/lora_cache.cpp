@@ -1,6 +1,7 @@
 // Host side of liblora_cache: pool layout, slot table (the adapter cache's entries and their
 // metadata, paper section 4.2), fills from host memory, plans and the apply launches.
 #include <algorithm>
+#include <limits>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -42,6 +43,8 @@ struct Slot {
     float alpha = 1.f;
     int32_t refcount = 0;
     int64_t use_count = 0, last_used = 0;
+    double req_freq = 0;   // requests that used the entry, halved every policy.freq_window requests
+    int64_t req_last = 0;  // number of the last such request
     uint32_t generation = 0;  // bumped whenever the slot is bound to another adapter or evicted
     std::vector<uint8_t> part;  // [n_layers * n_proj] 1 = data enqueued
     int32_t parts_filled = 0;
@@ -110,6 +113,8 @@ struct lora_cache {
     int64_t apply_ev_seq[N_APPLY_EVENTS] = {};
 
     lora_cache_stats_t stats = {};
+    lora_policy_t policy = {0.45, 0.10, 0.45, 0};  // section 4.2's F, R, S
+    int64_t req_seq = 0;                           // requests seen by lora_cache_acquire
 
     // benchmark aid: event pairs around kernels
     bool timing = false;
@@ -240,9 +245,71 @@ void unbind(lora_cache &c, Slot &s)
     s.rank = 0;
     s.alpha = 1.f;
     s.use_count = 0;
+    s.req_freq = 0;
+    s.req_last = 0;
+    s.refcount = 0;
     s.parts_filled = 0;
     std::fill(s.part.begin(), s.part.end(), 0);
     ++s.generation;
+}
+
+// Section 4.2's eviction score of every cached entry: F * frequency + R * recency + S * size.
+// The paper gives no units: each term is scaled to [0, 1] over the cached entries (frequency and
+// rank by the largest cached, recency as 1 - age / largest age, age counted in requests), so that
+// the coefficients weigh comparable quantities.  Entries that are not cached get +inf.
+std::vector<double> eviction_scores(const lora_cache &c)
+{
+    double max_f = 0, max_age = 0, max_rank = 0;
+    for (const Slot &s : c.slots) {
+        if (!s.bound) continue;
+        max_f = std::max(max_f, s.req_freq);
+        max_age = std::max(max_age, (double)(c.req_seq - s.req_last));
+        max_rank = std::max(max_rank, (double)s.rank);
+    }
+    std::vector<double> score(c.slots.size(), std::numeric_limits<double>::infinity());
+    for (size_t i = 0; i < c.slots.size(); ++i) {
+        const Slot &s = c.slots[i];
+        if (!s.bound) continue;
+        const double f = max_f > 0 ? s.req_freq / max_f : 0.0;
+        const double r = max_age > 0 ? 1.0 - (double)(c.req_seq - s.req_last) / max_age : 1.0;
+        const double z = (double)s.rank / max_rank;
+        score[i] = c.policy.w_freq * f + c.policy.w_recency * r + c.policy.w_size * z;
+    }
+    return score;
+}
+
+bool is_queued(const int64_t *ids, int32_t n, int64_t id)
+{
+    for (int32_t i = 0; i < n; ++i)
+        if (ids[i] == id) return true;
+    return false;
+}
+
+// The entry to evict for an adapter of `rank` (any rank if 0): lowest score among the entries
+// no running request uses and whose slot is large enough; entries of queued requests only if
+// there is no other (section 4.2).  Ties go to the lower slot.  -1 if every candidate is in use.
+int32_t choose_victim(const lora_cache &c, int32_t rank, const int64_t *queued, int32_t n_queued)
+{
+    const std::vector<double> score = eviction_scores(c);
+    for (int pass = 0; pass < 2; ++pass) {
+        int32_t best = -1;
+        for (int32_t i = 0; i < c.n_slots; ++i) {
+            const Slot &s = c.slots[i];
+            if (!s.bound || s.refcount > 0 || c.class_rank[s.cls] < rank) continue;
+            if (pass == 0 && is_queued(queued, n_queued, s.adapter_id)) continue;
+            if (best < 0 || score[i] < score[best]) best = i;
+        }
+        if (best >= 0) return best;
+    }
+    return -1;
+}
+
+// bytes of pool memory the entry of a slot holds: its rank's storage rows in every layer and projection
+size_t entry_bytes(const lora_cache &c, const Slot &s)
+{
+    size_t per_row = 0;
+    for (size_t p = 0; p < c.proj.size(); ++p) per_row += c.row_bytes[p];
+    return (size_t)lora::rank_storage(s.rank) * per_row * (size_t)c.n_layers;
 }
 
 int slot_state(lora_cache &c, Slot &s)
@@ -727,6 +794,114 @@ int lora_cache_find_free_slot(lora_cache_t *c, int32_t rank, int32_t *slot)
             }
     }
     return LORA_E_NOMEM;
+}
+
+int lora_cache_set_policy(lora_cache_t *c, const lora_policy_t *p)
+{
+    if (!c || !p || !(p->w_freq >= 0) || !(p->w_recency >= 0) || !(p->w_size >= 0) || p->freq_window < 0) return LORA_E_INVAL;
+    c->policy = *p;
+    return LORA_OK;
+}
+
+int lora_cache_get_policy(const lora_cache_t *c, lora_policy_t *p)
+{
+    if (!c || !p) return LORA_E_INVAL;
+    *p = c->policy;
+    return LORA_OK;
+}
+
+int lora_cache_score(lora_cache_t *c, int32_t slot, double *score)
+{
+    if (!c || !score || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;
+    if (!c->slots[slot].bound) return LORA_E_STATE;
+    *score = eviction_scores(*c)[slot];
+    return LORA_OK;
+}
+
+int lora_cache_choose_victim(lora_cache_t *c, int32_t rank, const int64_t *queued_ids, int32_t n_queued, int32_t *slot)
+{
+    if (!c || !slot || rank < 0 || n_queued < 0 || (n_queued > 0 && !queued_ids)) return LORA_E_INVAL;
+    const int32_t v = choose_victim(*c, rank, queued_ids, n_queued);
+    if (v < 0) return LORA_E_NOMEM;
+    *slot = v;
+    return LORA_OK;
+}
+
+int lora_cache_acquire(lora_cache_t *c, int64_t adapter_id, int32_t rank, float alpha, int32_t pin,
+                       const int64_t *queued_ids, int32_t n_queued, int32_t *slot, int32_t *hit)
+{
+    if (!c || !slot || !hit || rank < 1 || n_queued < 0 || (n_queued > 0 && !queued_ids)) return LORA_E_INVAL;
+    if (rank > c->class_rank.back()) return LORA_E_INVAL;
+    auto touch = [&](Slot &s) {
+        ++c->req_seq;
+        if (c->policy.freq_window > 0 && c->req_seq % c->policy.freq_window == 0)
+            for (Slot &o : c->slots) o.req_freq *= 0.5;
+        s.req_freq += 1.0;
+        s.req_last = c->req_seq;
+        if (pin) ++s.refcount;
+    };
+    auto it = c->id2slot.find(adapter_id);
+    if (it != c->id2slot.end()) {
+        Slot &s = c->slots[it->second];
+        if (s.rank != rank) return LORA_E_INVAL;
+        ++c->stats.hits;
+        touch(s);
+        *slot = it->second;
+        *hit = 1;
+        return LORA_OK;
+    }
+    int32_t where = -1;
+    if (lora_cache_find_free_slot(c, rank, &where) != LORA_OK) {
+        where = choose_victim(*c, rank, queued_ids, n_queued);
+        if (where < 0) return LORA_E_NOMEM;  // every large-enough entry is used by a running request
+        ++c->stats.evictions;
+        unbind(*c, c->slots[where]);
+    }
+    ++c->stats.misses;
+    Slot &s = c->slots[where];
+    s.bound = true;
+    s.adapter_id = adapter_id;
+    s.rank = rank;
+    s.alpha = alpha;
+    s.use_count = 0;
+    ++s.generation;
+    c->id2slot[adapter_id] = where;
+    touch(s);
+    *slot = where;
+    *hit = 0;
+    return LORA_OK;
+}
+
+int lora_cache_resident_bytes(const lora_cache_t *c, size_t *bytes)
+{
+    if (!c || !bytes) return LORA_E_INVAL;
+    size_t sum = 0;
+    for (const Slot &s : c->slots)
+        if (s.bound) sum += entry_bytes(*c, s);
+    *bytes = sum;
+    return LORA_OK;
+}
+
+int lora_cache_trim(lora_cache_t *c, size_t max_bytes, const int64_t *queued_ids, int32_t n_queued, int32_t *n_evicted)
+{
+    if (!c || n_queued < 0 || (n_queued > 0 && !queued_ids)) return LORA_E_INVAL;
+    size_t held = 0;
+    lora_cache_resident_bytes(c, &held);
+    int32_t n = 0;
+    int rc = LORA_OK;
+    while (held > max_bytes) {
+        const int32_t v = choose_victim(*c, 0, queued_ids, n_queued);
+        if (v < 0) {
+            rc = LORA_E_NOMEM;  // what is left is in use
+            break;
+        }
+        held -= entry_bytes(*c, c->slots[v]);
+        ++c->stats.evictions;
+        unbind(*c, c->slots[v]);
+        ++n;
+    }
+    if (n_evicted) *n_evicted = n;
+    return rc;
 }
 
 int lora_cache_stats(const lora_cache_t *c, lora_cache_stats_t *out)
