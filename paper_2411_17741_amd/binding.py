@@ -51,6 +51,12 @@ class lora_slot_info_t(ctypes.Structure):
     ]
 
 
+class lora_sched_config_t(ctypes.Structure):
+    _fields_ = [("n_queues", c_int32), ("quota", POINTER(c_int64)), ("boundaries", POINTER(ctypes.c_double)),
+                ("max_input", c_int32), ("max_output", c_int32), ("max_rank", c_int32), ("tokens_per_rank", c_int32),
+                ("a_input", ctypes.c_double), ("b_output", ctypes.c_double)]
+
+
 class lora_policy_t(ctypes.Structure):
     _fields_ = [("w_freq", ctypes.c_double), ("w_recency", ctypes.c_double), ("w_size", ctypes.c_double), ("freq_window", c_int64)]
 
@@ -119,6 +125,17 @@ _SIGS = {
     "lora_cache_set_timing": (c_int, [c_void_p, c_int32]),
     "lora_cache_read_timing": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "lora_cache_check_fault": (c_int, [c_void_p, c_void_p, _i32p]),
+    "lora_sched_wrs": (ctypes.c_double, [c_int32, c_int32, c_int32, c_int32, c_int32, c_int32, ctypes.c_double, ctypes.c_double]),
+    "lora_sched_create": (c_int, [POINTER(lora_sched_config_t), POINTER(c_void_p)]),
+    "lora_sched_destroy": (c_int, [c_void_p]),
+    "lora_sched_submit": (c_int, [c_void_p, c_int64, c_int32, c_int32, c_int64, c_int32, _i32p]),
+    "lora_sched_generate_batch": (c_int, [c_void_p, POINTER(c_int64), c_int32, _i32p]),
+    "lora_sched_finish": (c_int, [c_void_p, c_int64]),
+    "lora_sched_queue_state": (c_int, [c_void_p, c_int32, POINTER(c_int64), _i32p]),
+    "lora_sched_waiting_adapters": (c_int, [c_void_p, POINTER(c_int64), c_int32, _i32p]),
+    "lora_sched_fit_queues": (c_int, [POINTER(ctypes.c_double), c_int32, c_int32, _i32p, POINTER(ctypes.c_double)]),
+    "lora_sched_min_quota": (c_int64, [ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double]),
+    "lora_sched_assign_quotas": (c_int, [c_int64, POINTER(c_int64), POINTER(ctypes.c_double), c_int32, POINTER(c_int64)]),
     "lora_strerror": (c_char_p, [c_int]),
     "lora_last_hip_error": (c_int, []),
 }
@@ -272,6 +289,84 @@ def lora_cache_trim(cache, max_bytes: int, queued_ids=None):
     n = c_int32(0)
     rc = _lib.lora_cache_trim(cache, max_bytes, qp, nq, ctypes.byref(n))
     return rc, n.value
+
+
+# ---- scheduler (include/lora_sched.h) -----------------------------------------------------------
+
+def lora_sched_wrs(input_len, output_len, rank, max_input, max_output, max_rank, a_input=0.0, b_output=0.0) -> float:
+    return float(_lib.lora_sched_wrs(input_len, output_len, rank, max_input, max_output, max_rank, a_input, b_output))
+
+
+def lora_sched_create(quota, boundaries, max_input, max_output, max_rank, tokens_per_rank, a_input=0.0, b_output=0.0):
+    """-> (status, handle)"""
+    q = np.ascontiguousarray(np.asarray(quota, dtype=np.int64))
+    b = np.ascontiguousarray(np.asarray(boundaries, dtype=np.float64))
+    cfg = lora_sched_config_t(int(q.size), q.ctypes.data_as(POINTER(c_int64)),
+                              b.ctypes.data_as(POINTER(ctypes.c_double)) if b.size else None,
+                              max_input, max_output, max_rank, tokens_per_rank, a_input, b_output)
+    h = c_void_p()
+    rc = _lib.lora_sched_create(ctypes.byref(cfg), ctypes.byref(h))
+    return rc, h
+
+
+def lora_sched_destroy(sched) -> int:
+    return _lib.lora_sched_destroy(sched)
+
+
+def lora_sched_submit(sched, req_id, input_len, output_len, adapter_id, rank):
+    """-> (status, queue)"""
+    q = c_int32(-1)
+    rc = _lib.lora_sched_submit(sched, req_id, input_len, output_len, adapter_id, rank, ctypes.byref(q))
+    return rc, q.value
+
+
+def lora_sched_generate_batch(sched, cap: int = 4096):
+    """-> (status, [request ids in admission order])"""
+    ids = (c_int64 * max(1, cap))()
+    n = c_int32(0)
+    rc = _lib.lora_sched_generate_batch(sched, ids, cap, ctypes.byref(n))
+    return rc, [int(ids[i]) for i in range(n.value)]
+
+
+def lora_sched_finish(sched, req_id) -> int:
+    return _lib.lora_sched_finish(sched, req_id)
+
+
+def lora_sched_queue_state(sched, queue: int):
+    """-> (status, free tokens, waiting requests)"""
+    f, w = c_int64(0), c_int32(0)
+    rc = _lib.lora_sched_queue_state(sched, queue, ctypes.byref(f), ctypes.byref(w))
+    return rc, f.value, w.value
+
+
+def lora_sched_waiting_adapters(sched, cap: int = 4096):
+    ids = (c_int64 * max(1, cap))()
+    n = c_int32(0)
+    rc = _lib.lora_sched_waiting_adapters(sched, ids, cap, ctypes.byref(n))
+    return rc, [int(ids[i]) for i in range(min(n.value, cap))]
+
+
+def lora_sched_fit_queues(sizes, k_max: int = 4):
+    """-> (status, K, [boundaries])"""
+    x = np.ascontiguousarray(np.asarray(sizes, dtype=np.float64))
+    k = c_int32(0)
+    b = (ctypes.c_double * max(1, k_max))()
+    rc = _lib.lora_sched_fit_queues(x.ctypes.data_as(POINTER(ctypes.c_double)), int(x.size), k_max, ctypes.byref(k), b)
+    return rc, k.value, [float(b[i]) for i in range(max(0, k.value - 1))]
+
+
+def lora_sched_min_quota(max_request_tokens, duration, slo, arrival_rate) -> int:
+    return int(_lib.lora_sched_min_quota(max_request_tokens, duration, slo, arrival_rate))
+
+
+def lora_sched_assign_quotas(total_tokens, least, weights):
+    """-> (status, [quota per queue])"""
+    l = np.ascontiguousarray(np.asarray(least, dtype=np.int64))
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.float64))
+    out = (c_int64 * max(1, int(l.size)))()
+    rc = _lib.lora_sched_assign_quotas(total_tokens, l.ctypes.data_as(POINTER(c_int64)), w.ctypes.data_as(POINTER(ctypes.c_double)),
+                                       int(l.size), out)
+    return rc, [int(out[i]) for i in range(int(l.size))]
 
 
 def lora_cache_slab(cache, layer: int, proj: int, slot: int):
