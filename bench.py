@@ -32,6 +32,7 @@ WORKLOAD_TEXT = {
     "mixed": "mixed: 224 decode + 32 prompts, 7B-shaped layer (q,k,v,o,gate,up,down) bf16, pool of 500, Zipf(1.2)",
     "stress": "stress: 512 decode + 4x512 prompt tokens, 13B-shaped layer bf16, pool of 1000 in 4 layer copies, Zipf(1.2)",
     "decode_heavy": "decode_heavy (extra, not one of the task's configurations): 1024 one-token requests, one 4096->4096 bf16 projection, pool of 500 adapters (ranks 8..128), Zipf(1.0)",
+    "decode_paper": "decode_paper (extra): one-token requests, one 4096->4096 bf16 projection, the paper's adapter population: --adapters N_a, N_a/5 of each rank 8..128, rank uniform, power law within the rank",
 }
 # HBM bytes per launch of a workload's dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs, scaled
 # by what the same counters read for a plain copy; figures and commands in profiles/gemv_fused_decode_traffic.txt and
@@ -39,8 +40,8 @@ WORKLOAD_TEXT = {
 # measured for the same commands are carried here.
 MEASURED_TRAFFIC = {("decode", "gemv_fused"): 28.15e6, ("prefill", "mfma_shrink"): 82.95e6, ("mixed", "mfma_expand"): 662.7e6,
                     ("stress", "gemv_fused"): 218.2e6, ("decode_heavy", "gemv_expand"): 139.2e6}
-DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8}
-DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40}
+DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32}
+DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100}
 
 
 def algorithmic_bytes(inst, w, esize=2):
@@ -79,6 +80,8 @@ def main() -> int:
     ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
     ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
     ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
+    ap.add_argument("--adapters", type=int, default=100, help="decode_paper: number of adapters N_a (a multiple of 5)")
+    ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -97,7 +100,10 @@ def main() -> int:
 
     steps = args.steps or DEFAULT_STEPS[args.workload]
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
-    inst = wl.CONFIGS[args.workload](seed=0)
+    if args.workload == "decode_paper":
+        inst = wl.decode_paper(seed=0, n_adapters=args.adapters, n_decode=args.tokens)
+    else:
+        inst = wl.CONFIGS[args.workload](seed=0)
     t_setup = time.time()
     pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv] | (B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0))
     h = pi.pool.handle
@@ -295,7 +301,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
-                   "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
+                   "pool_adapters": int(inst.n_adapters), "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
                    "host_index_us": index_us, "host_plan_create_us": plan_us,
                    "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},

@@ -2,7 +2,9 @@
 
 Python face of `lora_oracle.c` (the fp64 definition of the batched
 heterogeneous-rank LoRA apply, paper section 3.1) and of `indexer.py` (the
-integer work lists).  Only `tests/`, `__graft_entry__.smoke()` and the
+integer work lists).  `manager.py` (cache manager, section 4.2) and
+`scheduler.py` (request scheduler, section 4.3) are imported by their tests
+directly.  Only `tests/`, `__graft_entry__.smoke()` and the
 `cpu_baseline` leg of `bench.py` import this package.  It imports nothing from
 the GPU package and shares no code with it.
 

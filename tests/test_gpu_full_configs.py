@@ -91,6 +91,15 @@ def test_prefill_config_full_size_sampled_other_seed():
     _run_full(inst, _sample_tokens(inst, seed=1))
 
 
+@pytest.mark.parametrize("n_adapters,n_decode", [(10, 64), (200, 64), (150, 512)])
+def test_decode_with_the_papers_adapter_population(n_adapters, n_decode):
+    """The adapter population of the paper's own workload (N_a / 5 adapters of every rank, rank
+    uniform, power law within the rank) at both ends of its sweep over N_a: every token checked."""
+    inst = wl.decode_paper(n_adapters=n_adapters, n_decode=n_decode)
+    assert np.array_equal(np.bincount(inst.ranks)[[8, 16, 32, 64, 128]], [n_adapters // 5] * 5)
+    _run_full(inst, np.arange(inst.T, dtype=np.int64))
+
+
 def test_stress_config_with_fills_overlapping_applies():
     """13B-shaped layer, pool of 1000 adapters in 4 layer copies (~39 GB).  Iteration k runs
     without the requests whose adapters are missing while those adapters are filled from pinned

@@ -21,6 +21,7 @@ from .gen import (  # noqa: F401
     tiny,
     decode,
     decode_heavy,
+    decode_paper,
     prefill,
     mixed,
     stress,

@@ -208,17 +208,32 @@ def make_instance(
     miss_fraction: float = 0.0,
     n_base_only: int = 0,
     note: str = "",
+    popularity_within_rank: bool = False,
 ) -> Instance:
-    """Mixed prefill/decode batch: one segment per request, requests in seeded order."""
-    ranks = _rng(seed, _P_RANK).choice(np.asarray(rank_choices, np.int32), size=n_adapters).astype(np.int32)
-    perm = _rng(seed, _P_POP, 0).permutation(n_adapters)  # popularity rank -> pool index
+    """Mixed prefill/decode batch: one segment per request, requests in seeded order.
+
+    popularity_within_rank: the paper's own law (section 5.1) -- every rank has the same number of
+    adapters, a request draws its rank uniformly and then an adapter of that rank by a power law
+    (exponent zipf_alpha; the paper does not state it).  Otherwise ranks are drawn per adapter and
+    one power law runs over the whole pool."""
     n_pre = len(prompt_lens)
     n_req = n_decode + n_pre + n_base_only
     prng = _rng(seed, _P_POP, 1)
-    if zipf_alpha is None:
-        pick = prng.integers(0, n_adapters, size=n_req)
+    perm = _rng(seed, _P_POP, 0).permutation(n_adapters)  # popularity rank -> pool index
+    if popularity_within_rank:
+        n_ranks = len(rank_choices)
+        assert n_adapters % n_ranks == 0 and zipf_alpha is not None
+        per_rank = n_adapters // n_ranks
+        ranks = np.empty(n_adapters, np.int32)
+        ranks[perm] = np.repeat(np.asarray(rank_choices, np.int32), per_rank)  # perm[c * per_rank + k]: k-th most popular of rank c
+        cls = prng.integers(0, n_ranks, size=n_req)
+        pick = perm[cls * per_rank + _zipf_choice(prng, per_rank, zipf_alpha, n_req)]
     else:
-        pick = perm[_zipf_choice(prng, n_adapters, zipf_alpha, n_req)]
+        ranks = _rng(seed, _P_RANK).choice(np.asarray(rank_choices, np.int32), size=n_adapters).astype(np.int32)
+        if zipf_alpha is None:
+            pick = prng.integers(0, n_adapters, size=n_req)
+        else:
+            pick = perm[_zipf_choice(prng, n_adapters, zipf_alpha, n_req)]
     pick = pick.astype(np.int32)
     lens = np.concatenate([np.ones(n_decode, np.int32), np.asarray(prompt_lens, np.int32), np.ones(n_base_only, np.int32)])
     if distinct_prefill_adapters and n_pre:
@@ -292,6 +307,17 @@ def decode_heavy(seed: int = 0, n_layers: int = 1) -> Instance:
     )
 
 
+def decode_paper(seed: int = 0, n_layers: int = 1, n_adapters: int = 100, n_decode: int = 64) -> Instance:
+    """Not one of the task's configurations: the decode configuration with the paper's own adapter
+    population (section 5.1: N_a adapters, N_a / 5 of each of the five ranks, rank drawn uniformly,
+    power law within the rank) -- for the sweep over N_a = 10 .. 200 of the paper's sensitivity study."""
+    return make_instance(
+        f"decode_paper_{n_adapters}", dtype="bf16", seed=seed, projs=[Projection("q", 4096, 4096, 0)], n_adapters=n_adapters,
+        rank_choices=[8, 16, 32, 64, 128], n_decode=n_decode, prompt_lens=[], zipf_alpha=1.0, n_layers=n_layers,
+        popularity_within_rank=True,
+    )
+
+
 def prefill(seed: int = 0, n_layers: int = 1) -> Instance:
     """8 prompts, lognormal(6, 0.8) lengths in [32, 2048], distinct adapters of rank {16,64,128}."""
     lens = _prompt_lengths(_rng(seed, _P_LEN), 8)
@@ -340,4 +366,5 @@ CONFIGS = {
     "stress": stress,
     "small_mixed": small_mixed,
     "decode_heavy": decode_heavy,
+    "decode_paper": decode_paper,
 }
