@@ -69,6 +69,75 @@ def algorithmic_bytes(inst, w, esize=2):
     return out
 
 
+MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
+    """y = x.W + s.(x.A).B in one pass per projection (lora_linear_plan), next to the same work done as a
+    vendor-library matmul followed by the apply on its output."""
+    import torch
+    from paper_2411_17741_amd import binding as B
+
+    h, sh, dev = pi.pool.handle, stream.cuda_stream, xs[0][inst.projs[0].x_key].device
+    n_proj = len(inst.projs)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4321)
+    wts = [[(torch.randn((p.h_out, p.h_in), generator=gen, device=dev) * 0.02).to(torch.bfloat16) for p in inst.projs] for _ in range(2)]
+
+    def step(s: int, fused: bool) -> None:
+        rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
+        B.check(rc, "lora_plan_create")
+        for l in range(n_layers):
+            for p in range(n_proj):
+                x, y, wt = xs[l % n_sets][inst.projs[p].x_key], ys[l % n_sets][p], wts[(s + l) % 2][p]
+                if fused:
+                    B.check(B.lora_linear_plan(h, plan, l, p, x.data_ptr(), wt.data_ptr(), y.data_ptr(), inst.scale, sh), "lora_linear_plan")
+                else:
+                    torch.matmul(x, wt.t(), out=y)
+                    B.check(B.lora_apply_plan(h, plan, l, p, x.data_ptr(), y.data_ptr(), inst.scale, sh), "lora_apply_plan")
+        B.check(B.lora_plan_destroy(h, plan))
+
+    def timed(fused: bool) -> float:
+        for s in range(args.warmup):
+            step(s, fused)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            step(args.warmup + s, fused)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_fused, ms_split = timed(True), timed(False)
+    B.check(B.lora_cache_set_timing(h, 1))
+    n_t = max(1, min(steps, 40 // n_layers))
+    for s in range(n_t):
+        step(args.warmup + s, True)
+    torch.cuda.synchronize()
+    rc, tm = B.lora_cache_read_timing(h)
+    B.check(rc)
+    B.check(B.lora_cache_set_timing(h, 0))
+    kernels = {k: {"launches": int(n), "avg_us": ms * 1e3 / n} for k, (ms, n) in tm.items() if n}
+    flops_layer = sum(2.0 * inst.T * p.h_in * p.h_out for p in inst.projs)
+    lin = kernels["linear"]
+    achieved = flops_layer / n_proj / (lin["avg_us"] * 1e-6) / 1e12  # average launch: one projection
+    out = {
+        "metric": "lora_linear_tokens_per_s_per_layer", "value": inst.T / (ms_fused / n_layers * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": args.warmup, "ms_per_step": ms_fused, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload] + "; base projection fused (lora_linear_plan), random base weights",
+                   "tokens": inst.T, "projections": n_proj, "layers_per_step": n_layers, "ms_per_layer": ms_fused / n_layers,
+                   "vendor_matmul_then_apply_ms_per_layer": ms_split / n_layers},
+        "roofline": {"bound": "mfma", "kernel": "linear", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None, "avg_launch_us": lin["avg_us"],
+                     "flops_per_launch": flops_layer / n_proj},
+        "cpu_baseline": None,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    pi.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +151,8 @@ def main() -> int:
     ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
     ap.add_argument("--adapters", type=int, default=100, help="decode_paper: number of adapters N_a (a multiple of 5)")
     ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
+    ap.add_argument("--fused-base", action="store_true", help="time lora_linear_plan (base projection and adapter update in one pass; "
+                    "random base weights) instead of the apply on a given base output; prints its own JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -126,6 +197,9 @@ def main() -> int:
     sh = stream.cuda_stream
     B.check(B.lora_cache_set_fencing(h, 1))
     n_proj = len(inst.projs)
+
+    if args.fused_base:
+        return fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream)
 
     descs = B.make_descs([(l, p, xs[l % n_sets][inst.projs[p].x_key].data_ptr(), ys[l % n_sets][p].data_ptr())
                           for l in range(n_layers) for p in range(n_proj)])

@@ -283,6 +283,18 @@ typedef struct {
 int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int32_t n, float scale,
                           void *stream);
 
+/* The base projection and the adapter update of a planned batch in one pass (section 3.1 with
+ * the separate addition folded away):  y[t] = x[t] . W + s_i * (x[t] . A_i) . B_i  for every token of
+ * the batch; tokens without an adapter get x[t] . W.  Wt is the device weight [h_out][h_in], bf16 --
+ * W transposed, the layout a linear layer keeps its weight in; y [T][h_out] is written only (it
+ * need not hold anything on entry, and must not overlap x).  The shrink runs as in lora_apply_plan;
+ * then one matrix-core kernel computes the base product over row tiles of 64 tokens and adds the
+ * adapter product of the tiles as one more slab of the contraction; tokens on the GEMV path get
+ * their adapter term added afterwards.  bf16 caches only (LORA_E_INVAL otherwise); other errors and
+ * stream semantics as for lora_apply_plan. */
+int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, const void *Wt, void *y,
+                     float scale, void *stream);
+
 /* One-call form: index + apply (uses one of 4 internal plans in rotation; blocks the
  * host only if the plan used 4 calls ago is still in flight). */
 int lora_apply(lora_cache_t *c, int32_t layer, int32_t proj, const void *x, void *base_out, int32_t T,
@@ -300,7 +312,7 @@ int lora_cache_set_fencing(lora_cache_t *c, int32_t on);
  * launch counts per kernel kind since the last read, and forgets them. */
 enum {
     LORA_K_MFMA_REDUCE = 0, LORA_K_MFMA_SHRINK = 1, LORA_K_GEMV_SHRINK = 2, LORA_K_MFMA_EXPAND = 3, LORA_K_GEMV_EXPAND = 4,
-    LORA_K_GEMV_FUSED = 5, LORA_K_COUNT = 6
+    LORA_K_GEMV_FUSED = 5, LORA_K_LINEAR = 6, LORA_K_COUNT = 7
 };
 int lora_cache_set_timing(lora_cache_t *c, int32_t on);
 int lora_cache_read_timing(lora_cache_t *c, double ms[LORA_K_COUNT], int64_t launches[LORA_K_COUNT]);

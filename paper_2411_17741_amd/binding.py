@@ -120,6 +120,7 @@ _SIGS = {
     "lora_plan_info": (c_int, [c_void_p, POINTER(lora_plan_info_t)]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
+    "lora_linear_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_float, c_void_p]),
     "lora_cache_set_fencing": (c_int, [c_void_p, c_int32]),
     "lora_cache_set_timing": (c_int, [c_void_p, c_int32]),
@@ -428,6 +429,11 @@ def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, s
                                 c_void_p(stream or None))
 
 
+def lora_linear_plan(cache, plan, layer: int, proj: int, x: int, Wt: int, y: int, scale: float, stream: int = 0) -> int:
+    return _lib.lora_linear_plan(cache, plan, layer, proj, c_void_p(x or None), c_void_p(Wt or None), c_void_p(y or None), scale,
+                                 c_void_p(stream or None))
+
+
 def make_descs(entries):
     """[(layer, proj, x device address, base_out device address), ...] -> C array for lora_apply_plan_multi."""
     arr = (lora_apply_desc_t * len(entries))()
@@ -447,7 +453,7 @@ def lora_apply(cache, layer: int, proj: int, x: int, base_out: int, T: int, seg_
                            _ptr(sr), len(ss), scale, c_void_p(stream or None))
 
 
-KERNEL_KINDS = ("mfma_reduce", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand", "gemv_fused")
+KERNEL_KINDS = ("mfma_reduce", "mfma_shrink", "gemv_shrink", "mfma_expand", "gemv_expand", "gemv_fused", "linear")
 
 
 def lora_cache_set_timing(cache, on: int) -> int:

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblora_cache.so")
 
-SOURCES = ["lora_cache.cpp", "indexer.cpp", "scheduler.cpp", "gemv_kernels.hip", "mfma_kernels.hip", "fill_kernels.hip"]
+SOURCES = ["lora_cache.cpp", "indexer.cpp", "scheduler.cpp", "gemv_kernels.hip", "mfma_kernels.hip", "linear_kernels.hip", "fill_kernels.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

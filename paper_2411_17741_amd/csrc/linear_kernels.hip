@@ -1,0 +1,279 @@
+// Base projection and adapter update in one matrix-core kernel for gfx950 (bf16 in, fp32 accumulate):
+//     y[t] = x[t] . W  +  s_i . v[t] . B_i          v[t] = x[t] . A_i from the shrink kernels
+// for row tiles of up to 64 tokens that share one adapter (or have none).  The adapter product enters
+// as one more slab of the contraction after the k loop over h_in, so the output is written once and
+// never read: the separate addition of the adapter result to the base output (paper section 3.1)
+// disappears.  This is the variant of the hot path whose roof is the matrix cores, not HBM.
+//
+// Block = 8 wavefronts on 256 rows (four row tiles) x 256 output columns; wavefront w owns the row
+// half w%2 and the column quarter w/2: 4 x 2 products of 32 x 32 (v_mfma_f32_32x32x16_bf16: 8 x 16
+// accumulator registers).  Two wavefronts per SIMD: with one (4 x 4 products each) every wait -- the
+// barrier of a stage, the first operand reads after it -- idles the matrix core (measured: 0.68
+// against 1.1 PFLOP/s).  x rows (gathered by token) and Wt rows (Wt[n][k] = W[k][n], the layout a
+// linear layer keeps its weight in) are both contiguous along k: every stage brings 64 k of both
+// into LDS, double-buffered, one barrier per stage, by global_load_lds_dwordx4 -- the load writes
+// LDS itself (at the wavefront's base + 16 bytes x lane; checked on the part), so no registers stage
+// the data (with 256 accumulator registers per lane, 64 more for staging made the compiler spill
+// them).  LDS rows are 128 bytes without padding; bank conflicts are avoided by a swizzle instead:
+// 16-byte slot s of row r holds piece s ^ ((r/2) % 8) of the row's 64 k, so the 16 rows an operand
+// read touches at once fall into 16 different bank groups.  Per 16-wide k step a wavefront reads
+// 4 + 2 operands from LDS for 8 products.
+// Operand layout of the instruction: A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7;
+// B (16 x 32): lane l holds column l%32, same k; D: lane l holds column l%32, rows 8*(i/4) + 4*(l/32) + i%4.
+// After the k loop the scaled intermediate s.v of the block's rows is staged in LDS as bf16 and every
+// wavefront adds, per row tile, the products with that tile's Bp, whose rank-packed layout gives the
+// B operand directly from global memory (32 lanes read 512 contiguous bytes).
+// Tokens on the GEMV path sit in row tiles without an adapter; their adapter term is computed by the
+// GEMV kernels beforehand into the (zeroed) output rows, and this kernel adds it to the accumulators of
+// those rows before the one rounding of the stored value (row tiles marked a = 1).
+#include <algorithm>
+
+#include "lora_device.h"
+
+namespace lora {
+
+namespace {
+constexpr int LBM = 256, LBN = 256, LBK = 64;
+constexpr int LROW = LBK * 2;                   // bytes per row of a stage in LDS (swizzled, not padded)
+constexpr int L_A = LBM * LROW;                 // x part of a stage
+constexpr int L_STAGE = (LBM + LBN) * LROW;     // 73728 bytes
+constexpr int SV_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per row of the staged s.v
+static_assert(LBM * SV_ROW <= 2 * L_STAGE, "s.v is staged in the stage buffers");
+}  // namespace
+
+__device__ __forceinline__ int row_tile_token(const int32_t *tok_list, const DevItem &it, int ti)
+{
+    return (it.consecutive || ti == 0) ? it.tok0 + ti : tok_list[it.tok_off + ti];
+}
+
+__global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __bf16 *__restrict__ Wt,
+                                                           const DevItem *__restrict__ tiles, int n_rt, int n_mt)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // two stages
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, h = lane >> 5;
+    const int rh = w & 1, cq = w >> 1;
+    const int bm = (int)blockIdx.x % n_mt, bn = (int)blockIdx.x / n_mt;
+    const int n0 = bn * LBN;
+
+    // the four row tiles of the block (a missing one counts as empty), and the two of this wavefront's
+    // row half once more under fixed names (indexing the four by the wavefront number would put them
+    // in scratch memory)
+    auto get_tile = [&](int idx) {
+        DevItem t = tiles[min(idx, n_rt - 1)];
+        if (idx >= n_rt) {
+            t.n_tok = 0;
+            t.rank = 0;
+        }
+        return t;
+    };
+    const DevItem it0 = get_tile(4 * bm), it1 = get_tile(4 * bm + 1), it2 = get_tile(4 * bm + 2), it3 = get_tile(4 * bm + 3);
+    const DevItem mine0 = get_tile(4 * bm + 2 * rh), mine1 = get_tile(4 * bm + 2 * rh + 1);
+    auto tile_of = [&](int j) -> const DevItem & { return j == 0 ? it0 : j == 1 ? it1 : j == 2 ? it2 : it3; };  // j: compile-time
+    const DevItem tile_of_wave = get_tile(4 * bm + (w >> 1));  // the row tile this wavefront loads half of
+    const int dead_tok = it0.tok0;  // rows past a tile's end read a live token's x; they are never stored
+
+    const __bf16 *x = static_cast<const __bf16 *>(a.x);
+    __bf16 *y = static_cast<__bf16 *>(a.y);
+    const int n_k = a.h_in / LBK;
+
+    // loader: wavefront w brings rows 32w + 8q + lane/8, q = 0..3, of both x and Wt: instruction q writes
+    // 8 rows x 128 bytes at the wavefront-uniform LDS address of its first row, lane l to slot l%8 of
+    // row l/8, for which it fetches piece (l%8) ^ ((row/2) % 8) of the row
+    const int lr = lane >> 3, ls = lane & 7;
+    const int piece_even = ls ^ ((lane >> 4) & 7), piece_odd = ls ^ (((lane >> 4) + 4) & 7);  // (row/2)%8 for q even / odd
+    const __bf16 *xg[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const DevItem &t = tile_of_wave;
+        const int ti = 32 * (w & 1) + 8 * q + lr;
+        const int tok = ti < t.n_tok ? row_tile_token(a.tok_list, t, ti) : dead_tok;
+        xg[q] = x + (size_t)tok * a.h_in + ((q & 1) ? piece_odd : piece_even) * 8;
+    }
+    // Wt rows n0 + 32w + 8q + lr; h_out is a multiple of 64, so a run of 32 rows is inside or outside as a whole
+    const int w_row0 = min(n0 + 32 * w, a.h_out - 32);
+    const __bf16 *wg_even = Wt + (size_t)(w_row0 + lr) * a.h_in + piece_even * 8;
+    const __bf16 *wg_odd = Wt + (size_t)(w_row0 + lr) * a.h_in + piece_odd * 8;
+    // (All blocks walk k in step: the blocks of a row or column of the grid then find each other's
+    // panel slices in L2.  Starting every block at another stage, as the tile shrink does, was no faster.)
+    auto load_stage = [&](int kt, int buf) {
+        const int k = kt * LBK;
+        unsigned char *sa = lds + buf * L_STAGE + (32 * w) * LROW;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(xg[q] + k, (__attribute__((address_space(3))) void *)(sa + q * 8 * LROW), 16, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(((q & 1) ? wg_odd : wg_even) + (size_t)(8 * q) * a.h_in + k,
+                                             (__attribute__((address_space(3))) void *)(sa + L_A + q * 8 * LROW), 16, 0, 0);
+    };
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+
+    load_stage(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    // operand reads: row R, k piece 2ks + h sits in slot (2ks + h) ^ ((R/2) % 8); R/2 % 8 = (m/2) % 8 for all of a lane's rows
+    const int swz = (m >> 1) & 7;
+    for (int kt = 0; kt < n_k; ++kt) {
+        // the next stage is requested before this one is multiplied, into the buffer that was read
+        // in the previous iteration (past the end: the last stage again, unconditionally)
+        load_stage(min(kt + 1, n_k - 1), (kt + 1) & 1);
+        const unsigned char *sa = lds + (kt & 1) * L_STAGE + (128 * rh + m) * LROW;
+        const unsigned char *sb = lds + (kt & 1) * L_STAGE + L_A + (64 * cq + m) * LROW;
+        // operands of k step ks+1 are read while the products of k step ks run; the fences keep the
+        // compiler from pulling all 32 operand reads of the stage to the front (it then spills the
+        // staging registers)
+        bf16x8 aop[2][4], bop[2][2];
+        auto read_ops = [&](int ks, bf16x8(&ao)[4], bf16x8(&bo)[2]) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * LROW + (((2 * ks + h) ^ swz) << 4));
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * LROW + (((2 * ks + h) ^ swz) << 4));
+        };
+        read_ops(0, aop[0], bop[0]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            // half of the step's products, then the operand reads of the next step, then the other half:
+            // the reads have four products' time to complete before the wait that precedes their use
+            // (the wait counts all LDS reads in flight; and left alone, the compiler sinks the reads
+            // below the products that free their registers)
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks & 1][mb], bop[ks & 1][nb], acc[mb][nb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks < 3) read_ops(ks + 1, aop[(ks + 1) & 1], bop[(ks + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mb = 2; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks & 1][mb], bop[ks & 1][nb], acc[mb][nb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's part of the next stage has landed
+        __syncthreads();
+    }
+
+    // ---- the adapter slab: s.v of the block's rows to LDS as bf16 (zero past a tile's rank or end) ----
+    unsigned char *sv = lds;
+    {
+        // chunk tid%16 (8 ranks) of rows tid/16 + 32*j: row tile j/2, row (tid/16 + 32*(j%2)) of it
+        const int c8 = tid & 15, r0 = tid >> 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const DevItem &t = tile_of(j >> 1);
+            const int ti = r0 + 32 * (j & 1);
+            const int ks16 = (t.rank + 15) >> 4;  // k steps this tile's products will read
+            if (c8 < 2 * ks16) {
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
+                if (ti < t.n_tok && c8 * 8 < t.rank) {
+                    const float s = a.scale * t.alpha;
+                    const float4 *vr = reinterpret_cast<const float4 *>(
+                        a.v + (size_t)row_tile_token(a.tok_list, t, ti) * a.v_stride + c8 * 8);
+                    const float4 lo = vr[0], hi = vr[1];
+                    const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)(c8 * 8 + e < t.rank ? s * f[e] : 0.f);
+                }
+                *reinterpret_cast<bf16x8 *>(sv + (64 * (j >> 1) + ti) * SV_ROW + c8 * 16) = o;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+        const DevItem &t = tl ? mine1 : mine0;
+        if (t.rank == 0 || t.n_tok == 0) continue;  // wavefront-uniform
+        const int rs8 = rank_storage(t.rank) >> 3, ks16 = (t.rank + 15) >> 4;
+        const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)t.row * a.row_bytes) + (size_t)(rs8 * 8) * a.h_in;
+        const unsigned char *svr = sv + (128 * rh + 64 * tl + m) * SV_ROW + h * 16;
+        for (int ks = 0; ks < ks16; ++ks) {
+            const __bf16 *bg = Bp + (size_t)min(2 * ks + h, rs8 - 1) * a.h_out * 8;
+            bf16x8 bop[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int col = min(n0 + 64 * cq + 32 * nb + m, a.h_out - 1);
+                bop[nb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bg + (size_t)col * 8));
+            }
+#pragma unroll
+            for (int mbl = 0; mbl < 2; ++mbl) {
+                const bf16x8 aop = *reinterpret_cast<const bf16x8 *>(svr + mbl * 32 * SV_ROW + ks * 32);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[2 * tl + mbl][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nb], acc[2 * tl + mbl][nb], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- store: register i of lane (m, h) of block (mb, nb) is row 32*mb + 8*(i/4) + 4*h + i%4, column 32*nb + m ----
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+        const DevItem &t = (mb >> 1) ? mine1 : mine0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int ti = 32 * (mb & 1) + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (ti >= t.n_tok) continue;
+            __bf16 *yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out;
+            const bool add_y = t.rank == 0 && t.a == 1;  // the row holds its adapter term already
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int col = n0 + 64 * cq + 32 * nb + m;
+                if (col < a.h_out) yr[col] = (__bf16)(acc[mb][nb][e] + (add_y ? (float)yr[col] : 0.f));
+            }
+        }
+    }
+}
+
+// y[token][0 .. h_out) = 0 for the listed tokens (the rows the GEMV expand then adds its term to)
+__global__ __launch_bounds__(256) void zero_rows_kernel(__bf16 *__restrict__ y, const int32_t *__restrict__ toks, int n, int h_out)
+{
+    const int per_row = h_out / 8;  // 16-byte pieces
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n * per_row; i += gridDim.x * 256) {
+        const int r = i / per_row, c = i - r * per_row;
+        *reinterpret_cast<uint4 *>(y + (size_t)toks[r] * h_out + c * 8) = make_uint4(0, 0, 0, 0);
+    }
+}
+
+hipError_t launch_zero_rows(void *y, const int32_t *toks, int n, int h_out, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const int blocks = std::min(1024, (n * (h_out / 8) + 255) / 256);
+    hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, st, static_cast<__bf16 *>(y), toks, n, h_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, hipStream_t st,
+                               const KernelTimer *tm)
+{
+    if (n_rt <= 0) return hipSuccess;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(linear_tiles_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 2 * L_STAGE);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int n_mt = (n_rt + 3) / 4, n_nt = (a.h_out + LBN - 1) / LBN;
+    hipEvent_t s = nullptr, e = nullptr;
+    if (tm) tm->pair(tm->ctx, LORA_K_LINEAR, &s, &e);
+    if (s && e)
+        hipExtLaunchKernelGGL(linear_tiles_kernel, dim3(n_mt * n_nt), dim3(512), 2 * L_STAGE, st, s, e, 0, a,
+                              static_cast<const __bf16 *>(Wt), row_tiles, n_rt, n_mt);
+    else
+        hipLaunchKernelGGL(linear_tiles_kernel, dim3(n_mt * n_nt), dim3(512), 2 * L_STAGE, st, a, static_cast<const __bf16 *>(Wt),
+                           row_tiles, n_rt, n_mt);
+    return hipGetLastError();
+}
+
+}  // namespace lora

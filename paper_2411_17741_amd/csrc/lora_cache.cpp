@@ -73,6 +73,10 @@ struct lora_plan {
     int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
     int32_t mfma_min_used = 0;  // the threshold the work lists were made with
     size_t off_tiles = 0, off_gs = 0, off_ge = 0;
+    // for lora_linear_plan: every token of the batch in row tiles -- the tiles above, then runs of up
+    // to 64 of the other tokens (rank 0) -- over a token list of its own
+    size_t off_lin_tok = 0, off_lin_tiles = 0;
+    int32_t n_lin_tiles = 0;
     std::vector<int32_t> slots;        // distinct slots the batch names
     std::vector<uint32_t> generations;  // their generation at plan time
 };
@@ -198,7 +202,9 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     const size_t max_batches = (size_t)c.max_segments + (size_t)c.max_tokens / LORA_GEMV_BATCH + 1;
     const size_t max_items = max_tiles + max_batches * (LORA_MAX_RANK / 4 + 16);
     c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) +
-                 align_up(sizeof(int32_t) * max_batches) + 4 * ALIGN;
+                 align_up(sizeof(int32_t) * max_batches) + 4 * ALIGN +
+                 align_up(sizeof(int32_t) * (size_t)c.max_tokens) +
+                 align_up(sizeof(lora_item_t) * (max_tiles + (size_t)c.max_tokens / LORA_TILE_TOKENS + 2));
     c.stage_cap = align_up(max_part) + ALIGN;
 
     size_t cur = align_up(c.layer_stride * (size_t)c.n_layers);
@@ -453,7 +459,40 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     p.off_tiles = align_up(sizeof(int32_t) * (size_t)w.n_tok_list);
     p.off_gs = p.off_tiles + align_up(sizeof(lora_item_t) * (size_t)w.n_tiles);
     p.off_ge = p.off_gs + align_up(sizeof(lora_item_t) * (size_t)w.n_gs_items);
-    const size_t bytes = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    // row tiles of the whole batch (bf16 caches: lora_linear_plan): the tiles; then runs of up to 64
+    // of the tokens of the GEMV groups (marked a = 1: their output rows carry the adapter term when
+    // the base product is added); then runs of the tokens that name no adapter.  The token list is
+    // tok_list followed by the latter.
+    std::vector<int32_t> lin_tok;
+    std::vector<lora::DevItem> lin_tiles;
+    if (c.dtype == LORA_BF16) {
+        std::vector<uint8_t> named((size_t)T, 0);
+        lin_tok.assign(w.tok_list, w.tok_list + w.n_tok_list);
+        for (int32_t t : lin_tok) named[t] = 1;
+        for (int32_t t = 0; t < T; ++t)
+            if (!named[t]) lin_tok.push_back(t);
+        lin_tiles.resize(w.n_tiles);
+        std::memcpy(lin_tiles.data(), w.tiles, sizeof(lora::DevItem) * (size_t)w.n_tiles);  // stamped above
+        auto plain_runs = [&](int32_t from, int32_t to, int32_t mark) {
+            for (int32_t o = from; o < to; o += LORA_TILE_TOKENS) {
+                lora::DevItem d{};
+                d.tok_off = o;
+                d.n_tok = std::min<int32_t>(LORA_TILE_TOKENS, to - o);
+                d.a = mark;
+                d.tok0 = lin_tok[o];
+                d.consecutive = 1;
+                for (int32_t i = 1; i < d.n_tok; ++i)
+                    if (lin_tok[o + i] != d.tok0 + i) d.consecutive = 0;
+                lin_tiles.push_back(d);
+            }
+        };
+        plain_runs(p.n_tile_tok, w.n_tok_list, 1);
+        plain_runs(w.n_tok_list, (int32_t)lin_tok.size(), 0);
+    }
+    p.n_lin_tiles = (int32_t)lin_tiles.size();
+    p.off_lin_tok = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    p.off_lin_tiles = p.off_lin_tok + align_up(sizeof(int32_t) * lin_tok.size());
+    const size_t bytes = p.off_lin_tiles + align_up(sizeof(lora::DevItem) * lin_tiles.size());
     if (bytes > c.plan_cap) {
         lora_worklists_free(&w);
         return LORA_E_NOMEM;
@@ -479,6 +518,8 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
         std::memcpy(p.pinned + p.off_gs, w.gs_items, sizeof(lora_item_t) * (size_t)w.n_gs_items);
         std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
+        if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
+        if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
         lora_worklists_free(&w);
         if (bytes) {
             HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
@@ -1138,6 +1179,71 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
     if (rc != LORA_OK) return rc;
     rc = enqueue_apply(c, p, layer, proj, x, base_out, scale, st);
     if (rc != LORA_OK) return rc;
+    return fence_applies(c, p, st);
+}
+
+int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, const void *Wt, void *y,
+                     float scale, void *stream)
+{
+    if (!c || !p || !p->in_use || c->host_only || c->dtype != LORA_BF16) return LORA_E_INVAL;
+    int rc = validate_apply(c, p, layer, proj, x, y);
+    if (rc != LORA_OK) return rc;
+    if (p->T > 0 && (!Wt || !aligned16(Wt))) return LORA_E_INVAL;
+    if (p->T == 0) return LORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (p->upload_pending) HIP_TRY(hipStreamWaitEvent(st, p->ev_upload, 0));
+    for (int32_t sl : p->slots) {
+        Slot &s = c->slots[sl];
+        if (s.fill_pending) {
+            if (hipEventQuery(s.fill_ev) == hipSuccess) s.fill_pending = false;
+            else HIP_TRY(hipStreamWaitEvent(st, s.fill_ev, 0));
+        }
+    }
+    const lora::KernelTimer timer{c, timer_pair};
+    const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
+    const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(p->dev + p->off_tiles);
+    const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
+    const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
+    lora::ApplyArgs a;
+    a.proj_base = c->pool + (size_t)layer * c->layer_stride + c->proj_off[proj];
+    a.row_bytes = (int64_t)c->row_bytes[proj];
+    a.tok_list = reinterpret_cast<const int32_t *>(p->dev);
+    a.x = x;
+    a.y = y;
+    a.v = reinterpret_cast<float *>(c->pool + c->off_v);
+    a.h_in = c->proj[proj].h_in;
+    a.h_out = c->proj[proj].h_out;
+    a.v_stride = c->v_stride;
+    a.scale = scale;
+    // shrink of the tiles and of the GEMV groups (x is read, v written)
+    if (p->n_tiles > 0) {
+        lora::ShrinkProjs ps;
+        ps.n = 1;
+        for (int j = 0; j < 9; ++j) ps.xcd_tile[j] = p->xcd_tile[j];
+        for (int i = 0; i < lora::MAX_SHRINK_PROJS; ++i) {
+            ps.proj_base[i] = i ? nullptr : a.proj_base;
+            ps.row_bytes[i] = i ? 0 : a.row_bytes;
+            ps.v[i] = i ? nullptr : a.v;
+            ps.part[i] = i ? nullptr : reinterpret_cast<float *>(c->pool + c->off_vpart);
+        }
+        HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, p->n_tile_tok, choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in), st, tm));
+    }
+    // the adapter term of the GEMV tokens, into their zeroed output rows
+    if (p->n_tok_list > p->n_tile_tok) {
+        HIP_TRY(lora::launch_zero_rows(y, a.tok_list + p->n_tile_tok, p->n_tok_list - p->n_tile_tok, a.h_out, st));
+        HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));
+        HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st, tm));
+    }
+    // base product of every token + adapter product of the tiles (+ the term just computed for the others)
+    lora::ApplyArgs lin = a;
+    lin.tok_list = reinterpret_cast<const int32_t *>(p->dev + p->off_lin_tok);
+    HIP_TRY(lora::launch_linear_tiles(lin, Wt, reinterpret_cast<const lora::DevItem *>(p->dev + p->off_lin_tiles), p->n_lin_tiles, st, tm));
+    const int64_t seq = ++c->apply_seq;
+    ++c->stats.applies;
+    for (int32_t sl : p->slots) {
+        c->slots[sl].last_used = seq;
+        ++c->slots[sl].use_count;
+    }
     return fence_applies(c, p, st);
 }
 

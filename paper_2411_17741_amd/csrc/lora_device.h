@@ -8,6 +8,7 @@ namespace lora {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // 8 consecutive elements: one 16-byte vector of bf16, two of fp32.
 template <typename E> struct Chunk;

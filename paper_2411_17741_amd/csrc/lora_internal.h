@@ -107,6 +107,11 @@ hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const D
                               int k_splits, hipStream_t st, const KernelTimer *tm);
 int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
+// y = x . Wt^T + adapter update for row tiles (tiles of the plan, then plain runs of the other tokens:
+// rank 0); a.tok_list must be the list the row tiles index; a.v holds the shrink results
+hipError_t launch_zero_rows(void *y, const int32_t *toks, int n, int h_out, hipStream_t st);  // y bf16 [..][h_out]
+hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, hipStream_t st,
+                               const KernelTimer *tm);
 // A [h_in][r] / B [r][h_out] (16-byte aligned; device memory, or pinned host memory as the device
 // sees it: from_host) -> slab layout
 hipError_t launch_repack(int dtype, const void *src_A, const void *src_B, void *slab, int32_t h_in, int32_t h_out,
