@@ -516,7 +516,18 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         }
         std::memcpy(p.pinned, w.tok_list, sizeof(int32_t) * (size_t)w.n_tok_list);
         std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
-        std::memcpy(p.pinned + p.off_gs, w.gs_items, sizeof(lora_item_t) * (size_t)w.n_gs_items);
+        {
+            // One block works on one shrink item and block b runs on XCD b % 8, each XCD behind its own
+            // L2.  The items of a token batch (4 slab rows each, all reading the batch's x rows) follow
+            // each other in the list: XCD j gets a run of consecutive items, the i-th of them as block
+            // 8i + j, so that a batch's x rows are fetched from memory by one XCD, not by all eight.
+            lora_item_t *dst = reinterpret_cast<lora_item_t *>(p.pinned + p.off_gs);
+            const int n = w.n_gs_items;
+            for (int b = 0; b < n; ++b) {
+                const int j = b & 7;
+                dst[b] = w.gs_items[j * (n >> 3) + std::min(j, n & 7) + (b >> 3)];
+            }
+        }
         std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
         if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
         if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
