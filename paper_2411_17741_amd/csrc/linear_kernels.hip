@@ -20,6 +20,9 @@
 // 4 + 2 operands from LDS for 8 products.
 // Operand layout of the instruction: A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7;
 // B (16 x 32): lane l holds column l%32, same k; D: lane l holds column l%32, rows 8*(i/4) + 4*(l/32) + i%4.
+// The products are formed transposed -- the W block is the row operand, the x block the column
+// operand -- so that a lane's four consecutive accumulator registers are four consecutive output
+// columns of one token: 8 bytes of bf16, parked in LDS and stored from there in whole 128-byte lines.
 // After the k loop the scaled intermediate s.v of the block's rows is staged in LDS as bf16 and every
 // wavefront adds, per row tile, the products with that tile's Bp, whose rank-packed layout gives the
 // B operand directly from global memory (32 lanes read 512 contiguous bytes).
@@ -38,7 +41,7 @@ constexpr int LROW = LBK * 2;                   // bytes per row of a stage in L
 constexpr int L_A = LBM * LROW;                 // x part of a stage
 constexpr int L_STAGE = (LBM + LBN) * LROW;     // 73728 bytes
 constexpr int SV_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per row of the staged s.v
-static_assert(LBM * SV_ROW <= 2 * L_STAGE, "s.v is staged in the stage buffers");
+static_assert(8 * 128 * 128 <= 2 * L_STAGE && LBM * SV_ROW <= 2 * L_STAGE, "s.v is staged in the stage buffers");
 }  // namespace
 
 __device__ __forceinline__ int row_tile_token(const int32_t *tok_list, const DevItem &it, int ti)
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks & 1][mb], bop[ks & 1][nb], acc[mb][nb], 0, 0, 0);
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[ks & 1][nb], aop[ks & 1][mb], acc[mb][nb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (ks < 3) read_ops(ks + 1, aop[(ks + 1) & 1], bop[(ks + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
             for (int mb = 2; mb < 4; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks & 1][mb], bop[ks & 1][nb], acc[mb][nb], 0, 0, 0);
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[ks & 1][nb], aop[ks & 1][mb], acc[mb][nb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's part of the next stage has landed
@@ -211,25 +214,73 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
                 const bf16x8 aop = *reinterpret_cast<const bf16x8 *>(svr + mbl * 32 * SV_ROW + ks * 32);
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[2 * tl + mbl][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop, bop[nb], acc[2 * tl + mbl][nb], 0, 0, 0);
+                    acc[2 * tl + mbl][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[nb], aop, acc[2 * tl + mbl][nb], 0, 0, 0);
             }
         }
     }
 
-    // ---- store: register i of lane (m, h) of block (mb, nb) is row 32*mb + 8*(i/4) + 4*h + i%4, column 32*nb + m ----
+    // ---- store.  The products are formed transposed (the W block is the instruction's row operand, the x
+    // block its column operand): lane (m, h) holds, in registers 4g .. 4g+3 of block (mb, nb), row 32*mb + m of
+    // the wavefront's 128 and the four consecutive columns 32*nb + 8g + 4h .. of its 64 -- 8 bytes of bf16.
+    // The wavefront parks its 128 x 64 outputs in LDS and stores whole 128-byte row pieces, 8 rows per
+    // instruction (stored from the registers, an instruction would write 16 bytes to each of 32 rows).
+    // Park layout, free of bank conflicts both ways: row r is 128 bytes, its 16-byte slot s sits at
+    // s ^ ((r/2) % 8), and the two 8-byte halves of a slot are swapped in rows with (r/16) % 2 = 1.
+    // Row tiles whose rows already hold the adapter term (GEMV tokens) are few and go straight from the
+    // registers, the sum formed in fp32 before the one rounding.
+    __syncthreads();  // every wavefront is done with the staged s.v
+    unsigned char *park = lds + w * (128 * 128);
+    const bool cols_live = n0 + 64 * cq < a.h_out;  // h_out is a multiple of 64
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-        const DevItem &t = (mb >> 1) ? mine1 : mine0;
+    for (int tl = 0; tl < 2; ++tl) {
+        const DevItem &t = tl ? mine1 : mine0;
+        if (t.n_tok == 0 || !cols_live) continue;  // wavefront-uniform
+        const bool add_y = t.rank == 0 && t.a == 1;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int ti = 32 * (mb & 1) + 8 * (e >> 2) + 4 * h + (e & 3);
-            if (ti >= t.n_tok) continue;
-            __bf16 *yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out;
-            const bool add_y = t.rank == 0 && t.a == 1;  // the row holds its adapter term already
+        for (int mbl = 0; mbl < 2; ++mbl) {
+            const int ti = 32 * mbl + m, row = 64 * tl + ti;
+            __bf16 *yr = nullptr;
+            if (add_y && ti < t.n_tok) yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 4 * h;
+            unsigned char *pr = park + row * 128 + ((h ^ ((row >> 4) & 1)) << 3);
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int col = n0 + 64 * cq + 32 * nb + m;
-                if (col < a.h_out) yr[col] = (__bf16)(acc[mb][nb][e] + (add_y ? (float)yr[col] : 0.f));
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const floatx16 &c = acc[2 * tl + mbl][nb];
+                    float f[4] = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                    if (add_y) {
+                        if (yr) {
+                            bf16x4 *dst = reinterpret_cast<bf16x4 *>(yr + 32 * nb + 8 * g);
+                            const bf16x4 old = *dst;
+                            bf16x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(f[e] + (float)old[e]);
+                            *dst = o;
+                        }
+                    } else {
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)f[e];
+                        *reinterpret_cast<bf16x4 *>(pr + (((4 * nb + g) ^ ((row >> 1) & 7)) << 4)) = o;
+                    }
+                }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // only this wavefront reads what it wrote; its LDS operations execute in order
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+        const DevItem &t = tl ? mine1 : mine0;
+        if (t.n_tok == 0 || !cols_live || (t.rank == 0 && t.a == 1)) continue;  // wavefront-uniform
+        const int rl = lane >> 3, sl = lane & 7;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int ti = 8 * i + rl, row = 64 * tl + ti;
+            if (ti < t.n_tok) {
+                uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((sl ^ ((row >> 1) & 7)) << 4));
+                if ((row >> 4) & 1) v = make_uint4(v.z, v.w, v.x, v.y);
+                *reinterpret_cast<uint4 *>(y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 8 * sl) = v;
             }
         }
     }

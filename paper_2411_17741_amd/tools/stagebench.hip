@@ -1,0 +1,164 @@
+// How fast can the blocks of the fused GEMM bring their stages into the CUs, alone and beside the products?  (microbenchmark)
+// Grid and addresses of linear_tiles_kernel on the prefill shape (23 x 16 blocks of 512 threads, 64 stages of 64 k;
+// a stage = 256 rows x 128 B of x and 256 rows x 128 B of Wt, rows 8 KB apart), three copies of the inputs in rotation.
+// Variants: stages written to LDS by the load itself or through registers, with and without a barrier per stage,
+// requested one stage ahead, and the same beside 32 matrix-core products per wavefront and stage (operands from
+// registers, or read from LDS as the kernel reads them), and the products alone.
+//   hipcc --offload-arch=gfx950 -O3 -std=c++17 stagebench.hip -o stagebench && ./stagebench
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <vector>
+#define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("hip error %s at %d\n", hipGetErrorString(e_), __LINE__); return 1; } } while (0)
+constexpr int H = 4096, NK = H / 64, STAGE = 65536;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+template <int MODE>
+__global__ __launch_bounds__(512) void stage_kernel(const unsigned short *__restrict__ x, const unsigned short *__restrict__ wt, int n_mt, uint4 *sink)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bm = blockIdx.x % n_mt, bn = blockIdx.x / n_mt;
+    const int lr = lane >> 3, ls = lane & 7;
+    const unsigned short *xg = x + (size_t)(256 * bm + 32 * w + lr) * H + ls * 8;
+    const unsigned short *wg = wt + (size_t)(256 * bn + 32 * w + lr) * H + ls * 8;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    if constexpr (MODE >= 6) {  // LDS-direct one stage ahead + MFMA (6), + LDS reads (7), + both (8); 9: MFMA + reads, no loads
+        auto load = [&](int kt, int buf) {
+            unsigned char *sa = lds + buf * STAGE + 32 * w * 128;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(xg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(wg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + 32768 + q * 1024), 16, 0, 0);
+        };
+        floatx16 c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) c[i][e] = 0.f;
+        bf16x8 ra, rb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ra[e] = (__bf16)(float)(lane + e); rb[e] = (__bf16)(float)(w + e); }
+        for (int i = tid; i < 2 * STAGE / 16; i += 512) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(tid, i, 3, 4);
+        __syncthreads();
+        load(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        const int m = lane & 31, hh = lane >> 5, swz = (m >> 1) & 7;
+        for (int kt = 0; kt < NK; ++kt) {
+            if (MODE != 9) load(min(kt + 1, NK - 1), (kt + 1) & 1);
+            const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * (w & 1) + m) * 128;
+            const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (64 * (w >> 1) + m) * 128;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 ao[4], bo[2];
+                if (MODE >= 7) {
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+                } else {
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb) ao[mb] = ra;
+                    bo[0] = rb; bo[1] = rb;
+                }
+                if (MODE == 6 || MODE >= 8) {
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < 2; ++nb) c[2 * mb + nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[mb], bo[nb], c[2 * mb + nb], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb) { acc.x ^= __builtin_bit_cast(uint4, ao[mb]).x; }
+                    acc.y ^= __builtin_bit_cast(uint4, bo[0]).y ^ __builtin_bit_cast(uint4, bo[1]).z;
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc.x ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
+    } else if constexpr (MODE == 0 || MODE == 2 || MODE == 3) {  // LDS-direct
+        auto load = [&](int kt, int buf) {
+            unsigned char *sa = lds + buf * STAGE + 32 * w * 128;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(xg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(wg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + 32768 + q * 1024), 16, 0, 0);
+        };
+        if (MODE == 3) {
+            load(0, 0);
+            for (int kt = 0; kt < NK; ++kt) {
+                load(min(kt + 1, NK - 1), (kt + 1) & 1);
+                asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            for (int kt = 0; kt < NK; ++kt) {
+                load(kt, kt & 1);
+                if (MODE == 0) { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); }
+                else { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+            }
+        }
+        __syncthreads();
+        acc = *reinterpret_cast<const uint4 *>(lds + tid * 16);
+    } else {  // registers
+        for (int kt = 0; kt < NK; ++kt) {
+            uint4 r[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(xg + (size_t)(8 * q) * H + kt * 64);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[4 + q] = *reinterpret_cast<const uint4 *>(wg + (size_t)(8 * q) * H + kt * 64);
+            if (MODE == 1) {
+                unsigned char *sa = lds + (kt & 1) * STAGE + 32 * w * 128 + lane * 16;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4 *>(sa + q * 1024) = r[q];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4 *>(sa + 32768 + q * 1024) = r[4 + q];
+                __syncthreads();
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) { acc.x ^= r[q].x; acc.y ^= r[q].y; acc.z ^= r[q].z; acc.w ^= r[q].w; }
+                if (MODE == 5) __syncthreads();
+            }
+        }
+        if (MODE == 1) acc = *reinterpret_cast<const uint4 *>(lds + tid * 16);
+    }
+    if ((acc.x ^ acc.y) == 0x12345678u) sink[blockIdx.x * 512 + tid] = acc;
+}
+template <int MODE> int run(const char *name, const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
+{
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(stage_kernel<MODE>, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x, wt, n_mt, sink);
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    const int reps = 21;
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(stage_kernel<MODE>, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x + (size_t)(i % 3) * n_mt * 256 * H, wt + (size_t)(i % 3) * n_nt * 256 * H, n_mt, sink);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+    const double us = ms * 1e3 / reps, bytes = (double)n_mt * n_nt * NK * STAGE;
+    printf("%-44s %8.1f us  %6.2f TB/s into the CUs  %5.1f GB/s per CU\n", name, us, bytes / us * 1e-6, bytes / us * 1e-3 / 256);
+    fflush(stdout);
+    return 0;
+}
+int main()
+{
+    const int n_mt = 23, n_nt = 16;
+    unsigned short *x, *wt; uint4 *sink;
+    CHECK(hipMalloc(&x, (size_t)3 * n_mt * 256 * H * 2)); CHECK(hipMalloc(&wt, (size_t)3 * n_nt * 256 * H * 2)); CHECK(hipMalloc(&sink, (size_t)n_mt * n_nt * 512 * 16));
+    CHECK(hipMemset(x, 1, (size_t)3 * n_mt * 256 * H * 2)); CHECK(hipMemset(wt, 2, (size_t)3 * n_nt * 256 * H * 2));
+    if (run<0>("LDS-direct, wait + barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<2>("LDS-direct, wait per stage, no barrier", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<3>("LDS-direct, one stage ahead, barrier", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<6>("LDS-direct ahead + 32 MFMA/stage (reg operands)", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<8>("LDS-direct ahead + 24 LDS reads + 32 MFMA/stage", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<9>("24 LDS reads + 32 MFMA/stage, no loads", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<1>("registers + ds_write, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<4>("registers only, no barrier", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<5>("registers only, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
+    return 0;
+}
