@@ -3,7 +3,8 @@
 // a stage = 256 rows x 128 B of x and 256 rows x 128 B of Wt, rows 8 KB apart), three copies of the inputs in rotation.
 // Variants: stages written to LDS by the load itself or through registers, with and without a barrier per stage,
 // requested one stage ahead, and the same beside 32 matrix-core products per wavefront and stage (operands from
-// registers, or read from LDS as the kernel reads them), and the products alone.
+// registers, or read from LDS as the kernel reads them), and the products alone; and a schedule in which
+// the two wavefronts of a SIMD alternate between (operand reads + load requests) and products, a barrier between the phases.
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 stagebench.hip -o stagebench && ./stagebench
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -22,7 +23,98 @@ __global__ __launch_bounds__(512) void stage_kernel(const unsigned short *__rest
     const unsigned short *xg = x + (size_t)(256 * bm + 32 * w + lr) * H + ls * 8;
     const unsigned short *wg = wt + (size_t)(256 * bn + 32 * w + lr) * H + ls * 8;
     uint4 acc = make_uint4(0, 0, 0, 0);
-    if constexpr (MODE >= 6) {  // LDS-direct one stage ahead + MFMA (6), + LDS reads (7), + both (8); 9: MFMA + reads, no loads
+    if constexpr (MODE == 10) {  // the two wavefronts of a SIMD alternate: one reads operands and requests loads, the other multiplies
+        auto load = [&](int kt, int buf) {
+            unsigned char *sa = lds + buf * STAGE + 32 * w * 128;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(xg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds(wg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + 32768 + q * 1024), 16, 0, 0);
+        };
+        floatx16 c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) c[i][e] = 0.f;
+        for (int i = tid; i < 2 * STAGE / 16; i += 512) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(tid, i, 3, 4);
+        __syncthreads();
+        load(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        const int m = lane & 31, hh = lane >> 5, swz = (m >> 1) & 7;
+        const int grp = w >> 2, wt_ = w & 3, rh = wt_ & 1, cq2 = (wt_ >> 1) + 2 * grp;  // 8 wavefront tiles as before
+        bf16x8 ao[2][4], bo[2][2];
+        auto mem = [&](int kt, int half) {
+            const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * rh + m) * 128;
+            const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (64 * cq2 + m) * 128;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int ks = 2 * half + kk;
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) ao[kk][mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) bo[kk][nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+            }
+        };
+        auto mul = [&]() {
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) c[2 * mb + nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk][mb], bo[kk][nb], c[2 * mb + nb], 0, 0, 0);
+        };
+        if (grp == 0) {
+            for (int kt = 0; kt < NK; ++kt) {
+                load(min(kt + 1, NK - 1), (kt + 1) & 1);
+                mem(kt, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mul();
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mem(kt, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mul();
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            for (int kt = 0; kt < NK; ++kt) {
+                load(min(kt + 1, NK - 1), (kt + 1) & 1);
+                mem(kt, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mul();
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mem(kt, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                mul();
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc.x ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
+    } else if constexpr (MODE >= 6) {  // LDS-direct one stage ahead + MFMA (6), + LDS reads (7), + both (8); 9: MFMA + reads, no loads
         auto load = [&](int kt, int buf) {
             unsigned char *sa = lds + buf * STAGE + 32 * w * 128;
 #pragma unroll
@@ -157,6 +249,7 @@ int main()
     if (run<6>("LDS-direct ahead + 32 MFMA/stage (reg operands)", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<8>("LDS-direct ahead + 24 LDS reads + 32 MFMA/stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<9>("24 LDS reads + 32 MFMA/stage, no loads", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<10>("alternating wavefronts: reads+loads | MFMA", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<1>("registers + ds_write, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<4>("registers only, no barrier", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<5>("registers only, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
