@@ -138,6 +138,147 @@ def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
     return 0
 
 
+def prefetch_sweep(args) -> int:
+    """Queue-driven prefetch (paper section 4.2: the adapters of waiting requests are loaded before their
+    batch runs) measured as fill/apply overlap on the host link.  A stream of decode batches over the
+    paper's adapter population (N_a/5 adapters per rank, rank uniform, power law within the rank) runs
+    against a pool that holds only part of the adapters.  Iteration k acquires the adapters of its batch
+    (pinned; a miss is loaded from pinned host memory on a side stream, and the apply waits for it), then
+    -- at depth d > 0 -- acquires unpinned and loads what batch k+d will need, and applies.  Prints one
+    JSON line: time per iteration, demand misses and bytes loaded for every depth."""
+    import torch
+    from paper_2411_17741_amd import binding as B
+    from paper_2411_17741_amd.pool import LoraPool
+
+    depths = [int(d) for d in args.prefetch_depths.split(",")]
+    n_tok, n_a, n_layers = args.tokens if args.tokens != 64 else 256, args.adapters if args.adapters != 100 else 200, args.layers or 8
+    ranks = [8, 16, 32, 64, 128]
+    per_rank = n_a // 5
+    slots_per_rank = args.slots_per_rank or per_rank - max(2, per_rank // 13)
+    projs = [(4096, 4096)] * 4
+    steps, warmup = args.steps or 40, max(args.warmup, 8)
+    n_iter = warmup + steps + max(depths) + 1
+    rng = np.random.default_rng(7)
+    # the request stream: per token a rank class, then an adapter of that rank by a power law (exponent 1.2: the paper states none)
+    w = 1.0 / np.arange(1, per_rank + 1) ** 1.2
+    cdf = np.cumsum(w / w.sum())
+    perm = [rng.permutation(per_rank) for _ in ranks]
+    batches = []
+    for _ in range(n_iter):
+        cls = rng.integers(0, 5, size=n_tok)
+        pos = np.minimum(np.searchsorted(cdf, rng.random(n_tok)), per_rank - 1)
+        batches.append(np.asarray([c * per_rank + perm[c][k] for c, k in zip(cls, pos)], np.int64))
+    need = [np.unique(b) for b in batches]
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    # every part of every adapter has host memory of its own in one pinned arena (what is loaded does not matter
+    # here, where from does: parts that shared host memory would be served from the GPU's caches, not over the link)
+    part_bytes = {r: 2 * 4096 * r * 2 for r in ranks}  # A [4096][r] + B [r][4096], bf16
+    adapter_bytes = [n_layers * 4 * part_bytes[ranks[a // per_rank]] for a in range(n_a)]
+    arena = torch.empty(sum(adapter_bytes), dtype=torch.uint8, pin_memory=True)
+    arena.view(torch.int16)[:] = 0x3c00  # a small bf16 number everywhere
+    parts_of, off = [], arena.data_ptr()
+    for a in range(n_a):
+        r = ranks[a // per_rank]
+        entries = []
+        for l in range(n_layers):
+            for p in range(4):
+                entries.append((l, p, off, off + part_bytes[r] // 2))
+                off += part_bytes[r]
+        parts_of.append(entries)
+    parts_c = [B.make_fill_parts(e) for e in parts_of]
+    x = torch.randn((n_tok, 4096), generator=gen, device=dev).to(torch.bfloat16)
+    ys = [torch.randn((n_tok, 4096), generator=gen, device=dev).to(torch.bfloat16) for _ in range(n_layers * 4)]
+    seg_offsets = np.arange(n_tok + 1, dtype=np.int32)
+    stream, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    sh = stream.cuda_stream
+    out = {}
+    for d in depths:
+        pool = LoraPool(projs, n_layers, ranks, [slots_per_rank] * 5, B.LORA_BF16, max_tokens=n_tok, max_segments=n_tok + 8, n_plans=4,
+                        flags=B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0)
+        h = pool.handle
+        B.check(B.lora_cache_set_fencing(h, 1))
+        descs = B.make_descs([(l, p, x.data_ptr(), ys[l * 4 + p].data_ptr()) for l in range(n_layers) for p in range(4)])
+        counts = {"demand_miss": 0, "demand_hit": 0, "prefetched": 0, "refused": 0, "bytes": 0, "t_fill": 0.0}
+
+        def load(a, slot):
+            r = ranks[a // per_rank]
+            t_f = time.perf_counter()
+            if args.fill_by_part:
+                for l, p, pa, pb in parts_of[a]:
+                    B.check(B.lora_cache_fill_slot(h, slot, 1000 + a, r, 1.0, l, p, pa, pb, side.cuda_stream), "fill")
+            else:
+                B.check(B.lora_cache_fill_slot_parts(h, slot, 1000 + a, r, 1.0, parts_c[a], side.cuda_stream), "fill")
+            counts["t_fill"] += time.perf_counter() - t_f
+            counts["bytes"] += adapter_bytes[a]
+
+        def iteration(k):
+            queued = np.concatenate(need[k + 1:k + 1 + d]) + 1000 if d else None
+            slot_of = {}
+            for a in need[k]:
+                a = int(a)
+                rc, slot, hit = B.lora_cache_acquire(h, 1000 + a, ranks[a // per_rank], 1.0, True, queued)
+                if rc == B.LORA_E_NOMEM:  # every slot of the class is held by this batch: the request runs without its adapter
+                    counts["refused"] += 1
+                    slot_of[a] = -1
+                    continue
+                B.check(rc, "acquire")
+                slot_of[a] = slot
+                counts["demand_hit" if hit else "demand_miss"] += 1
+                if not hit:
+                    load(a, slot)
+            if d:
+                for a in need[k + d]:
+                    a = int(a)
+                    rc, slot, hit = B.lora_cache_acquire(h, 1000 + a, ranks[a // per_rank], 1.0, False, queued)
+                    if rc != B.LORA_E_NOMEM:  # no slot to spare: the adapter will be a demand miss
+                        B.check(rc, "acquire")
+                    if rc == B.LORA_OK and not hit:
+                        counts["prefetched"] += 1
+                        load(a, slot)
+            seg_slot = np.asarray([slot_of[int(a)] for a in batches[k]], np.int32)
+            seg_rank = np.asarray([ranks[int(a) // per_rank] for a in batches[k]], np.int32)
+            rc, plan = B.lora_plan_create(h, n_tok, seg_offsets, seg_slot, seg_rank, sh)
+            B.check(rc, "lora_plan_create")
+            B.check(B.lora_apply_plan_multi(h, plan, descs, 2.0, sh), "lora_apply_plan_multi")
+            B.check(B.lora_plan_destroy(h, plan))
+            for a, slot in slot_of.items():
+                if slot >= 0:
+                    B.check(B.lora_cache_slot_ref(h, slot, -1))
+
+        for k in range(warmup):
+            iteration(k)
+        torch.cuda.synchronize()
+        for key in counts:
+            counts[key] = 0
+        t0 = time.perf_counter()
+        for k in range(warmup, warmup + steps):
+            iteration(k)
+        t_host = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        t_all = time.perf_counter() - t0
+        pool.check_fault()
+        out[str(d)] = {"ms_per_iteration": t_all * 1e3 / steps, "host_enqueue_ms_per_iteration": t_host * 1e3 / steps,
+                       "host_ms_in_fill_calls_per_iteration": counts["t_fill"] * 1e3 / steps,
+                       "demand_misses_per_iteration": counts["demand_miss"] / steps, "demand_hit_rate": counts["demand_hit"] / max(1, counts["demand_hit"] + counts["demand_miss"]),
+                       "prefetched_per_iteration": counts["prefetched"] / steps, "refused_per_iteration": counts["refused"] / steps,
+                       "loaded_MB_per_iteration": counts["bytes"] / steps / 1e6,
+                       "host_link_GBs": counts["bytes"] / t_all / 1e9}
+        pool.close()
+    best = min(out.values(), key=lambda r: r["ms_per_iteration"])
+    print(json.dumps({
+        "metric": "lora_apply_tokens_per_s_per_layer", "value": n_tok / (best["ms_per_iteration"] * 1e-3 / n_layers), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": best["ms_per_iteration"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"decode batches of {n_tok} one-token requests over {n_a} adapters (N_a/5 per rank 8..128, power law 1.2 within the rank), "
+                               f"pool of {slots_per_rank} slots per rank, q,k,v,o 4096->4096 bf16, {n_layers} layers; misses loaded from pinned host memory "
+                               "on a side stream; queue-driven prefetch at the listed depths", "tokens": n_tok, "layers_per_step": n_layers},
+        "prefetch_depth": out, "roofline": None, "cpu_baseline": None}))
+    return 0
+
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +294,11 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
     ap.add_argument("--fused-base", action="store_true", help="time lora_linear_plan (base projection and adapter update in one pass; "
                     "random base weights) instead of the apply on a given base output; prints its own JSON line")
+    ap.add_argument("--prefetch-depths", default="", help="e.g. 0,1,2,4: run the queue-driven prefetch experiment instead (own JSON line); "
+                    "uses --tokens (default 256), --adapters (default 200), --layers (default 8), --slots-per-rank, --direct-fill, --fill-by-part")
+    ap.add_argument("--fill-by-part", action="store_true", help="prefetch experiment: one lora_cache_fill_slot call per (layer, projection) "
+                    "instead of one lora_cache_fill_slot_parts call per adapter")
+    ap.add_argument("--slots-per-rank", type=int, default=0, help="prefetch experiment: pool slots per rank class (default: all but 3 of the 40 adapters of a rank)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -169,6 +315,8 @@ def main() -> int:
     from paper_2411_17741_amd import binding as B
     from paper_2411_17741_amd import harness as H
 
+    if args.prefetch_depths:
+        return prefetch_sweep(args)
     steps = args.steps or DEFAULT_STEPS[args.workload]
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
     if args.workload == "decode_paper":

@@ -135,6 +135,21 @@ int lora_cache_destroy(lora_cache_t *c);
 int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha,
                          int32_t layer, int32_t proj, const void *host_A, const void *host_B, void *fill_stream);
 
+/* The same for several parts of one adapter in one call (section 4.2: a missing adapter is loaded
+ * as a whole before its batch runs): parts[i] names a (layer, projection) and its two host arrays.
+ * One wait for earlier applies, one event, and -- with LORA_CACHE_DIRECT_FILL and pinned, 16-byte
+ * aligned host arrays -- one kernel per 32 parts instead of one per part: the host side of loading an
+ * adapter then costs about as much as one part did.  Otherwise the parts go through the staging
+ * buffers one after the other as lora_cache_fill_slot sends them.  Errors as lora_cache_fill_slot;
+ * on an error no part of the call is enqueued. */
+typedef struct {
+    int32_t layer, proj;
+    const void *host_A; /* [h_in][rank] */
+    const void *host_B; /* [rank][h_out] */
+} lora_fill_part_t;
+int lora_cache_fill_slot_parts(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha,
+                               const lora_fill_part_t *parts, int32_t n_parts, void *fill_stream);
+
 /* Evict: any state -> EMPTY.  No write-back (entries are read-only).  LORA_E_STATE if refcount > 0. */
 int lora_cache_release_slot(lora_cache_t *c, int32_t slot);
 

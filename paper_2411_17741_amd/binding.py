@@ -76,6 +76,9 @@ class lora_plan_info_t(ctypes.Structure):
 class lora_apply_desc_t(ctypes.Structure):
     _fields_ = [("layer", c_int32), ("proj", c_int32), ("x", c_void_p), ("base_out", c_void_p)]
 
+class lora_fill_part_t(ctypes.Structure):
+    _fields_ = [("layer", c_int32), ("proj", c_int32), ("host_A", c_void_p), ("host_B", c_void_p)]
+
 
 class lora_worklists_t(ctypes.Structure):
     _fields_ = [
@@ -99,6 +102,7 @@ _SIGS = {
     "lora_cache_create": (c_int, [POINTER(lora_cache_config_t), c_void_p, c_size_t, POINTER(c_void_p)]),
     "lora_cache_destroy": (c_int, [c_void_p]),
     "lora_cache_fill_slot": (c_int, [c_void_p, c_int32, c_int64, c_int32, c_float, c_int32, c_int32, c_void_p, c_void_p, c_void_p]),
+    "lora_cache_fill_slot_parts": (c_int, [c_void_p, c_int32, c_int64, c_int32, c_float, c_void_p, c_int32, c_void_p]),
     "lora_cache_release_slot": (c_int, [c_void_p, c_int32]),
     "lora_cache_slot_ref": (c_int, [c_void_p, c_int32, c_int32]),
     "lora_cache_lookup": (c_int, [c_void_p, c_int64, _i32p, _i32p]),
@@ -204,6 +208,19 @@ def lora_cache_fill_slot(cache, slot: int, adapter_id: int, rank: int, alpha: fl
                          host_A: int, host_B: int, fill_stream: int = 0) -> int:
     return _lib.lora_cache_fill_slot(cache, slot, adapter_id, rank, alpha, layer, proj, c_void_p(host_A or None),
                                      c_void_p(host_B or None), c_void_p(fill_stream or None))
+
+
+def make_fill_parts(entries):
+    """[(layer, proj, host_A address, host_B address), ...] -> C array for lora_cache_fill_slot_parts."""
+    arr = (lora_fill_part_t * len(entries))()
+    for i, (layer, proj, a, b) in enumerate(entries):
+        arr[i] = lora_fill_part_t(int(layer), int(proj), c_void_p(a or None), c_void_p(b or None))
+    return arr
+
+
+def lora_cache_fill_slot_parts(cache, slot: int, adapter_id: int, rank: int, alpha: float, parts, fill_stream: int = 0) -> int:
+    return _lib.lora_cache_fill_slot_parts(cache, slot, adapter_id, rank, alpha, ctypes.cast(parts, c_void_p), len(parts),
+                                           c_void_p(fill_stream or None))
 
 
 def lora_cache_release_slot(cache, slot: int) -> int:

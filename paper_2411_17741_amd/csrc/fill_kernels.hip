@@ -24,17 +24,18 @@ constexpr int REPACK_HOST_BLOCKS = 32;
 // B block: 256 threads x 8 columns; a thread loads the 8 columns of the 8 ranks of a granule
 // (8 loads, each 1 KB contiguous across a wavefront), transposes them in registers and writes
 // 8 chunks of Bp = 128 contiguous bytes.
+constexpr int REPACK_TROW = LORA_MAX_RANK + 2;  // LDS row stride in elements (breaks the power of two)
+
+// one work unit of a part; every thread of the block calls it with the same arguments
 template <typename E>
-__global__ __launch_bounds__(256) void repack_kernel(const E *__restrict__ A, const E *__restrict__ B, E *__restrict__ At,
-                                                     E *__restrict__ Bp, int h_in, int h_out, int r, int rs, int n_a_blocks)
+__device__ __forceinline__ void repack_unit(const E *__restrict__ A, const E *__restrict__ B, E *__restrict__ At, E *__restrict__ Bp,
+                                            int h_in, int h_out, int r, int rs, int n_a_blocks, int unit, E *tile)
 {
     constexpr int EPV = 16 / sizeof(E);            // elements per 16-byte piece
-    constexpr int TROW = LORA_MAX_RANK + 2;        // LDS row stride in elements (breaks the power of two)
-    __shared__ E tile[64 * TROW];
+    constexpr int TROW = REPACK_TROW;
     const int tid = threadIdx.x;
     const int nb = (h_out + 256 * 8 - 1) / (256 * 8);
-    const int n_units = n_a_blocks + (rs / 8) * nb;
-    for (int unit = blockIdx.x; unit < n_units; unit += gridDim.x) {  // uniform over the block
+    {
         if (unit < n_a_blocks) {
             const int k0 = unit * 64;
             const uint4 *src = reinterpret_cast<const uint4 *>(A + (size_t)k0 * r);
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const E *__restrict__ A, co
             // columns n0 .. n0+7 of granule j8
             const int bb = unit - n_a_blocks;
             const int j8 = bb / nb, n0 = ((bb - j8 * nb) * 256 + tid) * 8;
-            if (n0 >= h_out) continue;  // h_out is a multiple of 64, so a thread's 8 columns are all in or all out
+            if (n0 >= h_out) return;  // h_out is a multiple of 64, so a thread's 8 columns are all in or all out
             E in[8][8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -105,6 +106,33 @@ __global__ __launch_bounds__(256) void repack_kernel(const E *__restrict__ A, co
 }
 
 template <typename E>
+__global__ __launch_bounds__(256) void repack_kernel(const E *__restrict__ A, const E *__restrict__ B, E *__restrict__ At,
+                                                     E *__restrict__ Bp, int h_in, int h_out, int r, int rs, int n_a_blocks)
+{
+    __shared__ E tile[64 * REPACK_TROW];
+    const int n_units = n_a_blocks + (rs / 8) * ((h_out + 256 * 8 - 1) / (256 * 8));
+    for (int unit = blockIdx.x; unit < n_units; unit += gridDim.x)  // uniform over the block
+        repack_unit<E>(A, B, At, Bp, h_in, h_out, r, rs, n_a_blocks, unit, tile);
+}
+
+// Several parts of one adapter (same rank) in one launch: the blocks walk over the units of all parts.
+template <typename E>
+__global__ __launch_bounds__(256) void repack_parts_kernel(RepackTable t)
+{
+    __shared__ E tile[64 * REPACK_TROW];
+    const int total = t.p[t.n - 1].unit_end;
+    int part = 0;
+    for (int g = blockIdx.x; g < total; g += gridDim.x) {  // uniform over the block; g only grows
+        while (g >= t.p[part].unit_end) ++part;
+        const RepackPart &q = t.p[part];
+        const int first = part ? t.p[part - 1].unit_end : 0;
+        E *At = static_cast<E *>(q.slab);
+        repack_unit<E>(static_cast<const E *>(q.A), static_cast<const E *>(q.B), At, At + (size_t)t.rs * q.h_in, q.h_in, q.h_out, t.r,
+                       t.rs, q.h_in / 64, g - first, tile);
+    }
+}
+
+template <typename E>
 static hipError_t repack_t(const void *sa, const void *sb, void *slab, int h_in, int h_out, int r, bool from_host, hipStream_t st)
 {
     const int rs = rank_storage(r);
@@ -122,6 +150,24 @@ hipError_t launch_repack(int dtype, const void *src_A, const void *src_B, void *
 {
     if (dtype == LORA_BF16) return repack_t<__bf16>(src_A, src_B, slab, h_in, h_out, rank, from_host, st);
     return repack_t<float>(src_A, src_B, slab, h_in, h_out, rank, from_host, st);
+}
+
+// Parts of one adapter of rank `rank`: sources A, B and destination slab per part, all 16-byte aligned;
+// unit_end is filled in here.  from_host as above.
+hipError_t launch_repack_parts(int dtype, RepackTable &t, int32_t rank, bool from_host, hipStream_t st)
+{
+    if (t.n <= 0) return hipSuccess;
+    t.r = rank;
+    t.rs = rank_storage(rank);
+    int total = 0;
+    for (int i = 0; i < t.n; ++i) {
+        total += t.p[i].h_in / 64 + (t.rs / 8) * ((t.p[i].h_out + 2047) / 2048);
+        t.p[i].unit_end = total;
+    }
+    const dim3 grid(from_host ? std::min(total, 2 * REPACK_HOST_BLOCKS) : total);
+    if (dtype == LORA_BF16) hipLaunchKernelGGL((repack_parts_kernel<__bf16>), grid, dim3(256), 0, st, t);
+    else hipLaunchKernelGGL((repack_parts_kernel<float>), grid, dim3(256), 0, st, t);
+    return hipGetLastError();
 }
 
 }  // namespace lora

@@ -784,6 +784,85 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
     return LORA_OK;
 }
 
+int lora_cache_fill_slot_parts(lora_cache_t *c, int32_t slot, int64_t adapter_id, int32_t rank, float alpha,
+                               const lora_fill_part_t *parts, int32_t n_parts, void *fill_stream)
+{
+    if (!c || slot < 0 || slot >= c->n_slots || rank < 1 || n_parts < 0 || (n_parts > 0 && !parts)) return LORA_E_INVAL;
+    Slot &s = c->slots[slot];
+    if (rank > c->class_rank[s.cls]) return LORA_E_INVAL;
+    bool direct = c->direct_fill && !c->host_only;
+    for (int32_t i = 0; i < n_parts; ++i) {
+        const lora_fill_part_t &q = parts[i];
+        if (q.layer < 0 || q.layer >= c->n_layers || q.proj < 0 || q.proj >= (int32_t)c->proj.size()) return LORA_E_INVAL;
+        if (!c->host_only && (!q.host_A || !q.host_B)) return LORA_E_INVAL;
+        if (s.bound && s.part[(size_t)q.layer * c->proj.size() + q.proj] && s.refcount > 0) return LORA_E_STATE;
+    }
+    if (s.bound) {
+        if (s.adapter_id != adapter_id || s.rank != rank || s.alpha != alpha) return LORA_E_STATE;
+    } else if (c->id2slot.find(adapter_id) != c->id2slot.end()) {
+        return LORA_E_STATE;
+    }
+    if (n_parts == 0) return LORA_OK;
+    // pinned host arrays as the device sees them (all parts, or the call takes the staged way)
+    std::vector<const void *> dev_view;
+    if (direct) {
+        dev_view.resize(2 * (size_t)n_parts);
+        for (int32_t i = 0; i < n_parts && direct; ++i) {
+            dev_view[2 * i] = device_view_of_pinned(parts[i].host_A);
+            dev_view[2 * i + 1] = device_view_of_pinned(parts[i].host_B);
+            if (!dev_view[2 * i] || !dev_view[2 * i + 1] ||
+                ((reinterpret_cast<uintptr_t>(dev_view[2 * i]) | reinterpret_cast<uintptr_t>(dev_view[2 * i + 1])) & 15))
+                direct = false;
+        }
+    }
+    if (!direct) {
+        for (int32_t i = 0; i < n_parts; ++i) {
+            const int rc = lora_cache_fill_slot(c, slot, adapter_id, rank, alpha, parts[i].layer, parts[i].proj, parts[i].host_A,
+                                                parts[i].host_B, fill_stream);
+            if (rc != LORA_OK) return rc;
+        }
+        return LORA_OK;
+    }
+    if (!s.bound) {
+        s.bound = true;
+        s.adapter_id = adapter_id;
+        s.rank = rank;
+        s.alpha = alpha;
+        s.use_count = 0;
+        ++s.generation;
+        c->id2slot[adapter_id] = slot;
+    }
+    hipStream_t st = static_cast<hipStream_t>(fill_stream);
+    if (c->fencing && s.last_used > 0) HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
+    for (int32_t i0 = 0; i0 < n_parts; i0 += lora::REPACK_MAX_PARTS) {
+        lora::RepackTable t;
+        t.n = std::min<int32_t>(lora::REPACK_MAX_PARTS, n_parts - i0);
+        for (int32_t i = 0; i < t.n; ++i) {
+            const lora_fill_part_t &q = parts[i0 + i];
+            t.p[i].A = dev_view[2 * (size_t)(i0 + i)];
+            t.p[i].B = dev_view[2 * (size_t)(i0 + i) + 1];
+            t.p[i].slab = slab_ptr(*c, q.layer, q.proj, slot);
+            t.p[i].h_in = c->proj[q.proj].h_in;
+            t.p[i].h_out = c->proj[q.proj].h_out;
+        }
+        HIP_TRY(lora::launch_repack_parts(c->dtype, t, rank, true, st));
+    }
+    if (!s.fill_ev) HIP_TRY(hipEventCreateWithFlags(&s.fill_ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(s.fill_ev, st));
+    s.fill_pending = true;
+    for (int32_t i = 0; i < n_parts; ++i) {
+        const lora_fill_part_t &q = parts[i];
+        const size_t part = (size_t)q.layer * c->proj.size() + q.proj;
+        if (!s.part[part]) {
+            s.part[part] = 1;
+            ++s.parts_filled;
+        }
+        ++c->stats.fills;
+        c->stats.bytes_filled += (int64_t)rank * (c->proj[q.proj].h_in + c->proj[q.proj].h_out) * c->esize;
+    }
+    return LORA_OK;
+}
+
 int lora_cache_release_slot(lora_cache_t *c, int32_t slot)
 {
     if (!c || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;

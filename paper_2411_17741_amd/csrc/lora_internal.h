@@ -116,5 +116,17 @@ hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem
 // sees it: from_host) -> slab layout
 hipError_t launch_repack(int dtype, const void *src_A, const void *src_B, void *slab, int32_t h_in, int32_t h_out,
                          int32_t rank, bool from_host, hipStream_t st);
+// the same for up to REPACK_MAX_PARTS parts of one adapter in one launch (unit_end, r, rs are set by the launcher)
+constexpr int REPACK_MAX_PARTS = 32;
+struct RepackPart {
+    const void *A, *B;
+    void *slab;
+    int32_t h_in, h_out, unit_end, pad;
+};
+struct RepackTable {
+    RepackPart p[REPACK_MAX_PARTS];
+    int32_t n, r, rs, pad;
+};
+hipError_t launch_repack_parts(int dtype, RepackTable &t, int32_t rank, bool from_host, hipStream_t st);
 
 }  // namespace lora

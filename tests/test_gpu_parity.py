@@ -303,7 +303,8 @@ def test_fill_paths_give_the_same_slabs():
     B, H = _mods()
     inst = _custom_instance([3, 20, 1, 70, 2, 5], [0, 1, 2, 3, 4, 5], [7, 16, 64, 128, 1, 100], h_in=320, h_out=448, seed=21)
     outs = []
-    for pinned, flags in ((True, 0), (False, 0), (True, B.LORA_CACHE_DIRECT_FILL)):
+    for pinned, flags, whole in ((True, 0, False), (False, 0, False), (True, B.LORA_CACHE_DIRECT_FILL, False),
+                                 (True, B.LORA_CACHE_DIRECT_FILL, True), (True, 0, True), (False, B.LORA_CACHE_DIRECT_FILL, True)):
         pi = H.PooledInstance(inst, adapters=[], mfma_min_tokens=16, flags=flags)
         try:
             keep = []
@@ -314,6 +315,11 @@ def test_fill_paths_give_the_same_slabs():
                     ta, tb = ta.pin_memory(), tb.pin_memory()
                 assert ta.is_pinned() == pinned
                 keep += [ta, tb]
+                if whole:  # the adapter's parts in one call (here it has one)
+                    B.check(B.lora_cache_fill_slot_parts(pi.pool.handle, int(pi.slot_of[a]), int(inst.adapter_ids[a]), int(inst.ranks[a]),
+                                                         float(inst.alpha[a]), B.make_fill_parts([(0, 0, ta.data_ptr(), tb.data_ptr())]),
+                                                         torch.cuda.current_stream().cuda_stream))
+                    continue
                 pi.pool.fill(int(pi.slot_of[a]), int(inst.adapter_ids[a]), int(inst.ranks[a]), float(inst.alpha[a]), 0, 0, ta, tb, pin=False)
             torch.cuda.synchronize()
             pi.pool.fills_done()
@@ -324,9 +330,48 @@ def test_fill_paths_give_the_same_slabs():
             outs.append(yd.float().cpu().numpy())
         finally:
             pi.close()
-    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
     ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, _oracle_adapters(inst, 0, inst.used_adapters()), inst.scale)
     _check(H.error_metrics(outs[0], ref, base), "bf16", "fill paths")
+
+
+def test_whole_adapter_fill_in_one_call():
+    """All (layer, projection) parts of an adapter handed over in one lora_cache_fill_slot_parts call, read
+    from pinned host memory by one kernel per 32 parts: 21 layers x 2 projections of different shapes (42
+    parts, so two launches).  Every layer copy must then give the results of part-by-part fills."""
+    B, H = _mods()
+    inst = wl.small_mixed(seed=13)
+    n_layers = 21
+    ref_pi = H.PooledInstance(inst, n_layers=1)
+    pi = H.PooledInstance(inst, n_layers=n_layers, adapters=[], flags=B.LORA_CACHE_DIRECT_FILL)
+    try:
+        keep = []
+        for a in inst.used_adapters():
+            a = int(a)
+            host = []
+            for p in range(len(inst.projs)):
+                A, Bm = inst.adapter_weights(a, p)
+                host.append((torch.from_numpy(A).to(torch.bfloat16).pin_memory(), torch.from_numpy(Bm).to(torch.bfloat16).pin_memory()))
+            keep += host
+            parts = B.make_fill_parts([(l, p, host[p][0].data_ptr(), host[p][1].data_ptr()) for l in range(n_layers) for p in range(len(inst.projs))])
+            B.check(B.lora_cache_fill_slot_parts(pi.pool.handle, int(pi.slot_of[a]), int(inst.adapter_ids[a]), int(inst.ranks[a]),
+                                                 float(inst.alpha[a]), parts, torch.cuda.current_stream().cuda_stream))
+            rc, info = B.lora_cache_slot_info(pi.pool.handle, int(pi.slot_of[a]))
+            assert info.parts_filled == n_layers * len(inst.projs)
+        torch.cuda.synchronize()
+        for p in range(len(inst.projs)):
+            x, base = inst.x(p), inst.base_out(p)
+            xd, want = H.to_device(x, pi.dtype), H.to_device(base, pi.dtype)
+            ref_pi.apply(0, p, xd, want)
+            ref_pi.pool.check_fault()
+            for layer in (0, 7, n_layers - 1):
+                yd = H.to_device(base, pi.dtype)
+                pi.apply(layer, p, xd, yd)
+                pi.pool.check_fault()
+                assert torch.equal(yd, want), f"projection {p}, layer copy {layer}"
+    finally:
+        pi.close()
+        ref_pi.close()
 
 
 def test_multi_apply_groups_projections_that_share_their_input():

@@ -166,6 +166,34 @@ def test_slot_table_state_machine():
     assert B.lora_cache_destroy(h) == B.LORA_OK
 
 
+def test_fill_of_several_parts_in_one_call():
+    """lora_cache_fill_slot_parts: the slot table moves as if the parts had come one by one; a call with a
+    bad part changes nothing."""
+    h = _host_cache()
+    st = lambda s: B.lora_cache_slot_info(h, s)[1]
+    parts = B.make_fill_parts([(0, 0, 0, 0), (0, 1, 0, 0), (1, 0, 0, 0)])
+    assert B.lora_cache_fill_slot_parts(h, 2, 77, 16, 0.5, parts) == B.LORA_OK
+    assert (st(2).parts_filled, st(2).state, st(2).adapter_id, st(2).rank) == (3, B.LORA_SLOT_FILLING, 77, 16)
+    assert B.lora_cache_fill_slot_parts(h, 2, 77, 16, 0.5, B.make_fill_parts([(1, 1, 0, 0)])) == B.LORA_OK
+    assert st(2).state == B.LORA_SLOT_READY
+    assert B.lora_cache_lookup(h, 77) == (B.LORA_OK, 2, 16)
+    # errors leave the slot as it was
+    assert B.lora_cache_fill_slot_parts(h, 0, 5, 8, 1.0, B.make_fill_parts([(0, 0, 0, 0), (2, 0, 0, 0)])) == B.LORA_E_INVAL  # layer
+    assert B.lora_cache_fill_slot_parts(h, 0, 5, 8, 1.0, B.make_fill_parts([(0, 0, 0, 0), (0, 2, 0, 0)])) == B.LORA_E_INVAL  # projection
+    assert st(0).state == B.LORA_SLOT_EMPTY and B.lora_cache_lookup(h, 5)[0] == B.LORA_E_NOTFOUND
+    assert B.lora_cache_fill_slot_parts(h, 0, 5, 16, 1.0, parts) == B.LORA_E_INVAL       # rank above the slot's class
+    assert B.lora_cache_fill_slot_parts(h, 0, 77, 8, 0.5, parts) == B.LORA_E_STATE      # cached elsewhere
+    assert B.lora_cache_fill_slot_parts(h, 2, 78, 16, 0.5, parts) == B.LORA_E_STATE     # bound to another adapter
+    assert B.lora_cache_slot_ref(h, 2, +1) == B.LORA_OK
+    assert B.lora_cache_fill_slot_parts(h, 2, 77, 16, 0.5, parts) == B.LORA_E_STATE     # in use and complete
+    assert B.lora_cache_slot_ref(h, 2, -1) == B.LORA_OK
+    assert B.lora_cache_fill_slot_parts(h, 2, 77, 16, 0.5, parts) == B.LORA_OK
+    assert B.lora_cache_fill_slot_parts(h, 0, 5, 8, 1.0, B.make_fill_parts([])) == B.LORA_OK and st(0).state == B.LORA_SLOT_EMPTY
+    rc, stats = B.lora_cache_stats(h)
+    assert stats.fills == 7
+    assert B.lora_cache_destroy(h) == B.LORA_OK
+
+
 def test_plan_validation_against_slot_table():
     h = _host_cache(n_layers=1, n_proj=1)
     assert B.lora_cache_fill_slot(h, 0, 5, 8, 1.0, 0, 0, 0, 0) == B.LORA_OK
