@@ -279,6 +279,174 @@ def prefetch_sweep(args) -> int:
 
 
 
+def serve_replay(args) -> int:
+    """Scheduler, cache manager, loads and applies together (paper sections 4.2-4.3) on Poisson arrivals:
+    every iteration the new requests are submitted, the scheduler forms the batch (lora_sched_generate_batch),
+    the adapters of the admitted requests are acquired (a miss is loaded whole from pinned host memory on a
+    side stream), the adapters of waiting requests are prefetched, and the batch -- the prompts of the new
+    requests, one token of every other running request -- goes through the apply of every projection and
+    layer.  Inputs are synthetic: prompt lengths lognormal(6, 0.8) in [32, 2048], output lengths
+    lognormal(3.5, 0.8) in [1, 256], the paper's adapter population.  The time to first token of a request
+    is taken from the start of its arrival's iteration to the end of the iteration that ran its prompt.
+    Run once with the queues fitted to the request sizes and once with a single queue.  Host-inclusive:
+    the loop is Python calling the C ABI, synchronised every iteration.  One JSON line."""
+    import torch
+    from paper_2411_17741_amd import binding as B
+    from paper_2411_17741_amd.pool import LoraPool
+
+    n_a, n_layers = args.adapters if args.adapters != 100 else 200, args.layers or 4
+    ranks = [8, 16, 32, 64, 128]
+    per_rank = n_a // 5
+    slots_per_rank = args.slots_per_rank or (3 * per_rank) // 4
+    projs = [(4096, 4096)] * 4
+    n_iter, warm = args.steps or 300, 40
+    rate, total_tokens, max_batch_tokens = args.arrivals, args.token_budget, 32768
+    rng = np.random.default_rng(11)
+    w = 1.0 / np.arange(1, per_rank + 1) ** 1.2
+    cdf = np.cumsum(w / w.sum())
+    perm = [rng.permutation(per_rank) for _ in ranks]
+    arrivals = []  # per iteration: [(input, output, adapter)]
+    for _ in range(n_iter + warm):
+        reqs = []
+        for _ in range(int(rng.poisson(rate))):
+            c = int(rng.integers(0, 5))
+            k = int(min(np.searchsorted(cdf, rng.random()), per_rank - 1))
+            reqs.append((int(np.clip(rng.lognormal(6.0, 0.8), 32, 2048)), int(np.clip(rng.lognormal(3.5, 0.8), 1, 256)), c * per_rank + int(perm[c][k])))
+        arrivals.append(reqs)
+    flat = [r for it in arrivals for r in it]
+    sizes = [B.lora_sched_wrs(i, o, ranks[a // per_rank], 2048, 256, 128) for i, o, a in flat]
+
+    dev = torch.device("cuda:0")
+    part_bytes = {r: 2 * 4096 * r * 2 for r in ranks}
+    adapter_bytes = [n_layers * 4 * part_bytes[ranks[a // per_rank]] for a in range(n_a)]
+    arena = torch.empty(sum(adapter_bytes), dtype=torch.uint8, pin_memory=True)
+    arena.view(torch.int16)[:] = 0x3c00
+    parts_c, off = [], arena.data_ptr()
+    for a in range(n_a):
+        r, entries = ranks[a // per_rank], []
+        for l in range(n_layers):
+            for p in range(4):
+                entries.append((l, p, off, off + part_bytes[r] // 2))
+                off += part_bytes[r]
+        parts_c.append(B.make_fill_parts(entries))
+    x = torch.zeros((max_batch_tokens, 4096), device=dev, dtype=torch.bfloat16)
+    y = torch.zeros((max_batch_tokens, 4096), device=dev, dtype=torch.bfloat16)
+    stream, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    sh = stream.cuda_stream
+
+    def run(k_max):
+        rc, K, bounds = B.lora_sched_fit_queues(sizes, k_max)
+        B.check(rc, "fit_queues")
+        q_of = np.searchsorted(np.asarray(bounds), np.asarray(sizes), side="right") if bounds else np.zeros(len(sizes), int)
+        need = np.asarray([i + o + ranks[a // per_rank] for i, o, a in flat])
+        least = [int(need[q_of == q].max()) if (q_of == q).any() else 0 for q in range(K)]
+        weights = [float(need[q_of == q].sum()) + 1.0 for q in range(K)]   # tokens the queue's requests ask for
+        rc, quotas = B.lora_sched_assign_quotas(total_tokens, least, weights)
+        B.check(rc, "assign_quotas")
+        rc, sched = B.lora_sched_create(quotas, bounds, 2048, 256, 128, 1)
+        B.check(rc, "sched_create")
+        pool = LoraPool(projs, n_layers, ranks, [slots_per_rank] * 5, B.LORA_BF16, max_tokens=max_batch_tokens, max_segments=4096, n_plans=2,
+                        flags=B.LORA_CACHE_DIRECT_FILL)
+        h = pool.handle
+        B.check(B.lora_cache_set_fencing(h, 1))
+        descs = B.make_descs([(l, p, x.data_ptr(), y.data_ptr()) for l in range(n_layers) for p in range(4)])
+        info, running = {}, {}   # request id -> (input, output, adapter, arrival time); -> [slot, outputs left, prompt pending]
+        ttft, ttft_small, batch_tokens, refused = [], [], [], 0
+        rid = 0
+        small_cut = float(np.median(sizes))
+        torch.cuda.synchronize()
+        t_begin = None
+        tokens_done = 0
+        for it in range(n_iter + warm):
+            if it == warm:
+                t_begin = time.perf_counter()
+                ttft, ttft_small, batch_tokens, tokens_done = [], [], [], 0
+                B.lora_cache_stats(h)
+            t_it = time.perf_counter()
+            for (i, o, a) in arrivals[it]:
+                B.check(B.lora_sched_submit(sched, rid, i, o, 1000 + a, ranks[a // per_rank])[0], "submit")
+                info[rid] = (i, o, a, t_it)
+                rid += 1
+            rc, batch = B.lora_sched_generate_batch(sched)
+            B.check(rc, "generate_batch")
+            rc, queued = B.lora_sched_waiting_adapters(sched)
+            queued_np = np.asarray(queued, np.int64) if queued else None
+            fresh = []
+            for r in batch:
+                i, o, a, t_arr = info[r]
+                rc, slot, hit = B.lora_cache_acquire(h, 1000 + a, ranks[a // per_rank], 1.0, True, queued_np)
+                if rc == B.LORA_E_NOMEM:   # every slot that fits is held by running requests: the request gives its tokens back
+                    B.check(B.lora_sched_finish(sched, r))
+                    refused += 1
+                    continue
+                B.check(rc, "acquire")
+                if not hit:
+                    B.check(B.lora_cache_fill_slot_parts(h, slot, 1000 + a, ranks[a // per_rank], 1.0, parts_c[a], side.cuda_stream), "fill")
+                running[r] = [slot, o, i]
+                fresh.append(r)
+            for aid in (queued[:args.prefetch] if queued else []):   # the adapters of the requests at the head of the queues
+                a = aid - 1000
+                rc, slot, hit = B.lora_cache_acquire(h, aid, ranks[a // per_rank], 1.0, False, queued_np)
+                if rc == B.LORA_OK and not hit:
+                    B.check(B.lora_cache_fill_slot_parts(h, slot, aid, ranks[a // per_rank], 1.0, parts_c[a], side.cuda_stream), "fill")
+            if running:
+                lens = [st[2] if st[2] else 1 for st in running.values()]
+                T = int(sum(lens))
+                if T > max_batch_tokens:
+                    raise RuntimeError(f"batch of {T} tokens exceeds the {max_batch_tokens} the run allows for")
+                seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+                seg_slot = np.asarray([st[0] for st in running.values()], np.int32)
+                seg_rank = np.asarray([ranks[info[r][2] // per_rank] for r in running], np.int32)
+                rc, plan = B.lora_plan_create(h, T, seg_off, seg_slot, seg_rank, sh)
+                B.check(rc, "lora_plan_create")
+                B.check(B.lora_apply_plan_multi(h, plan, descs, 2.0, sh), "lora_apply_plan_multi")
+                B.check(B.lora_plan_destroy(h, plan))
+                stream.synchronize()
+                tokens_done += T
+                batch_tokens.append(T)
+            t_end = time.perf_counter()
+            for r in fresh:
+                d = (t_end - info[r][3]) * 1e3
+                ttft.append(d)
+                if sizes[r] < small_cut:
+                    ttft_small.append(d)
+            for r in list(running):
+                st = running[r]
+                st[2] = 0
+                st[1] -= 1
+                if st[1] <= 0:
+                    B.check(B.lora_sched_finish(sched, r))
+                    B.check(B.lora_cache_slot_ref(h, st[0], -1))
+                    del running[r]
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_begin
+        pool.check_fault()
+        rc, stats = B.lora_cache_stats(h)
+        waiting = sum(B.lora_sched_queue_state(sched, q)[2] for q in range(K))
+        B.lora_sched_destroy(sched)
+        pool.close()
+        pct = lambda v, p: float(np.percentile(v, p)) if len(v) else None
+        return {"queues": K, "boundaries": bounds, "quotas": quotas, "ms_per_iteration": elapsed * 1e3 / n_iter,
+                "tokens_per_s_per_layer": tokens_done / elapsed, "mean_batch_tokens": float(np.mean(batch_tokens)) if batch_tokens else 0.0,
+                "ttft_ms": {"p50": pct(ttft, 50), "p99": pct(ttft, 99)}, "ttft_ms_smaller_half": {"p50": pct(ttft_small, 50), "p99": pct(ttft_small, 99)},
+                "requests_admitted": len(ttft), "requests_refused": refused, "requests_still_waiting": waiting,
+                "cache": {"hits": int(stats.hits), "misses": int(stats.misses), "evictions": int(stats.evictions), "loaded_MB": stats.bytes_filled / 1e6}}
+
+    fitted = run(4)
+    single = run(1)
+    print(json.dumps({
+        "metric": "lora_apply_tokens_per_s_per_layer", "value": fitted["tokens_per_s_per_layer"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": n_iter, "warmup": warm, "ms_per_step": fitted["ms_per_iteration"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"serving replay: Poisson({rate}) requests per iteration, prompts lognormal(6,0.8) in [32,2048], outputs lognormal(3.5,0.8) in [1,256], "
+                               f"{n_a} adapters (N_a/5 per rank 8..128, power law 1.2 within the rank), pool of {slots_per_rank} slots per rank, "
+                               f"q,k,v,o 4096->4096 bf16, {n_layers} layers, token budget {total_tokens}, prefetch of {args.prefetch} waiting adapters; host-inclusive",
+                   "layers_per_step": n_layers},
+        "queues_fitted": fitted, "single_queue": single, "roofline": None, "cpu_baseline": None}))
+    return 0
+
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +464,11 @@ def main() -> int:
                     "random base weights) instead of the apply on a given base output; prints its own JSON line")
     ap.add_argument("--prefetch-depths", default="", help="e.g. 0,1,2,4: run the queue-driven prefetch experiment instead (own JSON line); "
                     "uses --tokens (default 256), --adapters (default 200), --layers (default 8), --slots-per-rank, --direct-fill, --fill-by-part")
+    ap.add_argument("--serve", action="store_true", help="replay Poisson arrivals through scheduler, cache manager, loads and applies (own JSON line); "
+                    "uses --arrivals, --token-budget, --prefetch, --adapters (default 200), --layers (default 4), --slots-per-rank, --steps (iterations)")
+    ap.add_argument("--arrivals", type=float, default=1.0, help="--serve: mean requests arriving per iteration")
+    ap.add_argument("--token-budget", type=int, default=65536, help="--serve: tokens the scheduler's queues share")
+    ap.add_argument("--prefetch", type=int, default=8, help="--serve: adapters of waiting requests prefetched per iteration")
     ap.add_argument("--fill-by-part", action="store_true", help="prefetch experiment: one lora_cache_fill_slot call per (layer, projection) "
                     "instead of one lora_cache_fill_slot_parts call per adapter")
     ap.add_argument("--slots-per-rank", type=int, default=0, help="prefetch experiment: pool slots per rank class (default: all but 3 of the 40 adapters of a rank)")
@@ -317,6 +490,8 @@ def main() -> int:
 
     if args.prefetch_depths:
         return prefetch_sweep(args)
+    if args.serve:
+        return serve_replay(args)
     steps = args.steps or DEFAULT_STEPS[args.workload]
     n_layers = args.layers or DEFAULT_LAYERS[args.workload]
     if args.workload == "decode_paper":
