@@ -4,7 +4,8 @@
 // Variants: stages written to LDS by the load itself or through registers, with and without a barrier per stage,
 // requested one stage ahead, and the same beside 32 matrix-core products per wavefront and stage (operands from
 // registers, or read from LDS as the kernel reads them), and the products alone; and a schedule in which
-// the two wavefronts of a SIMD alternate between (operand reads + load requests) and products, a barrier between the phases.
+// the two wavefronts of a SIMD alternate between (operand reads + load requests) and products, a barrier between the phases;
+// and four wavefronts of 128 x 128 (one per SIMD) instead of eight of 128 x 64.
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 stagebench.hip -o stagebench && ./stagebench
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -219,6 +220,59 @@ __global__ __launch_bounds__(512) void stage_kernel(const unsigned short *__rest
     }
     if ((acc.x ^ acc.y) == 0x12345678u) sink[blockIdx.x * 512 + tid] = acc;
 }
+
+// four wavefronts, each 128 x 128 of the 256 x 256 block (one per SIMD, 256 accumulator registers)
+__global__ __launch_bounds__(256) void stage_kernel_4w(const unsigned short *__restrict__ x, const unsigned short *__restrict__ wt, int n_mt, uint4 *sink)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bm = blockIdx.x % n_mt, bn = blockIdx.x / n_mt;
+    const int lr = lane >> 3, ls = lane & 7;
+    const unsigned short *xg = x + (size_t)(256 * bm + 64 * w + lr) * H + ls * 8;
+    const unsigned short *wg = wt + (size_t)(256 * bn + 64 * w + lr) * H + ls * 8;
+    auto load = [&](int kt, int buf) {
+        unsigned char *sa = lds + buf * STAGE + 64 * w * 128;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            __builtin_amdgcn_global_load_lds(xg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            __builtin_amdgcn_global_load_lds(wg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + 32768 + q * 1024), 16, 0, 0);
+    };
+    floatx16 c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c[i][e] = 0.f;
+    for (int i = tid; i < 2 * STAGE / 16; i += 256) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(tid, i, 3, 4);
+    __syncthreads();
+    load(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    const int m = lane & 31, hh = lane >> 5, swz = (m >> 1) & 7;
+    const int rh = w & 1, ch = w >> 1;
+    for (int kt = 0; kt < NK; ++kt) {
+        load(min(kt + 1, NK - 1), (kt + 1) & 1);
+        const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * rh + m) * 128;
+        const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (128 * ch + m) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 ao[4], bo[4];
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) c[4 * mb + nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[mb], bo[nb], c[4 * mb + nb], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    unsigned accx = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) accx ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
+    if (accx == 0x12345678u) sink[blockIdx.x * 256 + tid] = make_uint4(accx, 0, 0, 0);
+}
 template <int MODE> int run(const char *name, const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
 {
     CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
@@ -237,6 +291,24 @@ template <int MODE> int run(const char *name, const unsigned short *x, const uns
     fflush(stdout);
     return 0;
 }
+
+int run4(const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
+{
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel_4w), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(stage_kernel_4w, dim3(n_mt * n_nt), dim3(256), 2 * STAGE, 0, x, wt, n_mt, sink);
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    const int reps = 21;
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(stage_kernel_4w, dim3(n_mt * n_nt), dim3(256), 2 * STAGE, 0, x + (size_t)(i % 3) * n_mt * 256 * H, wt + (size_t)(i % 3) * n_nt * 256 * H, n_mt, sink);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+    printf("%-44s %8.1f us\n", "4 wavefronts of 128x128: loads + reads + MFMA", ms * 1e3 / reps);
+    fflush(stdout);
+    return 0;
+}
 int main()
 {
     const int n_mt = 23, n_nt = 16;
@@ -250,6 +322,7 @@ int main()
     if (run<8>("LDS-direct ahead + 24 LDS reads + 32 MFMA/stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<9>("24 LDS reads + 32 MFMA/stage, no loads", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<10>("alternating wavefronts: reads+loads | MFMA", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run4(x, wt, sink, n_mt, n_nt)) return 1;
     if (run<1>("registers + ds_write, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<4>("registers only, no barrier", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<5>("registers only, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
