@@ -6,26 +6,28 @@
 // disappears.  This is the variant of the hot path whose roof is the matrix cores, not HBM.
 //
 // Block = 8 wavefronts on 256 rows (four row tiles) x 256 output columns; wavefront w owns the row
-// half w%2 and the column quarter w/2: 4 x 2 products of 32 x 32 (v_mfma_f32_32x32x16_bf16: 8 x 16
-// accumulator registers).  Two wavefronts per SIMD: with one (4 x 4 products each) every wait -- the
-// barrier of a stage, the first operand reads after it -- idles the matrix core (measured: 0.68
-// against 1.1 PFLOP/s).  x rows (gathered by token) and Wt rows (Wt[n][k] = W[k][n], the layout a
-// linear layer keeps its weight in) are both contiguous along k: every stage brings 64 k of both
-// into LDS, double-buffered, one barrier per stage, by global_load_lds_dwordx4 -- the load writes
+// half w%2 and the column quarter w/2: 8 x 4 products of 16 x 16 (v_mfma_f32_16x16x32_bf16, 128
+// accumulator registers).  The 32x32x16 form of the product has the higher peak rate, but beside the
+// stage loads it is the slower one: the k loop of this kernel as a microbenchmark takes 197 us with it
+// and 173 us with the 16x16x32 form on the prefill shape (loads alone 120 us, products alone 120 us).
+// Two wavefronts per SIMD: with one, every wait -- the barrier of a stage, the first operand reads
+// after it -- idles the matrix core.  x rows (gathered by token) and Wt rows (Wt[n][k] = W[k][n], the
+// layout a linear layer keeps its weight in) are both contiguous along k: every stage brings 64 k of
+// both into LDS, double-buffered, one barrier per stage, by global_load_lds_dwordx4 -- the load writes
 // LDS itself (at the wavefront's base + 16 bytes x lane; checked on the part), so no registers stage
-// the data (with 256 accumulator registers per lane, 64 more for staging made the compiler spill
-// them).  LDS rows are 128 bytes without padding; bank conflicts are avoided by a swizzle instead:
-// 16-byte slot s of row r holds piece s ^ ((r/2) % 8) of the row's 64 k, so the 16 rows an operand
-// read touches at once fall into 16 different bank groups.  Per 16-wide k step a wavefront reads
-// 4 + 2 operands from LDS for 8 products.
-// Operand layout of the instruction: A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7;
-// B (16 x 32): lane l holds column l%32, same k; D: lane l holds column l%32, rows 8*(i/4) + 4*(l/32) + i%4.
+// the data (loads that return into registers while products run took more than twice as long).
+// LDS rows are 128 bytes without padding; bank conflicts are avoided by a swizzle instead: 16-byte
+// slot s of row r holds piece s ^ ((r/2) % 8) of the row's 64 k, so the 16 rows an operand read
+// touches at once fall into 16 different bank groups.  Per 32-wide k step a wavefront reads 8 + 4
+// operands from LDS for 32 products.
+// Operand layout of the instruction: A (16 x 32): lane l holds row l%16, k = 8*(l/16) .. +7;
+// B (32 x 16): lane l holds column l%16, same k; D: lane l holds column l%16, rows 4*(l/16) .. +3.
 // The products are formed transposed -- the W block is the row operand, the x block the column
-// operand -- so that a lane's four consecutive accumulator registers are four consecutive output
-// columns of one token: 8 bytes of bf16, parked in LDS and stored from there in whole 128-byte lines.
+// operand -- so that a lane's four accumulator registers are four consecutive output columns of one
+// token: 8 bytes of bf16, parked in LDS and stored from there in whole 128-byte lines.
 // After the k loop the scaled intermediate s.v of the block's rows is staged in LDS as bf16 and every
 // wavefront adds, per row tile, the products with that tile's Bp, whose rank-packed layout gives the
-// B operand directly from global memory (32 lanes read 512 contiguous bytes).
+// row operand directly from global memory (a lane's 8 ranks are 16 contiguous bytes).
 // Tokens on the GEMV path sit in row tiles without an adapter; their adapter term is computed by the
 // GEMV kernels beforehand into the (zeroed) output rows, and this kernel adds it to the accumulators of
 // those rows before the one rounding of the stored value (row tiles marked a = 1).
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // two stages
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m = lane & 31, h = lane >> 5;
+    const int m = lane & 15, g = lane >> 4;
     const int rh = w & 1, cq = w >> 1;
     const int bm = (int)blockIdx.x % n_mt, bn = (int)blockIdx.x / n_mt;
     const int n0 = bn * LBN;
@@ -111,18 +113,18 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
                                              (__attribute__((address_space(3))) void *)(sa + L_A + q * 8 * LROW), 16, 0, 0);
     };
 
-    floatx16 acc[4][2];
+    floatx4 acc[8][4];  // [block of 16 rows][block of 16 columns]
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < 8; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[mb][nb][e] = 0.f;
 
     load_stage(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    // operand reads: row R, k piece 2ks + h sits in slot (2ks + h) ^ ((R/2) % 8); R/2 % 8 = (m/2) % 8 for all of a lane's rows
+    // operand reads: row R, k piece 4ks + g sits in slot (4ks + g) ^ ((R/2) % 8); R/2 % 8 = m/2 for all of a lane's rows
     const int swz = (m >> 1) & 7;
     for (int kt = 0; kt < n_k; ++kt) {
         // the next stage is requested before this one is multiplied, into the buffer that was read
@@ -130,43 +132,46 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         load_stage(min(kt + 1, n_k - 1), (kt + 1) & 1);
         const unsigned char *sa = lds + (kt & 1) * L_STAGE + (128 * rh + m) * LROW;
         const unsigned char *sb = lds + (kt & 1) * L_STAGE + L_A + (64 * cq + m) * LROW;
-        // operands of k step ks+1 are read while the products of k step ks run; the fences keep the
-        // compiler from pulling all 32 operand reads of the stage to the front (it then spills the
-        // staging registers)
-        bf16x8 aop[2][4], bop[2][2];
-        auto read_ops = [&](int ks, bf16x8(&ao)[4], bf16x8(&bo)[2]) {
+        // (The compiler's own order -- operand reads in twos and fours between groups of eight products -- is
+        // as fast as reading the operands of every group one group ahead by hand.)
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * LROW + (((2 * ks + h) ^ swz) << 4));
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 xo[8], wo[4];
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * LROW + (((2 * ks + h) ^ swz) << 4));
-        };
-        read_ops(0, aop[0], bop[0]);
+            for (int nb = 0; nb < 4; ++nb) wo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 16 * LROW + (((4 * ks + g) ^ swz) << 4));
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            // half of the step's products, then the operand reads of the next step, then the other half:
-            // the reads have four products' time to complete before the wait that precedes their use
-            // (the wait counts all LDS reads in flight; and left alone, the compiler sinks the reads
-            // below the products that free their registers)
+            for (int mb = 0; mb < 8; ++mb) xo[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 16 * LROW + (((4 * ks + g) ^ swz) << 4));
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < 8; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[ks & 1][nb], aop[ks & 1][mb], acc[mb][nb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ks < 3) read_ops(ks + 1, aop[(ks + 1) & 1], bop[(ks + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int mb = 2; mb < 4; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[ks & 1][nb], aop[ks & 1][mb], acc[mb][nb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wo[nb], xo[mb], acc[mb][nb], 0, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's part of the next stage has landed
         __syncthreads();
     }
 
-    // ---- the adapter slab: s.v of the block's rows to LDS as bf16 (zero past a tile's rank or end) ----
+    // ---- the adapter slab.  Bp operands of a row tile: granule 4ks + g (the 8 ranks a lane's operand holds,
+    // contiguous per column; past the stored rank the last granule, which meets zeros of s.v), all four k
+    // steps requested at once -- and for the wavefront's first tile before s.v is staged, so that the
+    // requests fly while the staging waits for its own loads.
+    auto bp_of = [&](const DevItem &t) {
+        return reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)t.row * a.row_bytes) + (size_t)rank_storage(t.rank) * a.h_in;
+    };
+    auto load_bp = [&](const DevItem &t, bf16x8(&bo)[4][4]) {
+        const int rs8 = rank_storage(max(t.rank, 1)) >> 3;
+        const __bf16 *Bp = bp_of(t);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const int col = min(n0 + 64 * cq + 16 * nb + m, a.h_out - 1);
+                bo[ks][nb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Bp + ((size_t)min(4 * ks + g, rs8 - 1) * a.h_out + col) * 8));
+            }
+    };
+    const bool live0 = mine0.rank != 0 && mine0.n_tok != 0, live1 = mine1.rank != 0 && mine1.n_tok != 0;  // wavefront-uniform
+    bf16x8 bo[4][4];
+    if (live0) load_bp(mine0, bo);
+    // s.v of the block's rows to LDS as bf16 (zero past a tile's rank or end)
     unsigned char *sv = lds;
     {
         // chunk tid%16 (8 ranks) of rows tid/16 + 32*j: row tile j/2, row (tid/16 + 32*(j%2)) of it
@@ -175,8 +180,8 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         for (int j = 0; j < 8; ++j) {
             const DevItem &t = tile_of(j >> 1);
             const int ti = r0 + 32 * (j & 1);
-            const int ks16 = (t.rank + 15) >> 4;  // k steps this tile's products will read
-            if (c8 < 2 * ks16) {
+            const int ks32 = (t.rank + 31) >> 5;  // k steps this tile's products will read
+            if (c8 < 4 * ks32) {
                 bf16x8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
@@ -197,37 +202,33 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl) {
         const DevItem &t = tl ? mine1 : mine0;
-        if (t.rank == 0 || t.n_tok == 0) continue;  // wavefront-uniform
-        const int rs8 = rank_storage(t.rank) >> 3, ks16 = (t.rank + 15) >> 4;
-        const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)t.row * a.row_bytes) + (size_t)(rs8 * 8) * a.h_in;
-        const unsigned char *svr = sv + (128 * rh + 64 * tl + m) * SV_ROW + h * 16;
-        for (int ks = 0; ks < ks16; ++ks) {
-            const __bf16 *bg = Bp + (size_t)min(2 * ks + h, rs8 - 1) * a.h_out * 8;
-            bf16x8 bop[2];
+        if (!(tl ? live1 : live0)) continue;
+        if (tl == 1) load_bp(mine1, bo);
+        const int ks32 = (t.rank + 31) >> 5;
+        const unsigned char *svr = sv + (128 * rh + 64 * tl + m) * SV_ROW + g * 16;
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int col = min(n0 + 64 * cq + 32 * nb + m, a.h_out - 1);
-                bop[nb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bg + (size_t)col * 8));
-            }
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < ks32) {
 #pragma unroll
-            for (int mbl = 0; mbl < 2; ++mbl) {
-                const bf16x8 aop = *reinterpret_cast<const bf16x8 *>(svr + mbl * 32 * SV_ROW + ks * 32);
+                for (int mbl = 0; mbl < 4; ++mbl) {
+                    const bf16x8 xo = *reinterpret_cast<const bf16x8 *>(svr + mbl * 16 * SV_ROW + ks * 64);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[2 * tl + mbl][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[nb], aop, acc[2 * tl + mbl][nb], 0, 0, 0);
+                    for (int nb = 0; nb < 4; ++nb)
+                        acc[4 * tl + mbl][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bo[ks][nb], xo, acc[4 * tl + mbl][nb], 0, 0, 0);
+                }
             }
         }
     }
 
     // ---- store.  The products are formed transposed (the W block is the instruction's row operand, the x
-    // block its column operand): lane (m, h) holds, in registers 4g .. 4g+3 of block (mb, nb), row 32*mb + m of
-    // the wavefront's 128 and the four consecutive columns 32*nb + 8g + 4h .. of its 64 -- 8 bytes of bf16.
-    // The wavefront parks its 128 x 64 outputs in LDS and stores whole 128-byte row pieces, 8 rows per
-    // instruction (stored from the registers, an instruction would write 16 bytes to each of 32 rows).
-    // Park layout, free of bank conflicts both ways: row r is 128 bytes, its 16-byte slot s sits at
-    // s ^ ((r/2) % 8), and the two 8-byte halves of a slot are swapped in rows with (r/16) % 2 = 1.
-    // Row tiles whose rows already hold the adapter term (GEMV tokens) are few and go straight from the
-    // registers, the sum formed in fp32 before the one rounding.
+    // block its column operand): lane (m, g) holds, in the four registers of block (mb, nb), row 16*mb + m of the
+    // wavefront's 128 and the four consecutive columns 16*nb + 4g .. of its 64 -- 8 bytes of bf16.  The
+    // wavefront parks its 128 x 64 outputs in LDS and stores whole 128-byte row pieces, 8 rows per
+    // instruction (stored from the registers, an instruction would write 32 bytes to each of 16 rows).
+    // Park layout, free of bank conflicts both ways: row r is 128 bytes, its 8-byte cell c sits at
+    // c ^ (2 * ((r/2) % 8)), i.e. its 16-byte slot s at s ^ ((r/2) % 8).  Row tiles whose rows already hold
+    // the adapter term (GEMV tokens) are few and go straight from the registers, the sum formed in fp32
+    // before the one rounding.
     __syncthreads();  // every wavefront is done with the staged s.v
     unsigned char *park = lds + w * (128 * 128);
     const bool cols_live = n0 + 64 * cq < a.h_out;  // h_out is a multiple of 64
@@ -238,33 +239,30 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         if (t.n_tok == 0 || !cols_live) continue;  // wavefront-uniform
         const bool add_y = t.rank == 0 && t.a == 1;
 #pragma unroll
-        for (int mbl = 0; mbl < 2; ++mbl) {
-            const int ti = 32 * mbl + m, row = 64 * tl + ti;
+        for (int mbl = 0; mbl < 4; ++mbl) {
+            const int ti = 16 * mbl + m, row = 64 * tl + ti;
             __bf16 *yr = nullptr;
-            if (add_y && ti < t.n_tok) yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 4 * h;
-            unsigned char *pr = park + row * 128 + ((h ^ ((row >> 4) & 1)) << 3);
+            if (add_y && ti < t.n_tok) yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 4 * g;
+            unsigned char *pr = park + row * 128;
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const floatx16 &c = acc[2 * tl + mbl][nb];
-                    float f[4] = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
-                    if (add_y) {
-                        if (yr) {
-                            bf16x4 *dst = reinterpret_cast<bf16x4 *>(yr + 32 * nb + 8 * g);
-                            const bf16x4 old = *dst;
-                            bf16x4 o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(f[e] + (float)old[e]);
-                            *dst = o;
-                        }
-                    } else {
+            for (int nb = 0; nb < 4; ++nb) {
+                const floatx4 c = acc[4 * tl + mbl][nb];
+                if (add_y) {
+                    if (yr) {
+                        bf16x4 *dst = reinterpret_cast<bf16x4 *>(yr + 16 * nb);
+                        const bf16x4 old = *dst;
                         bf16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)f[e];
-                        *reinterpret_cast<bf16x4 *>(pr + (((4 * nb + g) ^ ((row >> 1) & 7)) << 4)) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + (float)old[e]);
+                        *dst = o;
                     }
+                } else {
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)c[e];
+                    *reinterpret_cast<bf16x4 *>(pr + (((4 * nb + g) ^ (((row >> 1) & 7) << 1)) << 3)) = o;
                 }
+            }
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // only this wavefront reads what it wrote; its LDS operations execute in order
@@ -278,8 +276,7 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         for (int i = 0; i < 8; ++i) {
             const int ti = 8 * i + rl, row = 64 * tl + ti;
             if (ti < t.n_tok) {
-                uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((sl ^ ((row >> 1) & 7)) << 4));
-                if ((row >> 4) & 1) v = make_uint4(v.z, v.w, v.x, v.y);
+                const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((sl ^ ((row >> 1) & 7)) << 4));
                 *reinterpret_cast<uint4 *>(y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 8 * sl) = v;
             }
         }

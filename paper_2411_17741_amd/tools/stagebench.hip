@@ -5,7 +5,8 @@
 // requested one stage ahead, and the same beside 32 matrix-core products per wavefront and stage (operands from
 // registers, or read from LDS as the kernel reads them), and the products alone; and a schedule in which
 // the two wavefronts of a SIMD alternate between (operand reads + load requests) and products, a barrier between the phases;
-// and four wavefronts of 128 x 128 (one per SIMD) instead of eight of 128 x 64.
+// four wavefronts of 128 x 128 (one per SIMD) instead of eight of 128 x 64; the 16x16x32 form of the
+// product instead of 32x32x16; the products alone; and stage loads that return into registers while the products run.
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 stagebench.hip -o stagebench && ./stagebench
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -139,13 +140,13 @@ __global__ __launch_bounds__(512) void stage_kernel(const unsigned short *__rest
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
         const int m = lane & 31, hh = lane >> 5, swz = (m >> 1) & 7;
         for (int kt = 0; kt < NK; ++kt) {
-            if (MODE != 9) load(min(kt + 1, NK - 1), (kt + 1) & 1);
+            if (MODE != 9 && MODE != 12) load(min(kt + 1, NK - 1), (kt + 1) & 1);
             const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * (w & 1) + m) * 128;
             const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (64 * (w >> 1) + m) * 128;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 bf16x8 ao[4], bo[2];
-                if (MODE >= 7) {
+                if (MODE >= 7 && MODE != 12) {
 #pragma unroll
                     for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
 #pragma unroll
@@ -166,7 +167,8 @@ __global__ __launch_bounds__(512) void stage_kernel(const unsigned short *__rest
                     acc.y ^= __builtin_bit_cast(uint4, bo[0]).y ^ __builtin_bit_cast(uint4, bo[1]).z;
                 }
             }
-            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+            if (MODE != 12) { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); }
+            else { ra[0] = (__bf16)((float)ra[0] + 1.f); }
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc.x ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
@@ -273,6 +275,160 @@ __global__ __launch_bounds__(256) void stage_kernel_4w(const unsigned short *__r
     for (int i = 0; i < 16; ++i) accx ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
     if (accx == 0x12345678u) sink[blockIdx.x * 256 + tid] = make_uint4(accx, 0, 0, 0);
 }
+
+// stage loads through registers (issued before the products, written to LDS after them) beside products
+template <bool READS>
+__global__ __launch_bounds__(512) void stage_kernel_regs(const unsigned short *__restrict__ x, const unsigned short *__restrict__ wt, int n_mt, uint4 *sink)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bm = blockIdx.x % n_mt, bn = blockIdx.x / n_mt;
+    const int lr = lane >> 3, ls = lane & 7;
+    const unsigned short *xg = x + (size_t)(256 * bm + 32 * w + lr) * H + ls * 8;
+    const unsigned short *wg = wt + (size_t)(256 * bn + 32 * w + lr) * H + ls * 8;
+    floatx16 c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c[i][e] = 0.f;
+    bf16x8 ra, rb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ra[e] = (__bf16)(float)(lane + e); rb[e] = (__bf16)(float)(w + e); }
+    for (int i = tid; i < 2 * STAGE / 16; i += 512) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(tid, i, 3, 4);
+    __syncthreads();
+    const int m = lane & 31, hh = lane >> 5, swz = (m >> 1) & 7;
+    for (int kt = 0; kt < NK; ++kt) {
+        uint4 r[8];
+        const int kn = min(kt + 1, NK - 1);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const uint4 *>(xg + (size_t)(8 * q) * H + kn * 64);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r[4 + q] = *reinterpret_cast<const uint4 *>(wg + (size_t)(8 * q) * H + kn * 64);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * (w & 1) + m) * 128;
+        const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (64 * (w >> 1) + m) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 ao[4], bo[2];
+            if (READS) {
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 32 * 128 + (((2 * ks + hh) ^ swz) << 4));
+            } else {
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) ao[mb] = ra;
+                bo[0] = rb; bo[1] = rb;
+            }
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) c[2 * mb + nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[mb], bo[nb], c[2 * mb + nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        unsigned char *sd = lds + ((kt + 1) & 1) * STAGE + 32 * w * 128 + lane * 16;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4 *>(sd + q * 1024) = r[q];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4 *>(sd + 32768 + q * 1024) = r[4 + q];
+        __syncthreads();
+    }
+    unsigned accx = *reinterpret_cast<const unsigned *>(lds + tid * 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) accx ^= __float_as_uint(c[i][0]) ^ __float_as_uint(c[i][7]);
+    if (accx == 0x12345678u) sink[blockIdx.x * 512 + tid] = make_uint4(accx, 0, 0, 0);
+}
+template <bool READS> int run_regs(const char *name, const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
+{
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel_regs<READS>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(stage_kernel_regs<READS>, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x, wt, n_mt, sink);
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    const int reps = 21;
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(stage_kernel_regs<READS>, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x + (size_t)(i % 3) * n_mt * 256 * H, wt + (size_t)(i % 3) * n_nt * 256 * H, n_mt, sink);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+    printf("%-44s %8.1f us\n", name, ms * 1e3 / reps);
+    fflush(stdout);
+    return 0;
+}
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+// the k loop with the 16x16x32 form of the product: 64 products and 24 operand reads per wavefront and stage
+__global__ __launch_bounds__(512) void stage_kernel_m16(const unsigned short *__restrict__ x, const unsigned short *__restrict__ wt, int n_mt, uint4 *sink)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bm = blockIdx.x % n_mt, bn = blockIdx.x / n_mt;
+    const int lr = lane >> 3, ls = lane & 7;
+    const unsigned short *xg = x + (size_t)(256 * bm + 32 * w + lr) * H + ls * 8;
+    const unsigned short *wg = wt + (size_t)(256 * bn + 32 * w + lr) * H + ls * 8;
+    auto load = [&](int kt, int buf) {
+        unsigned char *sa = lds + buf * STAGE + 32 * w * 128;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(xg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(wg + (size_t)(8 * q) * H + kt * 64, (__attribute__((address_space(3))) void *)(sa + 32768 + q * 1024), 16, 0, 0);
+    };
+    floatx4 c[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c[i][j][e] = 0.f;
+    for (int i = tid; i < 2 * STAGE / 16; i += 512) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(tid, i, 3, 4);
+    __syncthreads();
+    load(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    const int m = lane & 15, g = lane >> 4, swz = (m >> 1) & 7;
+    for (int kt = 0; kt < NK; ++kt) {
+        load(min(kt + 1, NK - 1), (kt + 1) & 1);
+        const unsigned char *sa = lds + (kt & 1) * STAGE + (128 * (w & 1) + m) * 128;
+        const unsigned char *sb = lds + (kt & 1) * STAGE + 32768 + (64 * (w >> 1) + m) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 ao[8], bo[4];
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) ao[mb] = *reinterpret_cast<const bf16x8 *>(sa + mb * 16 * 128 + (((4 * ks + g) ^ swz) << 4));
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) bo[nb] = *reinterpret_cast<const bf16x8 *>(sb + nb * 16 * 128 + (((4 * ks + g) ^ swz) << 4));
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) c[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ao[mb], bo[nb], c[mb][nb], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    unsigned accx = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) accx ^= __float_as_uint(c[i][j][0]) ^ __float_as_uint(c[i][j][3]);
+    if (accx == 0x12345678u) sink[blockIdx.x * 512 + tid] = make_uint4(accx, 0, 0, 0);
+}
+int run_m16(const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
+{
+    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel_m16), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(stage_kernel_m16, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x, wt, n_mt, sink);
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    const int reps = 21;
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(stage_kernel_m16, dim3(n_mt * n_nt), dim3(512), 2 * STAGE, 0, x + (size_t)(i % 3) * n_mt * 256 * H, wt + (size_t)(i % 3) * n_nt * 256 * H, n_mt, sink);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+    printf("%-44s %8.1f us\n", "16x16x32 products: loads + 24 reads + 64 MFMA", ms * 1e3 / reps);
+    fflush(stdout);
+    return 0;
+}
 template <int MODE> int run(const char *name, const unsigned short *x, const unsigned short *wt, uint4 *sink, int n_mt, int n_nt)
 {
     CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(stage_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE));
@@ -322,7 +478,11 @@ int main()
     if (run<8>("LDS-direct ahead + 24 LDS reads + 32 MFMA/stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<9>("24 LDS reads + 32 MFMA/stage, no loads", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<10>("alternating wavefronts: reads+loads | MFMA", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run<12>("32 MFMA/stage from registers only", x, wt, sink, n_mt, n_nt)) return 1;
     if (run4(x, wt, sink, n_mt, n_nt)) return 1;
+    if (run_m16(x, wt, sink, n_mt, n_nt)) return 1;
+    if (run_regs<false>("loads via registers + 32 MFMA (reg operands)", x, wt, sink, n_mt, n_nt)) return 1;
+    if (run_regs<true>("loads via registers + LDS reads + 32 MFMA", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<1>("registers + ds_write, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<4>("registers only, no barrier", x, wt, sink, n_mt, n_nt)) return 1;
     if (run<5>("registers only, barrier per stage", x, wt, sink, n_mt, n_nt)) return 1;
