@@ -99,13 +99,19 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     }
     // At operands: block slot q -> rank block nbq; rows past the stored rank are clamped (their
     // results are never written)
+    // A B operand wants, in lane (m, g), rank row m and k chunk g of the step: 16 rows x 64 bytes per load
+    // instruction with neighbouring lanes in different rows, the costliest shape for the load path.  The same
+    // 16 x 64 bytes are therefore fetched with the four lanes of a quad on one row (lane l: row l/4, chunk
+    // l%4 -- a 64-byte request per quad) and put in operand order by a lane permutation on the way to the
+    // products (ds_bpermute: lane (m, g) takes the registers of lane 4m + g).
     int nbq[NBW];
     const __bf16 *ag[NBW];
 #pragma unroll
     for (int q = 0; q < NBW; ++q) {
         nbq[q] = NSPLIT ? w + 4 * q : q;
-        ag[q] = At + (size_t)min(16 * nbq[q] + m, rs - 1) * a.h_in;
+        ag[q] = At + (size_t)min(16 * nbq[q] + (lane >> 2), rs - 1) * a.h_in;
     }
+    const int perm_src = 4 * (4 * m + g);  // byte address of the source lane, as ds_bpermute takes it
     const int ks0 = NSPLIT ? 0 : w;  // first MFMA k step of a stage for this wavefront
 
     uint4 xr[2][4];
@@ -122,11 +128,19 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     };
     uint4 br[2][NBW][NKW];
     auto load_at = [&](int st, uint4(&d)[NBW][NKW]) {
-        const int k = stage_k(st) + 8 * g;
+        const int k = stage_k(st) + 8 * (lane & 3);
 #pragma unroll
         for (int q = 0; q < NBW; ++q)
 #pragma unroll
             for (int j = 0; j < NKW; ++j) d[q][j] = *reinterpret_cast<const uint4 *>(ag[q] + min(k + 32 * (ks0 + j), k_last));
+    };
+    auto operand_of = [&](const uint4 &r) {
+        uint4 o;
+        o.x = __builtin_amdgcn_ds_bpermute(perm_src, r.x);
+        o.y = __builtin_amdgcn_ds_bpermute(perm_src, r.y);
+        o.z = __builtin_amdgcn_ds_bpermute(perm_src, r.z);
+        o.w = __builtin_amdgcn_ds_bpermute(perm_src, r.w);
+        return __builtin_bit_cast(bf16x8, o);
     };
 
     floatx4 acc[4][NBW];
@@ -149,6 +163,11 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
         constexpr int SLOT = decltype(slot_tag)::value;
         load_at(st + 1, br[CUR ^ 1]);  // At of the next stage, then this stage's products
         const unsigned char *xb = xs[SLOT];
+        bf16x8 bop[NBW][NKW];
+#pragma unroll
+        for (int q = 0; q < NBW; ++q)
+#pragma unroll
+            for (int j = 0; j < NKW; ++j) bop[q][j] = operand_of(br[CUR][q][j]);
 #pragma unroll
         for (int j = 0; j < NKW; ++j) {
             const int ks = ks0 + j;
@@ -156,9 +175,7 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
             for (int mb = 0; mb < 4; ++mb) {
                 const bf16x8 av = *reinterpret_cast<const bf16x8 *>(&xb[(16 * mb + m) * XROW + (4 * ks + g) * 16]);
 #pragma unroll
-                for (int q = 0; q < NBW; ++q)
-                    acc[mb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, br[CUR][q][j]),
-                                                                         acc[mb][q], 0, 0, 0);
+                for (int q = 0; q < NBW; ++q) acc[mb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bop[q][j], acc[mb][q], 0, 0, 0);
             }
         }
         // stage st+1 goes to LDS (its buffer was last read two barriers ago), stage st+3 is requested
