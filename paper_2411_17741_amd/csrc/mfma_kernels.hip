@@ -30,8 +30,10 @@ constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the st
 //    contiguous bytes, two stages ahead of the one being multiplied (so two stages of loads are
 //    in flight in registers while a third waits ready in LDS), one barrier per stage.  Rows are
 //    padded by 16 bytes, which puts the 16 rows of an A-operand read in distinct banks.
-//  - At, which comes out of L2 and is shared by all tiles of a segment, is loaded straight into
-//    B-operand registers one stage ahead.
+//  - At, which comes out of L2 and is shared by all tiles of a segment, is loaded into registers one
+//    stage ahead -- the four lanes of a quad on one rank row (64-byte requests; in the operand's own
+//    order, with neighbouring lanes in different rows, the same bytes cost the load path 1.7 times
+//    as long) -- and put in operand order by a lane permutation before the products.
 //  - From 4 rank blocks (of 16) up, wavefront w owns rank blocks w and w+4 for the whole k range
 //    and writes its part of V itself.  Below that, the wavefronts split the four MFMA k steps of
 //    a stage instead, each covering all rank blocks, and their partials are summed through LDS.
