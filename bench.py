@@ -84,6 +84,8 @@ def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
     gen.manual_seed(4321)
     wts = [[(torch.randn((p.h_out, p.h_in), generator=gen, device=dev) * 0.02).to(torch.bfloat16) for p in inst.projs] for _ in range(2)]
 
+    ws = torch.empty((inst.T * max(p.h_out for p in inst.projs),), dtype=torch.float32, device=dev)  # fp32 adapter term of the GEMV tokens
+
     def step(s: int, fused: bool) -> None:
         rc, plan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
         B.check(rc, "lora_plan_create")
@@ -91,7 +93,8 @@ def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
             for p in range(n_proj):
                 x, y, wt = xs[l % n_sets][inst.projs[p].x_key], ys[l % n_sets][p], wts[(s + l) % 2][p]
                 if fused:
-                    B.check(B.lora_linear_plan(h, plan, l, p, x.data_ptr(), wt.data_ptr(), y.data_ptr(), inst.scale, sh), "lora_linear_plan")
+                    B.check(B.lora_linear_plan(h, plan, l, p, x.data_ptr(), wt.data_ptr(), y.data_ptr(), inst.scale, sh,
+                                               workspace=ws.data_ptr(), workspace_bytes=ws.numel() * 4), "lora_linear_plan")
                 else:
                     torch.matmul(x, wt.t(), out=y)
                     B.check(B.lora_apply_plan(h, plan, l, p, x.data_ptr(), y.data_ptr(), inst.scale, sh), "lora_apply_plan")

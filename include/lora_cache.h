@@ -304,11 +304,17 @@ int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc
  * W transposed, the layout a linear layer keeps its weight in; y [T][h_out] is written only (it
  * need not hold anything on entry, and must not overlap x).  The shrink runs as in lora_apply_plan;
  * then one matrix-core kernel computes the base product over row tiles of 64 tokens and adds the
- * adapter product of the tiles as one more slab of the contraction; tokens on the GEMV path get
- * their adapter term added afterwards.  bf16 caches only (LORA_E_INVAL otherwise); other errors and
- * stream semantics as for lora_apply_plan. */
+ * adapter product of the tiles as one more slab of the contraction.  Tokens on the GEMV path get their
+ * adapter term from the GEMV kernels beforehand, and the matrix-core kernel adds it to their rows
+ * before the one rounding of the output: as fp32 through `workspace` (device, caller-owned, 16-byte
+ * aligned, at least lora_linear_workspace_bytes() bytes: T * h_out floats when the plan has GEMV
+ * tokens, else 0; its contents are scratch), or, with workspace = NULL, through the output rows
+ * themselves, where the term is rounded to bf16 on the way (its error then adds to the output's).
+ * bf16 caches only (LORA_E_INVAL otherwise; also for a workspace that is misaligned or too small);
+ * other errors and stream semantics as for lora_apply_plan. */
+int lora_linear_workspace_bytes(const lora_cache_t *c, const lora_plan_t *p, int32_t proj, size_t *bytes);
 int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, const void *Wt, void *y,
-                     float scale, void *stream);
+                     float scale, void *workspace, size_t workspace_bytes, void *stream);
 
 /* One-call form: index + apply (uses one of 4 internal plans in rotation; blocks the
  * host only if the plan used 4 calls ago is still in flight). */

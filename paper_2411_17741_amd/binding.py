@@ -124,7 +124,8 @@ _SIGS = {
     "lora_plan_info": (c_int, [c_void_p, POINTER(lora_plan_info_t)]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
-    "lora_linear_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_float, c_void_p]),
+    "lora_linear_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_float, c_void_p, c_size_t, c_void_p]),
+    "lora_linear_workspace_bytes": (c_int, [c_void_p, c_void_p, c_int32, POINTER(c_size_t)]),
     "lora_apply": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_float, c_void_p]),
     "lora_cache_set_fencing": (c_int, [c_void_p, c_int32]),
     "lora_cache_set_timing": (c_int, [c_void_p, c_int32]),
@@ -446,9 +447,17 @@ def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, s
                                 c_void_p(stream or None))
 
 
-def lora_linear_plan(cache, plan, layer: int, proj: int, x: int, Wt: int, y: int, scale: float, stream: int = 0) -> int:
+def lora_linear_workspace_bytes(cache, plan, proj: int):
+    """-> (status, bytes)"""
+    n = c_size_t(0)
+    rc = _lib.lora_linear_workspace_bytes(cache, plan, proj, ctypes.byref(n))
+    return rc, n.value
+
+
+def lora_linear_plan(cache, plan, layer: int, proj: int, x: int, Wt: int, y: int, scale: float, stream: int = 0,
+                     workspace: int = 0, workspace_bytes: int = 0) -> int:
     return _lib.lora_linear_plan(cache, plan, layer, proj, c_void_p(x or None), c_void_p(Wt or None), c_void_p(y or None), scale,
-                                 c_void_p(stream or None))
+                                 c_void_p(workspace or None), workspace_bytes, c_void_p(stream or None))
 
 
 def make_descs(entries):

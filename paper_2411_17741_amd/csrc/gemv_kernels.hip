@@ -272,7 +272,10 @@ __device__ __forceinline__ void gemv_expand_body(const ApplyArgs &a, const GemvI
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 const int n = c0 + lane + 64 * p;
-                if (n < c1) y[(size_t)it.tok[t] * a.h_out + n] = from_float<E>(to_float(yv[t][p]) + s * acc[t][p]);
+                if (n < c1) {
+                    if (a.y32) a.y32[(size_t)it.tok[t] * a.h_out + n] = s * acc[t][p];
+                    else y[(size_t)it.tok[t] * a.h_out + n] = from_float<E>(to_float(yv[t][p]) + s * acc[t][p]);
+                }
             }
         }
     }
@@ -365,7 +368,10 @@ __device__ __forceinline__ void gemv_expand_mfma(const ApplyArgs &a, const GemvI
         o[1] = (__bf16)(__uint_as_float(lo & 0xffff0000u) + d[1]);
         o[2] = (__bf16)(__uint_as_float(hi << 16) + d[2]);
         o[3] = (__bf16)(__uint_as_float(hi & 0xffff0000u) + d[3]);
-        if (tok_q >= 0 && 4 * i < n_cb) *reinterpret_cast<bf16x4 *>(yrow + 64 * i) = o;
+        if (tok_q >= 0 && 4 * i < n_cb) {
+            if (a.y32) *reinterpret_cast<gv_floatx4 *>(a.y32 + (size_t)tok_q * a.h_out + c0 + 4 * q + 64 * i) = d;
+            else *reinterpret_cast<bf16x4 *>(yrow + 64 * i) = o;
+        }
     }
 }
 
@@ -420,7 +426,8 @@ __device__ __forceinline__ void gemv_expand_generic(const ApplyArgs &a, const Ge
         for (int t = 0; t < TB; ++t) {
             if (it.tok[t] >= 0) {
                 E *yp = y + (size_t)it.tok[t] * a.h_out + n;
-                *yp = from_float<E>(to_float(*yp) + acc[t]);
+                if (a.y32) a.y32[(size_t)it.tok[t] * a.h_out + n] = acc[t];
+                else *yp = from_float<E>(to_float(*yp) + acc[t]);
             }
         }
     }

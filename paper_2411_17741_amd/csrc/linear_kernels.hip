@@ -250,10 +250,16 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
                 if (add_y) {
                     if (yr) {
                         bf16x4 *dst = reinterpret_cast<bf16x4 *>(yr + 16 * nb);
-                        const bf16x4 old = *dst;
                         bf16x4 o;
+                        if (a.y32) {  // the rows' adapter term as fp32, same place in the workspace as in y
+                            const floatx4 t32 = *reinterpret_cast<const floatx4 *>(a.y32 + (yr - y) + 16 * nb);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + (float)old[e]);
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + t32[e]);
+                        } else {
+                            const bf16x4 old = *dst;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + (float)old[e]);
+                        }
                         *dst = o;
                     }
                 } else {

@@ -1272,10 +1272,21 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
     return fence_applies(c, p, st);
 }
 
+int lora_linear_workspace_bytes(const lora_cache_t *c, const lora_plan_t *p, int32_t proj, size_t *bytes)
+{
+    if (!c || !p || !p->in_use || !bytes || proj < 0 || proj >= (int32_t)c->proj.size()) return LORA_E_INVAL;
+    *bytes = p->n_tok_list > p->n_tile_tok ? (size_t)p->T * c->proj[proj].h_out * sizeof(float) : 0;
+    return LORA_OK;
+}
+
 int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, const void *Wt, void *y,
-                     float scale, void *stream)
+                     float scale, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!c || !p || !p->in_use || c->host_only || c->dtype != LORA_BF16) return LORA_E_INVAL;
+    if (workspace) {
+        size_t need = 0;
+        if (lora_linear_workspace_bytes(c, p, proj, &need) != LORA_OK || !aligned16(workspace) || workspace_bytes < need) return LORA_E_INVAL;
+    }
     int rc = validate_apply(c, p, layer, proj, x, y);
     if (rc != LORA_OK) return rc;
     if (p->T > 0 && (!Wt || !aligned16(Wt))) return LORA_E_INVAL;
@@ -1318,9 +1329,11 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
         }
         HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, p->n_tile_tok, choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in), st, tm));
     }
-    // the adapter term of the GEMV tokens, into their zeroed output rows
+    // the adapter term of the GEMV tokens: as fp32 into the caller's workspace (row = token), or, without
+    // one, into their zeroed output rows (rounded to the output type on the way)
     if (p->n_tok_list > p->n_tile_tok) {
-        HIP_TRY(lora::launch_zero_rows(y, a.tok_list + p->n_tile_tok, p->n_tok_list - p->n_tile_tok, a.h_out, st));
+        a.y32 = static_cast<float *>(workspace);
+        if (!a.y32) HIP_TRY(lora::launch_zero_rows(y, a.tok_list + p->n_tile_tok, p->n_tok_list - p->n_tile_tok, a.h_out, st));
         HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));
         HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st, tm));
     }

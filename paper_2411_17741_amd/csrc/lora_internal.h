@@ -55,6 +55,9 @@ struct ApplyArgs {
     float *v;                 // device [max_tokens][v_stride] shrink result
     int32_t h_in, h_out, v_stride;
     float scale;
+    // when set, the GEMV expand writes its term s.v.B there as fp32 ([token][h_out]) instead of adding it to y,
+    // and linear_tiles_kernel takes the term of its GEMV rows from there
+    float *y32 = nullptr;
 };
 
 // Optional per-kernel timing: when a launch gets a KernelTimer it asks it for an event pair and

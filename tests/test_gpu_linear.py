@@ -24,7 +24,7 @@ def _weight(inst, p, seed):
     return wl.bf16_round(w)
 
 
-def _run(inst, p, rows, seed=0, mfma_min_tokens=0):
+def _run(inst, p, rows, seed=0, mfma_min_tokens=0, workspace=True):
     B, H = _mods()
     pi = H.PooledInstance(inst, n_layers=1, mfma_min_tokens=mfma_min_tokens)
     try:
@@ -34,7 +34,11 @@ def _run(inst, p, rows, seed=0, mfma_min_tokens=0):
         yd = torch.full((inst.T, inst.projs[p].h_out), float("nan"), dtype=torch.bfloat16, device=xd.device)  # written only
         plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
         st = torch.cuda.current_stream().cuda_stream
-        B.check(B.lora_linear_plan(pi.pool.handle, plan, 0, p, xd.data_ptr(), wtd.data_ptr(), yd.data_ptr(), inst.scale, st))
+        rc, ws_bytes = B.lora_linear_workspace_bytes(pi.pool.handle, plan, p)
+        B.check(rc)
+        ws = torch.full((max(1, ws_bytes // 4),), float("nan"), dtype=torch.float32, device=xd.device) if workspace else None
+        B.check(B.lora_linear_plan(pi.pool.handle, plan, 0, p, xd.data_ptr(), wtd.data_ptr(), yd.data_ptr(), inst.scale, st,
+                                   workspace=ws.data_ptr() if workspace else 0, workspace_bytes=ws_bytes if workspace else 0))
         pi.pool.check_fault()
         y_rows = yd[torch.from_numpy(rows).to(yd.device)].float().cpu().numpy()
         assert np.isfinite(y_rows).all()
@@ -55,16 +59,18 @@ def _run(inst, p, rows, seed=0, mfma_min_tokens=0):
         pi.close()
 
 
+@pytest.mark.parametrize("workspace", [True, False])
 @pytest.mark.parametrize("mfma_min_tokens", [0, 16])
-def test_linear_small_mixed_every_token(mfma_min_tokens):
+def test_linear_small_mixed_every_token(mfma_min_tokens, workspace):
     """Decode tokens, short and long prompts with ragged tails, a hot adapter, tokens without an adapter;
-    512 -> 640: the last column block is partial."""
+    512 -> 640: the last column block is partial.  With the fp32 workspace for the adapter term of the GEMV
+    tokens and without (the term then passes through the bf16 output rows)."""
     base = wl.small_mixed(seed=5)
     projs = [wl.Projection("g", 512, 640, 0), wl.Projection("d", 640, 320, 1)]
     inst = wl.Instance(name="lin_small", dtype="bf16", seed=5, projs=projs, ranks=base.ranks, adapter_ids=base.adapter_ids,
                        alpha=base.alpha, scale=base.scale, seg_offsets=base.seg_offsets, seg_adapter=base.seg_adapter)
     for p in range(2):
-        _run(inst, p, np.arange(inst.T, dtype=np.int64), seed=p, mfma_min_tokens=mfma_min_tokens)
+        _run(inst, p, np.arange(inst.T, dtype=np.int64), seed=p, mfma_min_tokens=mfma_min_tokens, workspace=workspace)
 
 
 def test_linear_prefill_config_sampled():
@@ -74,3 +80,27 @@ def test_linear_prefill_config_sampled():
                                      inst.seg_offsets[:-1] + 63, inst.seg_offsets[:-1] + 64])).astype(np.int64)
     rows = rows[rows < inst.T]
     _run(inst, 0, rows)
+
+
+def test_linear_workspace_arguments():
+    B, H = _mods()
+    inst = wl.small_mixed(seed=2)
+    pi = H.PooledInstance(inst, n_layers=1)
+    try:
+        plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+        rc, need = B.lora_linear_workspace_bytes(pi.pool.handle, plan, 0)
+        assert rc == B.LORA_OK and need == inst.T * inst.projs[0].h_out * 4   # the small batch is all on the GEMV path
+        x = H.to_device(inst.x(0), pi.dtype)
+        wt = torch.zeros((inst.projs[0].h_out, inst.projs[0].h_in), dtype=torch.bfloat16, device=x.device)
+        y = torch.zeros((inst.T, inst.projs[0].h_out), dtype=torch.bfloat16, device=x.device)
+        ws = torch.zeros((need // 4 + 4,), dtype=torch.float32, device=x.device)
+        call = lambda ptr, n: B.lora_linear_plan(pi.pool.handle, plan, 0, 0, x.data_ptr(), wt.data_ptr(), y.data_ptr(), 1.0, 0,
+                                                 workspace=ptr, workspace_bytes=n)
+        assert call(ws.data_ptr(), need - 4) == B.LORA_E_INVAL       # too small
+        assert call(ws.data_ptr() + 4, need) == B.LORA_E_INVAL       # not 16-byte aligned
+        assert call(ws.data_ptr(), need) == B.LORA_OK
+        assert B.lora_linear_workspace_bytes(pi.pool.handle, plan, 9)[0] == B.LORA_E_INVAL
+        torch.cuda.synchronize()
+        pi.pool.plan_destroy(plan)
+    finally:
+        pi.close()

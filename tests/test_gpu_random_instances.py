@@ -65,8 +65,11 @@ def test_random_instance(case):
             wtd = H.to_device(np.ascontiguousarray(W.T), pi.dtype)
             yl = torch.full((inst.T, pr.h_out), float("nan"), dtype=torch.bfloat16, device=xd.device)
             plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)
+            rc, ws_bytes = B.lora_linear_workspace_bytes(pi.pool.handle, plan, p)
+            B.check(rc)
+            ws = torch.full((max(1, ws_bytes // 4),), float("nan"), dtype=torch.float32, device=xd.device)
             B.check(B.lora_linear_plan(pi.pool.handle, plan, 0, p, xd.data_ptr(), wtd.data_ptr(), yl.data_ptr(), inst.scale,
-                                       torch.cuda.current_stream().cuda_stream))
+                                       torch.cuda.current_stream().cuda_stream, workspace=ws.data_ptr(), workspace_bytes=ws_bytes))
             pi.pool.check_fault()
             ylin = yl.float().cpu().numpy()
             pi.pool.plan_destroy(plan)
@@ -75,6 +78,8 @@ def test_random_instance(case):
             ref = oracle.lora_apply(x, base64, inst.seg_offsets, inst.seg_adapter, ads, inst.scale)
             m = H.error_metrics(ylin, ref, base64)
             for k, lim in TOL["bf16"].items():
+                if k == "delta_rel_fro" and not (ta >= 0).any():
+                    continue  # a batch without any adapter has no delta to measure against
                 assert m[k] <= lim, f"{what}, proj {p}, fused linear: {k} = {m[k]:.3e} > {lim}"
     finally:
         pi.close()
