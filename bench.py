@@ -39,7 +39,7 @@ WORKLOAD_TEXT = {
 # profiles/tile_and_gemv_kernels_traffic.txt).  A counter run cannot happen inside this process, so the figures
 # measured for the same commands are carried here.
 MEASURED_TRAFFIC = {("decode", "gemv_fused"): 25.37e6, ("prefill", "mfma_shrink"): 63.8e6, ("prefill", "mfma_expand"): 146.8e6, ("mixed", "mfma_expand"): 662.8e6,
-                    ("stress", "gemv_fused"): 218.2e6, ("decode_heavy", "gemv_expand"): 139.2e6}
+                    ("stress", "gemv_fused"): 218.2e6, ("decode_heavy", "gemv_expand"): 139.2e6}  # (decode_heavy: measured for the two-launch form, --gemv split)
 DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32}
 DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100}
 

@@ -499,11 +499,19 @@ __global__ __launch_bounds__(256) void gemv_fused_kernel(ApplyArgs a, const Gemv
         const GemvItem it = gs[blockIdx.x];
         gemv_shrink_dispatch<E>(a, it, ho, red);
     } else {
-        const int w = threadIdx.x >> 6;
+        // the wavefront number and everything read through it are the same in all lanes: say so, and the
+        // item's fields and the addresses built from them stay in scalar registers
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int unit = ((int)blockIdx.x - n_gs) * 4 + w;
         const int item = unit / n_super;
         if (item >= n_ge) return;
-        const GemvItem it = ge[item];
+        GemvItem it = ge[item];
+#pragma unroll
+        for (int t = 0; t < LORA_GEMV_BATCH; ++t) it.tok[t] = __builtin_amdgcn_readfirstlane(it.tok[t]);
+        it.row = __builtin_amdgcn_readfirstlane(it.row);
+        it.rank = __builtin_amdgcn_readfirstlane(it.rank);
+        it.a = __builtin_amdgcn_readfirstlane(it.a);
+        it.alpha = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, it.alpha)));
         gemv_expand_wave<E>(a, it, unit - item * n_super, ho, vs[w]);
     }
 }

@@ -154,17 +154,18 @@ def test_stress_config_with_fills_overlapping_applies():
         pi.close()
 
 
-def test_large_decode_batch_takes_the_two_launch_form():
+@pytest.mark.parametrize("form", ["auto", "split"])
+def test_large_decode_batch_in_both_gemv_forms(form):
     """2048 decode requests over 300 adapters, uniform popularity (so hardly any slot reaches the
-    tile threshold): several thousand GEMV shrink items, which the library runs as two launches.
-    Sampled tokens against the oracle."""
+    tile threshold): several thousand GEMV shrink items -- as one launch with the in-kernel hand-over
+    (what the library picks up to 8192 items) and as two launches.  Sampled tokens against the oracle."""
     B, H = _mods()
     inst = wl.make_instance("big_decode", dtype="bf16", seed=3, projs=[wl.Projection("q", 4096, 4096, 0)], n_adapters=300,
                             rank_choices=[8, 16, 32, 64, 128], n_decode=2048, prompt_lens=[], zipf_alpha=None, n_base_only=16)
-    pi = H.PooledInstance(inst)
+    pi = H.PooledInstance(inst, flags=B.LORA_CACHE_SPLIT_GEMV if form == "split" else 0)
     try:
         rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, B.LORA_MFMA_MIN_TOKENS, counts_only=True)
-        assert w["n_gs_items"] > 2048  # above the library's bound for the one-launch form
+        assert 4096 < w["n_gs_items"] <= 8192
         h = pi.pool.handle
         B.check(B.lora_cache_set_timing(h, 1))
         x, base = inst.x(0), inst.base_out(0)
@@ -172,7 +173,10 @@ def test_large_decode_batch_takes_the_two_launch_form():
         pi.apply(0, 0, xd, yd)
         pi.pool.check_fault()
         rc, tm = B.lora_cache_read_timing(h)
-        assert tm["gemv_shrink"][1] == 1 and tm["gemv_expand"][1] == 1 and tm["gemv_fused"][1] == 0
+        if form == "split":
+            assert tm["gemv_shrink"][1] == 1 and tm["gemv_expand"][1] == 1 and tm["gemv_fused"][1] == 0
+        else:
+            assert tm["gemv_shrink"][1] == 0 and tm["gemv_expand"][1] == 0 and tm["gemv_fused"][1] == 1
         rows = _sample_tokens(inst, n_random=160, seed=3)
         y_rows = yd[torch.from_numpy(rows).to(yd.device)].float().cpu().numpy()
         _check_sampled(inst, 0, rows, y_rows, x[rows], base[rows], inst.token_adapter()[rows], "large decode batch")
