@@ -475,6 +475,7 @@ def main() -> int:
     ap.add_argument("--fill-by-part", action="store_true", help="prefetch experiment: one lora_cache_fill_slot call per (layer, projection) "
                     "instead of one lora_cache_fill_slot_parts call per adapter")
     ap.add_argument("--slots-per-rank", type=int, default=0, help="prefetch experiment: pool slots per rank class (default: all but 3 of the 40 adapters of a rank)")
+    ap.add_argument("--prewarm-s", type=float, default=1.0, help="seconds of untimed steps before the warm-up steps (a cold GPU ramps its clocks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -544,6 +545,15 @@ def main() -> int:
     torch.cuda.synchronize()
     cold_call_us = (time.perf_counter() - t_c) * 1e6
 
+    # a GPU that has been idle runs its first second of work at about half speed (the same bench as the
+    # first process on a fresh box: 0.83 ms per step, 0.46 ms with 1.4 s of steps before it): about a
+    # second of untimed steps comes first, then the W warm-up steps, then the K timed ones
+    prewarm_steps, t_pre = 0, time.perf_counter()
+    while time.perf_counter() - t_pre < args.prewarm_s and prewarm_steps < 20000:
+        for s in range(8):
+            step(s)
+        torch.cuda.synchronize()
+        prewarm_steps += 8
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
@@ -708,6 +718,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "fill_overlap": fill_overlap,
+        "prewarm_steps": prewarm_steps,
         "layer": {"algorithmic_bytes": step_bytes, "flops": step_flops, "achieved_GBs": step_bytes / (ms_per_layer * 1e-3) / 1e9,
                   "hbm_frac": step_bytes / (ms_per_layer * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "achieved_TFLOPs": step_flops / (ms_per_layer * 1e-3) / 1e12, "setup_s": t_setup},
