@@ -604,7 +604,7 @@ def main() -> int:
     B.check(B.lora_plan_destroy(h, plan))
     rc, w = B.lora_index(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, plan_info.mfma_min_tokens)
     B.check(rc)
-    assert len(w["tiles"]) == plan_info.n_tiles and len(w["gs_items"]) == plan_info.n_gemv_shrink_items
+    assert len(w["tiles"]) == plan_info.n_tiles
     per_proj = algorithmic_bytes(inst, w)
     step_bytes = sum(sum(b for k, b in v.items() if k != "gemv_fused") for v in per_proj)
     step_flops = sum(2 * it[1] * it[3] * (p.h_in + p.h_out) for p in inst.projs for it in (w["tiles"] + w["groups"]))
@@ -714,7 +714,7 @@ def main() -> int:
                    "pool_adapters": int(inst.n_adapters), "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
                    "host_index_us": index_us, "host_plan_create_us": plan_us,
-                   "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": len(w["gs_items"]), "gemv_groups": len(w["groups"])},
+                   "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": plan_info.n_gemv_shrink_items, "gemv_groups": len(w["groups"])},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "fill_overlap": fill_overlap,

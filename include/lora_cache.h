@@ -49,7 +49,9 @@ typedef enum {
     LORA_E_STATE = -2,    /* slot in the wrong state (apply on an unfilled slot, evict/refill while referenced) */
     LORA_E_NOMEM = -3,    /* caller's pool buffer too small, no free plan, host allocation failed */
     LORA_E_HIP = -4,      /* a HIP call failed; see lora_last_hip_error() */
-    LORA_E_NOTFOUND = -5  /* adapter id not cached */
+    LORA_E_NOTFOUND = -5, /* adapter id not cached */
+    LORA_E_FAULT = -6     /* a kernel of an earlier apply gave up a bounded wait (its outputs are invalid); every apply
+                             returns this until lora_cache_check_fault has been called */
 } lora_status;
 
 enum { LORA_F32 = 0, LORA_BF16 = 1 };                               /* element type of x, base_out, A, B */
@@ -70,7 +72,6 @@ enum {
 #define LORA_TILE_TOKENS 64      /* tokens per matrix-core tile */
 #define LORA_MFMA_MIN_TOKENS 16  /* default: segments / pooled slots with fewer tokens take the GEMV path ... */
 #define LORA_MFMA_MIN_TOKENS_MIXED 8 /* ... and, with the default, this is the threshold once a batch has any tile at 16 */
-#define LORA_GEMV_BATCH 4        /* tokens one GEMV work item handles */
 
 typedef struct lora_cache lora_cache_t; /* opaque */
 typedef struct lora_plan lora_plan_t;   /* opaque: device-resident work lists of one batch */
@@ -169,6 +170,11 @@ typedef struct {
 } lora_slot_info_t;
 int lora_cache_slot_info(lora_cache_t *c, int32_t slot, lora_slot_info_t *out);
 
+/* The state alone (section 4.2: an entry is loaded before the batch that needs it is sent):
+ * LORA_SLOT_EMPTY, LORA_SLOT_FILLING (bound, not all parts enqueued or the last copy still in
+ * flight) or LORA_SLOT_READY. */
+int lora_cache_slot_state(lora_cache_t *c, int32_t slot, int32_t *state);
+
 /* A free slot of the smallest class that fits `rank`, or LORA_E_NOMEM. */
 int lora_cache_find_free_slot(lora_cache_t *c, int32_t rank, int32_t *slot);
 
@@ -185,8 +191,8 @@ int lora_cache_stats(const lora_cache_t *c, lora_cache_stats_t *out);
  * defaults) but not the units of the three terms; here each is scaled to [0, 1] over the cached
  * entries: frequency = requests that used the entry / the largest such count; recency =
  * 1 - age / largest age, age counted in requests since the entry's last use; size = rank / largest
- * cached rank (a larger adapter costs more to reload, so it is kept longer).  "Within a specific
- * time frame": every freq_window requests all frequencies are halved (0 = never).
+ * cached rank (a larger adapter costs more to reload, so it is kept longer).  The paper counts uses
+ * over a limited period only: here every freq_window requests all frequencies are halved (0 = never).
  * (0, 1, 0) is LRU; equal weights are the paper's FairShare comparison point. */
 typedef struct {
     double w_freq, w_recency, w_size;
@@ -227,25 +233,22 @@ int lora_cache_slab(const lora_cache_t *c, int32_t layer, int32_t proj, int32_t 
 
 /* ---- indexing ------------------------------------------------------------------------ */
 
-/* One unit of work.  tok_off/n_tok name tokens in tok_list; a, b depend on the list:
- * tiles: a = running tile number inside its segment or pool;  groups: unused;
- * gs_items (GEMV shrink): n_tok <= LORA_GEMV_BATCH, a = first rank row, b = rows (<= 4);
- * ge_items (GEMV expand): n_tok <= LORA_GEMV_BATCH, a = column offset inside a 1024-column
- * super-chunk, b = columns.  c, d are 0. */
+/* A tile or a group: tokens tok_list[tok_off .. tok_off + n_tok) of one slot.  a = running tile
+ * number inside its segment or pool (0 for groups); b, c, d are 0. */
 typedef struct {
     int32_t tok_off, n_tok, slot, rank, a, b, c, d;
 } lora_item_t;
 
 typedef struct {
-    int32_t n_tok_list, n_tiles, n_groups, n_gs_items, n_ge_items;
+    int32_t n_tok_list, n_tiles, n_groups;
     int32_t *tok_list;     /* tokens of all tiles, then of all groups */
     lora_item_t *tiles;    /* <= LORA_TILE_TOKENS tokens of one slot each (matrix-core path) */
     lora_item_t *groups;   /* all remaining tokens of one slot (GEMV path) */
-    lora_item_t *gs_items; /* groups x blocks of 4 rank rows */
-    lora_item_t *ge_items; /* groups x column chunks */
 } lora_worklists_t;
 
-/* Pure host: build the canonical work lists of a batch (integer work only).
+/* Pure host: which token goes which way, and with which cache entry (integer work only; section 2:
+ * one batch mixes requests of different adapters, section 4.1: the batch is formed anew every
+ * iteration, so this runs once per iteration).
  *  - seg_offsets [n_seg+1] non-decreasing, [0] = 0, [n_seg] = T; seg_slot [n_seg], < 0 =
  *    no adapter (tokens keep base_out); seg_rank [n_seg] in 1..LORA_MAX_RANK where slot >= 0.
  *  - A non-empty segment with slot >= 0 and at least mfma_min_tokens tokens is cut into
@@ -253,9 +256,8 @@ typedef struct {
  *    such segments are pooled per slot (slots ascending, tokens ascending); a pool of at
  *    least mfma_min_tokens tokens is cut into tiles too, any other is one group.
  *    mfma_min_tokens = 0 turns tiles off (everything is pooled into groups).
- *  - A group is worked on in token batches: runs of up to LORA_GEMV_BATCH consecutive entries of
- *    its part of tok_list.  gs_items: per batch one item per 4 rank rows.  ge_items: per batch,
- *    with rs = rank rounded up to 8 and Nc = 64 * max(1, 128 / rs), items (0,Nc), (Nc,Nc), ... < 1024.
+ * How the kernels cut tiles and groups into blocks and wavefronts is not part of this contract
+ * (lora_plan_dump shows it for a plan).
  * All segments that name one slot must carry the same rank (else LORA_E_INVAL).
  * Arrays in *out are malloc'ed; free them with lora_worklists_free. */
 int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot, const int32_t *seg_rank,
@@ -279,9 +281,36 @@ typedef struct {
 } lora_plan_info_t;
 int lora_plan_info(const lora_plan_t *p, lora_plan_info_t *out);
 
+/* For tests and tools: the units of work the kernels will execute for a plan on projection `proj`,
+ * decoded from the very buffer the kernels read (the device copy, fetched back with a blocking
+ * copy; the staged host copy for a LORA_CACHE_HOST_ONLY cache) by the routines the kernels
+ * themselves decode their work items with.  The slot/segment indexing is correct when:
+ * the TILE units and the tokens of the GEMV units partition the batch's tokens that have an
+ * adapter; every unit names the slot and rank of its tokens' segments; for every GEMV token the
+ * SHRINK units cover rank rows [0, rank) exactly once and the EXPAND units cover output columns
+ * [0, h_out) exactly once; the LINEAR_ROWS units (bf16 caches: the row tiles of lora_linear_plan)
+ * cover every token of the batch exactly once.
+ * Writes at most cap_units units and cap_toks tokens; *n_units and *n_toks return the full counts
+ * (call with zero capacities to size the arrays). */
+enum { LORA_UNIT_TILE = 0, LORA_UNIT_GEMV_SHRINK = 1, LORA_UNIT_GEMV_EXPAND = 2, LORA_UNIT_LINEAR_ROWS = 3 };
+typedef struct {
+    int32_t kind;
+    int32_t tok_off, n_tok; /* the unit's tokens: toks[tok_off .. tok_off + n_tok) */
+    int32_t slot, rank;     /* slot found back from the storage row the kernels address; -1, 0: rows without adapter */
+    int32_t lo, hi;         /* GEMV_SHRINK: rank rows [lo, hi); GEMV_EXPAND: output columns [lo, hi); else 0, 0 */
+    int32_t where;          /* TILE: the XCD share (0..7) whose blocks run its shrink; GEMV_SHRINK: position in launch
+                               order; LINEAR_ROWS: 2 = a tile, 1 = rows of GEMV tokens, 0 = rows without adapter */
+    float alpha;            /* the cache entry's own factor as the kernels will apply it */
+} lora_plan_unit_t;
+int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_plan_unit_t *units, int32_t cap_units,
+                   int32_t *n_units, int32_t *toks, int32_t cap_toks, int32_t *n_toks);
+
 /* base_out[t] += scale*alpha*(x[t].A).B for the planned batch; x [T][h_in] and base_out
  * [T][h_out] are device, row-major, contiguous, element type cfg.dtype.  Asynchronous on
- * `stream`.  LORA_E_STATE if a named slot has no data for (layer, proj). */
+ * `stream`, which need not be the stream the plan was created on (the apply waits for the plan's
+ * upload).  LORA_E_STATE if a named slot has no data for (layer, proj).  All checks happen before
+ * the first launch.  If the runtime then refuses a launch (LORA_E_HIP), the launches before it stay
+ * enqueued and the base_out of this call is unspecified; cache and plan remain usable. */
 int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
                     void *base_out, float scale, void *stream);
 
@@ -341,7 +370,9 @@ int lora_cache_read_timing(lora_cache_t *c, double ms[LORA_K_COUNT], int64_t lau
 /* Blocks until `stream` is idle, then reports whether any kernel of this cache gave up a
  * bounded wait since the last call (*fault = 1; the outputs of that apply are then invalid)
  * and clears the flag.  The fused GEMV launch is the only kernel that waits; with a working
- * device the flag never rises. */
+ * device the flag never rises.  The flag lives in pinned host memory that the kernel writes
+ * directly, so applies also see it without any synchronisation: once it is up they return
+ * LORA_E_FAULT until this call has cleared it. */
 int lora_cache_check_fault(lora_cache_t *c, void *stream, int32_t *fault);
 
 const char *lora_strerror(int status);

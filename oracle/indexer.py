@@ -1,8 +1,9 @@
 """CPU ORACLE (test infrastructure, not part of the product): segment/slot indexer.
 
 Restates, with the dumbest loops available, the integer work the GPU library
-does before it launches anything: which cache slot and rank every token uses,
-and the canonical work lists derived from that.  The GPU library's indexer is
+does before it launches anything: which cache slot and rank every token uses
+(`token_map`), and which tokens go to the tile path and which to the GEMV path
+under the library's stated threshold rule (`index`).  The GPU library's indexer is
 written separately (C++, different algorithm); tests demand exact equality.
 
 The batch structure follows the paper: the scheduler re-forms the batch on
@@ -24,12 +25,11 @@ Canonical work lists (the library's contract for `lora_index`):
 * `tok_list` = tokens of all tiles (long-segment tiles first, then gathered
   tiles), then tokens of all groups.  A tile or group names its tokens as
   (`tok_off`, `n_tok`) into `tok_list`.
-* A group is worked on in *token batches*: runs of up to 4 consecutive entries
-  of its part of `tok_list`.  Shrink items: per batch, one per block of 4 rank
-  rows, (j0, n_rows).  Expand items: per batch, with rs = rank rounded up to a
-  multiple of 8 and Nc = 64 * max(1, 128 // rs) columns per item, one item per
-  Nc columns of a 1024-column super-chunk: (col_off, n_cols) for col_off = 0,
-  Nc, ... < 1024.  Items name their batch as (`tok_off`, `n_tok` <= 4).
+
+How the kernels cut a tile or a group into blocks, wavefronts, rank rows and
+column runs is their own business and no part of this contract; the tests check
+those work lists through properties (every token, rank row and output column
+covered exactly once, with the slot and rank `token_map` gives).
 """
 from __future__ import annotations
 
@@ -98,27 +98,8 @@ def index(
         groups.append((len(tok_list), len(toks), slot, rank, 0, 0))
         tok_list.extend(toks)
 
-    gs_items: List[Item] = []
-    ge_items: List[Item] = []
-    for (off, n, slot, rank, _, _) in groups:
-        for b0 in range(0, n, 4):
-            bn = min(4, n - b0)
-            j0 = 0
-            while j0 < rank:
-                gs_items.append((off + b0, bn, slot, rank, j0, min(4, rank - j0)))
-                j0 += 4
-        rs = (rank + 7) // 8 * 8
-        nc = 64 * max(1, 128 // rs)
-        for b0 in range(0, n, 4):
-            bn = min(4, n - b0)
-            c = 0
-            while c < 1024:
-                ge_items.append((off + b0, bn, slot, rank, c, nc))
-                c += nc
     return {
         "tok_list": tok_list,
         "tiles": tiles,
         "groups": groups,
-        "gs_items": gs_items,
-        "ge_items": ge_items,
     }

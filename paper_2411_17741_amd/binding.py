@@ -16,9 +16,9 @@ from typing import Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblora_cache.so")
+LIB_PATH = os.environ.get("LORA_CACHE_LIB") or os.path.join(_HERE, "liblora_cache.so")  # the variable names another build of the same library
 
-LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND = 0, -1, -2, -3, -4, -5
+LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND, LORA_E_FAULT = 0, -1, -2, -3, -4, -5, -6
 LORA_F32, LORA_BF16 = 0, 1
 LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
 LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV, LORA_CACHE_DIRECT_FILL = 1, 2, 4, 8
@@ -82,10 +82,16 @@ class lora_fill_part_t(ctypes.Structure):
 
 class lora_worklists_t(ctypes.Structure):
     _fields_ = [
-        ("n_tok_list", c_int32), ("n_tiles", c_int32), ("n_groups", c_int32), ("n_gs_items", c_int32), ("n_ge_items", c_int32),
+        ("n_tok_list", c_int32), ("n_tiles", c_int32), ("n_groups", c_int32),
         ("tok_list", POINTER(c_int32)), ("tiles", POINTER(lora_item_t)), ("groups", POINTER(lora_item_t)),
-        ("gs_items", POINTER(lora_item_t)), ("ge_items", POINTER(lora_item_t)),
     ]
+
+
+LORA_UNIT_TILE, LORA_UNIT_GEMV_SHRINK, LORA_UNIT_GEMV_EXPAND, LORA_UNIT_LINEAR_ROWS = 0, 1, 2, 3
+
+
+class lora_plan_unit_t(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("kind", "tok_off", "n_tok", "slot", "rank", "lo", "hi", "where")] + [("alpha", c_float)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -107,6 +113,7 @@ _SIGS = {
     "lora_cache_slot_ref": (c_int, [c_void_p, c_int32, c_int32]),
     "lora_cache_lookup": (c_int, [c_void_p, c_int64, _i32p, _i32p]),
     "lora_cache_slot_info": (c_int, [c_void_p, c_int32, POINTER(lora_slot_info_t)]),
+    "lora_cache_slot_state": (c_int, [c_void_p, c_int32, _i32p]),
     "lora_cache_find_free_slot": (c_int, [c_void_p, c_int32, _i32p]),
     "lora_cache_stats": (c_int, [c_void_p, POINTER(lora_cache_stats_t)]),
     "lora_cache_set_policy": (c_int, [c_void_p, POINTER(lora_policy_t)]),
@@ -122,6 +129,7 @@ _SIGS = {
     "lora_plan_create": (c_int, [c_void_p, c_int32, _i32p, _i32p, _i32p, c_int32, c_void_p, POINTER(c_void_p)]),
     "lora_plan_destroy": (c_int, [c_void_p, c_void_p]),
     "lora_plan_info": (c_int, [c_void_p, POINTER(lora_plan_info_t)]),
+    "lora_plan_dump": (c_int, [c_void_p, c_void_p, c_int32, POINTER(lora_plan_unit_t), c_int32, _i32p, _i32p, c_int32, _i32p]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
     "lora_linear_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_float, c_void_p, c_size_t, c_void_p]),
@@ -244,6 +252,13 @@ def lora_cache_slot_info(cache, slot: int):
     info = lora_slot_info_t()
     rc = _lib.lora_cache_slot_info(cache, slot, ctypes.byref(info))
     return rc, info
+
+
+def lora_cache_slot_state(cache, slot: int):
+    """-> (status, state)"""
+    st = c_int32(-1)
+    rc = _lib.lora_cache_slot_state(cache, slot, ctypes.byref(st))
+    return rc, st.value
 
 
 def lora_cache_find_free_slot(cache, rank: int):
@@ -408,16 +423,13 @@ def lora_index(T: int, seg_offsets, seg_slot, seg_rank, mfma_min_tokens: int, co
     if rc != LORA_OK:
         return rc, None
     if counts_only:
-        out = {"n_tok_list": w.n_tok_list, "n_tiles": w.n_tiles, "n_groups": w.n_groups, "n_gs_items": w.n_gs_items,
-               "n_ge_items": w.n_ge_items}
+        out = {"n_tok_list": w.n_tok_list, "n_tiles": w.n_tiles, "n_groups": w.n_groups}
         _lib.lora_worklists_free(ctypes.byref(w))
         return rc, out
     out = {
         "tok_list": [w.tok_list[i] for i in range(w.n_tok_list)],
         "tiles": _items(w.tiles, w.n_tiles),
         "groups": _items(w.groups, w.n_groups),
-        "gs_items": _items(w.gs_items, w.n_gs_items),
-        "ge_items": _items(w.ge_items, w.n_ge_items),
     }
     _lib.lora_worklists_free(ctypes.byref(w))
     return rc, out
@@ -440,6 +452,21 @@ def lora_plan_info(plan):
     info = lora_plan_info_t()
     rc = _lib.lora_plan_info(plan, ctypes.byref(info))
     return rc, info
+
+
+def lora_plan_dump(cache, plan, proj: int):
+    """-> (status, units as a numpy record array with the fields of lora_plan_unit_t, tokens as an int32 array)"""
+    nu, nt = c_int32(0), c_int32(0)
+    rc = _lib.lora_plan_dump(cache, plan, proj, None, 0, ctypes.byref(nu), None, 0, ctypes.byref(nt))
+    if rc != LORA_OK:
+        return rc, None, None
+    units = (lora_plan_unit_t * max(1, nu.value))()
+    toks = np.zeros(max(1, nt.value), np.int32)
+    rc = _lib.lora_plan_dump(cache, plan, proj, units, nu.value, ctypes.byref(nu), _ptr(toks), nt.value, ctypes.byref(nt))
+    if rc != LORA_OK:
+        return rc, None, None
+    rec = np.frombuffer(units, dtype=np.dtype([(n, np.int32) for n in ("kind", "tok_off", "n_tok", "slot", "rank", "lo", "hi", "where")] + [("alpha", np.float32)]), count=nu.value).copy()
+    return rc, rec, toks[: nt.value].copy()
 
 
 def lora_apply_plan(cache, plan, layer: int, proj: int, x: int, base_out: int, scale: float, stream: int = 0) -> int:

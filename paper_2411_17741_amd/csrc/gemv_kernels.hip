@@ -24,7 +24,7 @@
 
 namespace lora {
 
-constexpr int TB = LORA_GEMV_BATCH;
+constexpr int TB = GEMV_BATCH;
 constexpr int GEMV_DP_ROW = 256 + 4;  // floats per token row of an expand wavefront's LDS (widest unit, padded)
 
 // How the two phases hand over v.
@@ -60,7 +60,7 @@ __device__ __forceinline__ bool fetch_v(const Handover &ho, const unsigned long 
         }
         __builtin_amdgcn_s_sleep(2);
     }
-    if ((threadIdx.x & 63) == 0) __hip_atomic_store(ho.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((threadIdx.x & 63) == 0) __hip_atomic_store(ho.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // pinned host memory
     return false;
 }
 
@@ -84,7 +84,8 @@ __device__ __forceinline__ void gemv_shrink_partial(const ApplyArgs &a, const Ge
 {
     constexpr int U = shrink_u<E>();
     const int lane = threadIdx.x & 63;
-    const int j0 = it.a & 0xff, n_rows = it.a >> 8;
+    int j0, n_rows;
+    gemv_shrink_rows(it, j0, n_rows);
     const E *slab = reinterpret_cast<const E *>(a.proj_base + (int64_t)it.row * a.row_bytes);
     const E *arow[4], *xrow[NT];
 #pragma unroll
@@ -144,9 +145,11 @@ __device__ __forceinline__ void gemv_shrink_item(const ApplyArgs &a, const GemvI
     float val = 0.f;
     for (int q = 0; q < W; ++q) val += red[q][lane];
     const int t = lane >> 2, r = lane & 3;
-    if (t < NT && r < (it.a >> 8)) {
+    int j0, n_rows;
+    gemv_shrink_rows(it, j0, n_rows);
+    if (t < NT && r < n_rows) {
         const int tok = t == 0 ? it.tok[0] : (t == 1 ? it.tok[1] : (t == 2 ? it.tok[2] : it.tok[3]));
-        const size_t idx = (size_t)tok * a.v_stride + (it.a & 0xff) + r;
+        const size_t idx = (size_t)tok * a.v_stride + j0 + r;
         if (ho.vtag) publish_v(ho, idx, val);
         else a.v[idx] = val;
     }
@@ -439,10 +442,10 @@ __device__ __forceinline__ void gemv_expand_wave(const ApplyArgs &a, const GemvI
                                                  float (*vs)[GEMV_DP_ROW])
 {
     const int rs = rank_storage(it.rank);
-    const int n_cols = 64 * max(1, 128 / rs);
-    const int c0 = sc * 1024 + (it.a & 0xf) * 64;
-    if (c0 >= a.h_out) return;
-    const int c1 = min(min(c0 + n_cols, (sc + 1) * 1024), a.h_out);
+    const int n_cols = gemv_expand_width(it.rank);
+    int c0, c1;
+    gemv_expand_cols(it, sc, a.h_out, c0, c1);
+    if (c0 >= c1) return;
     const E *Bp = reinterpret_cast<const E *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     if constexpr (sizeof(E) == 2) {
         if (rs >= 32) {  // uniform over the wavefront
@@ -507,7 +510,7 @@ __global__ __launch_bounds__(256) void gemv_fused_kernel(ApplyArgs a, const Gemv
         if (item >= n_ge) return;
         GemvItem it = ge[item];
 #pragma unroll
-        for (int t = 0; t < LORA_GEMV_BATCH; ++t) it.tok[t] = __builtin_amdgcn_readfirstlane(it.tok[t]);
+        for (int t = 0; t < GEMV_BATCH; ++t) it.tok[t] = __builtin_amdgcn_readfirstlane(it.tok[t]);
         it.row = __builtin_amdgcn_readfirstlane(it.row);
         it.rank = __builtin_amdgcn_readfirstlane(it.rank);
         it.a = __builtin_amdgcn_readfirstlane(it.a);
@@ -538,7 +541,7 @@ hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *ite
                               const KernelTimer *tm)
 {
     if (n_items <= 0) return hipSuccess;
-    const dim3 grid(n_items, (a.h_out + 1023) / 1024);
+    const dim3 grid(n_items, (a.h_out + GEMV_SUPER_COLS - 1) / GEMV_SUPER_COLS);
     if (dtype == LORA_BF16) launch_k(tm, LORA_K_GEMV_EXPAND, gemv_expand_kernel<__bf16>, grid, dim3(64), st, a, items);
     else launch_k(tm, LORA_K_GEMV_EXPAND, gemv_expand_kernel<float>, grid, dim3(64), st, a, items);
     return hipGetLastError();
@@ -548,7 +551,7 @@ hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, 
                              unsigned long long *vtag, uint32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm)
 {
     if (n_gs <= 0 || n_ge <= 0) return hipSuccess;
-    const int n_super = (a.h_out + 1023) / 1024;
+    const int n_super = (a.h_out + GEMV_SUPER_COLS - 1) / GEMV_SUPER_COLS;
     const int n_expand_blocks = (n_ge * n_super + 3) / 4;
     const dim3 grid(n_gs + n_expand_blocks), block(256);
     const Handover ho{vtag, epoch, fault};

@@ -51,7 +51,7 @@ extern "C" int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *
 
     const int32_t TM = LORA_TILE_TOKENS;
     std::vector<int32_t> tile_tok, group_tok;
-    std::vector<lora_item_t> tiles, groups, gs, ge;
+    std::vector<lora_item_t> tiles, groups;
     std::vector<ShortSeg> shorts;
 
     // long segments become runs of tiles straight away; the rest is bucketed by slot
@@ -93,35 +93,16 @@ extern "C" int lora_index(int32_t T, const int32_t *seg_offsets, const int32_t *
     }
 
     const int32_t n_tile_tok = (int32_t)tile_tok.size();
-    for (auto &gr : groups) {
-        gr.tok_off += n_tile_tok;
-        const int32_t rs = lora::rank_storage(gr.rank);
-        const int32_t nc = 64 * std::max(1, 128 / rs);
-        // token batches of up to LORA_GEMV_BATCH tokens: every batch gets its own items so that
-        // batches run side by side instead of one after the other
-        for (int32_t b0 = 0; b0 < gr.n_tok; b0 += LORA_GEMV_BATCH) {
-            const int32_t bn = std::min<int32_t>(LORA_GEMV_BATCH, gr.n_tok - b0);
-            for (int32_t j0 = 0; j0 < gr.rank; j0 += 4)
-                gs.push_back(make_item(gr.tok_off + b0, bn, gr.slot, gr.rank, j0, std::min(4, gr.rank - j0)));
-        }
-        for (int32_t b0 = 0; b0 < gr.n_tok; b0 += LORA_GEMV_BATCH) {
-            const int32_t bn = std::min<int32_t>(LORA_GEMV_BATCH, gr.n_tok - b0);
-            for (int32_t c = 0; c < 1024; c += nc) ge.push_back(make_item(gr.tok_off + b0, bn, gr.slot, gr.rank, c, nc));
-        }
-    }
+    for (auto &gr : groups) gr.tok_off += n_tile_tok;
     tile_tok.insert(tile_tok.end(), group_tok.begin(), group_tok.end());
 
     out->n_tok_list = (int32_t)tile_tok.size();
     out->n_tiles = (int32_t)tiles.size();
     out->n_groups = (int32_t)groups.size();
-    out->n_gs_items = (int32_t)gs.size();
-    out->n_ge_items = (int32_t)ge.size();
     out->tok_list = dup(tile_tok);
     out->tiles = dup(tiles);
     out->groups = dup(groups);
-    out->gs_items = dup(gs);
-    out->ge_items = dup(ge);
-    if (!out->tok_list || !out->tiles || !out->groups || !out->gs_items || !out->ge_items) {
+    if (!out->tok_list || !out->tiles || !out->groups) {
         lora_worklists_free(out);
         return LORA_E_NOMEM;
     }
@@ -134,7 +115,5 @@ extern "C" void lora_worklists_free(lora_worklists_t *w)
     std::free(w->tok_list);
     std::free(w->tiles);
     std::free(w->groups);
-    std::free(w->gs_items);
-    std::free(w->ge_items);
     std::memset(w, 0, sizeof(*w));
 }

@@ -48,7 +48,7 @@ static_assert(8 * 128 * 128 <= 2 * L_STAGE && LBM * SV_ROW <= 2 * L_STAGE, "s.v 
 
 __device__ __forceinline__ int row_tile_token(const int32_t *tok_list, const DevItem &it, int ti)
 {
-    return (it.consecutive || ti == 0) ? it.tok0 + ti : tok_list[it.tok_off + ti];
+    return tile_token_of(tok_list, it, ti);
 }
 
 __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __bf16 *__restrict__ Wt,

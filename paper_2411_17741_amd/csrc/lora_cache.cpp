@@ -72,7 +72,7 @@ struct lora_plan {
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
     int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
     int32_t mfma_min_used = 0;  // the threshold the work lists were made with
-    size_t off_tiles = 0, off_gs = 0, off_ge = 0;
+    size_t off_tiles = 0, off_gs = 0, off_ge = 0, bytes = 0;
     // for lora_linear_plan: every token of the batch in row tiles -- the tiles above, then runs of up
     // to 64 of the other tokens (rank 0) -- over a token list of its own
     size_t off_lin_tok = 0, off_lin_tiles = 0;
@@ -115,6 +115,10 @@ struct lora_cache {
     int64_t apply_seq = 0;
     hipEvent_t apply_ev[N_APPLY_EVENTS] = {};
     int64_t apply_ev_seq[N_APPLY_EVENTS] = {};
+    std::unordered_map<hipStream_t, hipEvent_t> stream_fence;  // per stream that ran applies: an event of its own, recorded with every fence
+    // raised by a kernel that gave up a bounded wait: one word of pinned host memory that the kernels
+    // write through its device address, so the host sees it without a synchronisation
+    int32_t *fault_host = nullptr, *fault_dev = nullptr;
 
     lora_cache_stats_t stats = {};
     lora_policy_t policy = {0.45, 0.10, 0.45, 0};  // section 4.2's F, R, S
@@ -195,11 +199,11 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
         max_part = std::max(max_part, (size_t)c.class_rank[n_cls - 1] * width * c.esize);
     }
     c.layer_stride = off;
-    c.v_stride = (c.class_rank[n_cls - 1] + 31) / 32 * 32;
+    c.v_stride = LORA_MAX_RANK;  // the GEMV expand reads whole rows of 128 entries (masked past the rank)
 
     const size_t max_tiles = (size_t)c.max_tokens / LORA_TILE_TOKENS + 2 * (size_t)c.max_segments + 2;
     // GEMV items: per token batch up to 32 shrink + 16 expand items; batches <= groups + tokens/4
-    const size_t max_batches = (size_t)c.max_segments + (size_t)c.max_tokens / LORA_GEMV_BATCH + 1;
+    const size_t max_batches = (size_t)c.max_segments + (size_t)c.max_tokens / lora::GEMV_BATCH + 1;
     const size_t max_items = max_tiles + max_batches * (LORA_MAX_RANK / 4 + 16);
     c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) +
                  align_up(sizeof(int32_t) * max_batches) + 4 * ALIGN +
@@ -369,7 +373,7 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         }
         double extra_bytes = 0;
         for (const auto &kv : of_slot)
-            extra_bytes += (double)((kv.second.first + LORA_GEMV_BATCH - 1) / LORA_GEMV_BATCH) * kv.second.second * mean_width * c.esize;
+            extra_bytes += (double)((kv.second.first + lora::GEMV_BATCH - 1) / lora::GEMV_BATCH) * kv.second.second * mean_width * c.esize;
         const double gemv_us = extra_bytes / TILE_PATH_L2_BYTES_PER_US;
         lora_worklists_free(&w);
         p.mfma_min_used = gemv_us < TILE_PATH_FIXED_US ? 0 : LORA_MFMA_MIN_TOKENS_MIXED;
@@ -434,31 +438,45 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         }
         p.xcd_tile[8] = w.n_tiles;
     }
-    auto stamp_gemv = [&](lora_item_t *items, int n, bool expand) {
-        for (int i = 0; i < n; ++i) {
-            const Slot &s = c.slots[items[i].slot];
-            lora::GemvItem d;
-            for (int t = 0; t < LORA_GEMV_BATCH; ++t)
-                d.tok[t] = t < items[i].n_tok ? w.tok_list[items[i].tok_off + t] : -1;
-            d.row = c.slot_row[items[i].slot];
-            d.rank = items[i].rank;
-            d.a = expand ? items[i].a / 64 : (items[i].a | (items[i].b << 8));
-            d.alpha = s.alpha;
-            std::memcpy(&items[i], &d, sizeof(d));
-        }
-    };
+    // GEMV work items.  A group is worked on in token batches (runs of up to GEMV_BATCH entries of its
+    // part of tok_list), every batch with items of its own so that batches run side by side: per batch
+    // one shrink item per GEMV_SHRINK_ROWS rank rows, and one expand item per run of
+    // gemv_expand_width(rank) columns of a super-chunk (the launch repeats it for every super-chunk of
+    // the projection).
+    std::vector<lora::GemvItem> gs, ge;
+    for (int i = 0; i < w.n_groups; ++i) {
+        const lora_item_t &gr = w.groups[i];
+        lora::GemvItem d;
+        d.row = c.slot_row[gr.slot];
+        d.rank = gr.rank;
+        d.alpha = c.slots[gr.slot].alpha;
+        const int32_t nc = lora::gemv_expand_width(gr.rank);
+        for (int pass = 0; pass < 2; ++pass)
+            for (int32_t b0 = 0; b0 < gr.n_tok; b0 += lora::GEMV_BATCH) {
+                for (int t = 0; t < lora::GEMV_BATCH; ++t) d.tok[t] = b0 + t < gr.n_tok ? w.tok_list[gr.tok_off + b0 + t] : -1;
+                if (pass == 0) {
+                    for (int32_t j0 = 0; j0 < gr.rank; j0 += lora::GEMV_SHRINK_ROWS) {
+                        d.a = lora::gemv_pack_shrink(j0, std::min(lora::GEMV_SHRINK_ROWS, gr.rank - j0));
+                        gs.push_back(d);
+                    }
+                } else {
+                    for (int32_t col = 0; col < lora::GEMV_SUPER_COLS; col += nc) {
+                        d.a = lora::gemv_pack_expand(col);
+                        ge.push_back(d);
+                    }
+                }
+            }
+    }
     stamp(w.tiles, w.n_tiles);
-    stamp_gemv(w.gs_items, w.n_gs_items, false);
-    stamp_gemv(w.ge_items, w.n_ge_items, true);
 
     p.T = T;
     p.n_tok_list = w.n_tok_list;
     p.n_tiles = w.n_tiles;
-    p.n_gs = w.n_gs_items;
-    p.n_ge = w.n_ge_items;
+    p.n_gs = (int32_t)gs.size();
+    p.n_ge = (int32_t)ge.size();
     p.off_tiles = align_up(sizeof(int32_t) * (size_t)w.n_tok_list);
     p.off_gs = p.off_tiles + align_up(sizeof(lora_item_t) * (size_t)w.n_tiles);
-    p.off_ge = p.off_gs + align_up(sizeof(lora_item_t) * (size_t)w.n_gs_items);
+    p.off_ge = p.off_gs + align_up(sizeof(lora::GemvItem) * gs.size());
     // row tiles of the whole batch (bf16 caches: lora_linear_plan): the tiles; then runs of up to 64
     // of the tokens of the GEMV groups (marked a = 1: their output rows carry the adapter term when
     // the base product is added); then runs of the tokens that name no adapter.  The token list is
@@ -490,55 +508,71 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         plain_runs(w.n_tok_list, (int32_t)lin_tok.size(), 0);
     }
     p.n_lin_tiles = (int32_t)lin_tiles.size();
-    p.off_lin_tok = p.off_ge + align_up(sizeof(lora_item_t) * (size_t)w.n_ge_items);
+    p.off_lin_tok = p.off_ge + align_up(sizeof(lora::GemvItem) * ge.size());
     p.off_lin_tiles = p.off_lin_tok + align_up(sizeof(int32_t) * lin_tok.size());
     const size_t bytes = p.off_lin_tiles + align_up(sizeof(lora::DevItem) * lin_tiles.size());
     if (bytes > c.plan_cap) {
         lora_worklists_free(&w);
         return LORA_E_NOMEM;
     }
-    if (!c.host_only) {
-        // A captured upload would re-read the pinned copy on every replay; plans are made
-        // outside of captures.
-        if (is_capturing(st)) {
+    // A captured upload would re-read the staged copy on every replay; plans are made outside of captures.
+    if (!c.host_only && is_capturing(st)) {
+        lora_worklists_free(&w);
+        return LORA_E_STATE;
+    }
+    // the staged copy may still be the source of an earlier upload; the device copy may still be read
+    // by earlier applies
+    if (p.upload_pending) {
+        const hipError_t e = hipEventSynchronize(p.ev_upload);
+        if (e != hipSuccess) {
             lora_worklists_free(&w);
-            return LORA_E_STATE;
+            g_last_hip = (int)e;
+            return LORA_E_HIP;
         }
-        // the pinned copy may still be the source of an earlier upload; the device copy may
-        // still be read by earlier applies
-        if (p.upload_pending) {
-            HIP_TRY(hipEventSynchronize(p.ev_upload));
-            p.upload_pending = false;
+        p.upload_pending = false;
+    }
+    std::memcpy(p.pinned, w.tok_list, sizeof(int32_t) * (size_t)w.n_tok_list);
+    std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
+    lora_worklists_free(&w);
+    {
+        // One block works on one shrink item and block b runs on XCD b % 8, each XCD behind its own
+        // L2.  The items of a token batch (4 slab rows each, all reading the batch's x rows) follow
+        // each other in the list: XCD j gets a run of consecutive items, the i-th of them as block
+        // 8i + j, so that a batch's x rows are fetched from memory by one XCD, not by all eight.
+        lora::GemvItem *dst = reinterpret_cast<lora::GemvItem *>(p.pinned + p.off_gs);
+        const int n = (int)gs.size();
+        for (int b = 0; b < n; ++b) {
+            const int j = b & 7;
+            dst[b] = gs[j * (n >> 3) + std::min(j, n & 7) + (b >> 3)];
         }
+    }
+    if (!ge.empty()) std::memcpy(p.pinned + p.off_ge, ge.data(), sizeof(lora::GemvItem) * ge.size());
+    if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
+    if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
+    p.bytes = bytes;
+    if (!c.host_only && bytes) {
         if (p.use_pending) {
             HIP_TRY(hipStreamWaitEvent(st, p.ev_last_use, 0));
             p.use_pending = false;
         }
-        std::memcpy(p.pinned, w.tok_list, sizeof(int32_t) * (size_t)w.n_tok_list);
-        std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
-        {
-            // One block works on one shrink item and block b runs on XCD b % 8, each XCD behind its own
-            // L2.  The items of a token batch (4 slab rows each, all reading the batch's x rows) follow
-            // each other in the list: XCD j gets a run of consecutive items, the i-th of them as block
-            // 8i + j, so that a batch's x rows are fetched from memory by one XCD, not by all eight.
-            lora_item_t *dst = reinterpret_cast<lora_item_t *>(p.pinned + p.off_gs);
-            const int n = w.n_gs_items;
-            for (int b = 0; b < n; ++b) {
-                const int j = b & 7;
-                dst[b] = w.gs_items[j * (n >> 3) + std::min(j, n & 7) + (b >> 3)];
-            }
-        }
-        std::memcpy(p.pinned + p.off_ge, w.ge_items, sizeof(lora_item_t) * (size_t)w.n_ge_items);
-        if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
-        if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
-        lora_worklists_free(&w);
-        if (bytes) {
-            HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
-            HIP_TRY(hipEventRecord(p.ev_upload, st));
-            p.upload_pending = true;
-        }
+        HIP_TRY(hipMemcpyAsync(p.dev, p.pinned, bytes, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipEventRecord(p.ev_upload, st));
+        p.upload_pending = true;
+    }
+    return LORA_OK;
+}
+
+// Makes `st` wait for every apply enqueued so far that named the slot.  The fence of the call that
+// used it last sits in a ring; once that entry has been taken over by a later call, the latest fence
+// of every stream that ever ran applies stands in (stream order covers the older ones).
+int wait_for_applies(lora_cache &c, const Slot &s, hipStream_t st)
+{
+    if (!c.fencing || s.last_used <= 0) return LORA_OK;
+    const int e = (int)(s.last_used % N_APPLY_EVENTS);
+    if (c.apply_ev_seq[e] == s.last_used) {
+        HIP_TRY(hipStreamWaitEvent(st, c.apply_ev[e], 0));
     } else {
-        lora_worklists_free(&w);
+        for (const auto &kv : c.stream_fence) HIP_TRY(hipStreamWaitEvent(st, kv.second, 0));
     }
     return LORA_OK;
 }
@@ -594,6 +628,7 @@ const char *lora_strerror(int status)
         case LORA_E_NOMEM: return "out of pool / plan / host memory";
         case LORA_E_HIP: return "HIP call failed";
         case LORA_E_NOTFOUND: return "adapter not cached";
+        case LORA_E_FAULT: return "a kernel of an earlier apply gave up a bounded wait";
         default: return "unknown status";
     }
 }
@@ -630,6 +665,14 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
     c->plans.resize(c->n_user_plans + N_INTERNAL_PLANS);
     for (size_t i = 0; i < c->plans.size(); ++i) c->plans[i].internal = (int)i >= c->n_user_plans;
     if (c->host_only) {
+        // plans are still built (and can be inspected with lora_plan_dump), only never uploaded
+        for (auto &p : c->plans) {
+            p.pinned = static_cast<char *>(std::malloc(c->plan_cap));
+            if (!p.pinned) {
+                lora_cache_destroy(c);
+                return LORA_E_NOMEM;
+            }
+        }
         *out = c;
         return LORA_OK;
     }
@@ -646,7 +689,9 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
 
     int rc = LORA_OK;
     // the tagged words must not carry a future launch number by accident: numbers start at 1
-    if (hipMemset(c->pool + c->off_fault, 0, ALIGN) != hipSuccess ||
+    if (hipHostMalloc(reinterpret_cast<void **>(&c->fault_host), 64, hipHostMallocMapped) != hipSuccess ||
+        hipHostGetDevicePointer(reinterpret_cast<void **>(&c->fault_dev), c->fault_host, 0) != hipSuccess ||
+        (*c->fault_host = 0, false) ||
         (c->fused_gemv &&
          hipMemset(c->pool + c->off_vtag, 0, sizeof(uint64_t) * (size_t)c->max_tokens * c->v_stride) != hipSuccess)) {
         g_last_hip = (int)hipGetLastError();
@@ -682,7 +727,9 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
 int lora_cache_destroy(lora_cache_t *c)
 {
     if (!c) return LORA_E_INVAL;
-    if (!c->host_only) {
+    if (c->host_only) {
+        for (auto &p : c->plans) std::free(p.pinned);
+    } else {
         for (auto &p : c->plans) {
             if (p.pinned) (void)hipHostFree(p.pinned);
             if (p.ev_upload) (void)hipEventDestroy(p.ev_upload);
@@ -692,6 +739,9 @@ int lora_cache_destroy(lora_cache_t *c)
             if (s.ev) (void)hipEventDestroy(s.ev);
         for (auto &e : c->apply_ev)
             if (e) (void)hipEventDestroy(e);
+        for (auto &kv : c->stream_fence)
+            if (kv.second) (void)hipEventDestroy(kv.second);
+        if (c->fault_host) (void)hipHostFree(c->fault_host);
         for (auto &s : c->slots)
             if (s.fill_ev) (void)hipEventDestroy(s.fill_ev);
         for (auto &t : c->timed) {
@@ -727,6 +777,7 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
     if (!c->host_only && (!host_A || !host_B)) return LORA_E_INVAL;
     const size_t part = (size_t)layer * c->proj.size() + proj;
 
+    const bool was_bound = s.bound;
     if (s.bound) {
         if (s.adapter_id != adapter_id || s.rank != rank || s.alpha != alpha) return LORA_E_STATE;
         if (s.part[part] && s.refcount > 0) return LORA_E_STATE;  // would overwrite data in use
@@ -746,10 +797,20 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
     const size_t bytes_a = (size_t)rank * h_in * c->esize, bytes_b = (size_t)rank * h_out * c->esize;
     if (!c->host_only) {
         hipStream_t st = static_cast<hipStream_t>(fill_stream);
-        if (c->fencing && s.last_used > 0) {
-            // applies enqueued earlier may still read this slab
-            HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
-        }
+        // a HIP failure below must not leave a bound, empty entry behind
+        struct Rollback {
+            lora_cache *c;
+            Slot *s;
+            bool armed;
+            ~Rollback()
+            {
+                if (armed) unbind(*c, *s);
+            }
+        } rollback{c, &s, !was_bound};
+        // applies enqueued earlier may still read this slab; an earlier fill of the slot (of the entry it
+        // held before, or of the same part) may still be writing it on another stream
+        if (int rc = wait_for_applies(*c, s, st)) return rc;
+        if (s.fill_pending) HIP_TRY(hipStreamWaitEvent(st, s.fill_ev, 0));
         char *slab = slab_ptr(*c, layer, proj, slot);
         const void *dev_A = c->direct_fill ? device_view_of_pinned(host_A) : nullptr;
         const void *dev_B = c->direct_fill ? device_view_of_pinned(host_B) : nullptr;
@@ -774,6 +835,7 @@ int lora_cache_fill_slot(lora_cache_t *c, int32_t slot, int64_t adapter_id, int3
         if (!s.fill_ev) HIP_TRY(hipEventCreateWithFlags(&s.fill_ev, hipEventDisableTiming));
         HIP_TRY(hipEventRecord(s.fill_ev, st));
         s.fill_pending = true;
+        rollback.armed = false;
     }
     if (!s.part[part]) {
         s.part[part] = 1;
@@ -823,6 +885,7 @@ int lora_cache_fill_slot_parts(lora_cache_t *c, int32_t slot, int64_t adapter_id
         }
         return LORA_OK;
     }
+    const bool was_bound = s.bound;
     if (!s.bound) {
         s.bound = true;
         s.adapter_id = adapter_id;
@@ -833,7 +896,17 @@ int lora_cache_fill_slot_parts(lora_cache_t *c, int32_t slot, int64_t adapter_id
         c->id2slot[adapter_id] = slot;
     }
     hipStream_t st = static_cast<hipStream_t>(fill_stream);
-    if (c->fencing && s.last_used > 0) HIP_TRY(hipStreamWaitEvent(st, c->apply_ev[s.last_used % N_APPLY_EVENTS], 0));
+    struct Rollback {
+        lora_cache *c;
+        Slot *s;
+        bool armed;
+        ~Rollback()
+        {
+            if (armed) unbind(*c, *s);
+        }
+    } rollback{c, &s, !was_bound};
+    if (int rc = wait_for_applies(*c, s, st)) return rc;
+    if (s.fill_pending) HIP_TRY(hipStreamWaitEvent(st, s.fill_ev, 0));
     for (int32_t i0 = 0; i0 < n_parts; i0 += lora::REPACK_MAX_PARTS) {
         lora::RepackTable t;
         t.n = std::min<int32_t>(lora::REPACK_MAX_PARTS, n_parts - i0);
@@ -850,6 +923,7 @@ int lora_cache_fill_slot_parts(lora_cache_t *c, int32_t slot, int64_t adapter_id
     if (!s.fill_ev) HIP_TRY(hipEventCreateWithFlags(&s.fill_ev, hipEventDisableTiming));
     HIP_TRY(hipEventRecord(s.fill_ev, st));
     s.fill_pending = true;
+    rollback.armed = false;
     for (int32_t i = 0; i < n_parts; ++i) {
         const lora_fill_part_t &q = parts[i];
         const size_t part = (size_t)q.layer * c->proj.size() + q.proj;
@@ -910,6 +984,13 @@ int lora_cache_slot_info(lora_cache_t *c, int32_t slot, lora_slot_info_t *out)
     out->last_used = s.last_used;
     out->alpha = s.alpha;
     out->parts_filled = s.parts_filled;
+    return LORA_OK;
+}
+
+int lora_cache_slot_state(lora_cache_t *c, int32_t slot, int32_t *state)
+{
+    if (!c || !state || slot < 0 || slot >= c->n_slots) return LORA_E_INVAL;
+    *state = slot_state(*c, c->slots[slot]);
     return LORA_OK;
 }
 
@@ -1065,9 +1146,7 @@ int lora_cache_check_fault(lora_cache_t *c, void *stream, int32_t *fault)
     if (!c || !fault || c->host_only) return LORA_E_INVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(hipStreamSynchronize(st));
-    int32_t v = 0;
-    HIP_TRY(hipMemcpy(&v, c->pool + c->off_fault, sizeof(v), hipMemcpyDeviceToHost));
-    if (v) HIP_TRY(hipMemset(c->pool + c->off_fault, 0, sizeof(v)));
+    const int32_t v = __atomic_exchange_n(c->fault_host, 0, __ATOMIC_ACQ_REL);
     *fault = v ? 1 : 0;
     return LORA_OK;
 }
@@ -1144,8 +1223,92 @@ int lora_plan_info(const lora_plan_t *p, lora_plan_info_t *out)
     return LORA_OK;
 }
 
+int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_plan_unit_t *units, int32_t cap_units,
+                   int32_t *n_units, int32_t *toks, int32_t cap_toks, int32_t *n_toks)
+{
+    if (!c || !p || !p->in_use || !n_units || !n_toks || proj < 0 || proj >= (int32_t)c->proj.size() || cap_units < 0 ||
+        cap_toks < 0 || (cap_units > 0 && !units) || (cap_toks > 0 && !toks))
+        return LORA_E_INVAL;
+    // the bytes the kernels read
+    std::vector<char> copy;
+    const char *buf = p->pinned;
+    if (!c->host_only) {
+        copy.resize(p->bytes);
+        if (p->upload_pending) HIP_TRY(hipEventSynchronize(p->ev_upload));
+        if (p->bytes) HIP_TRY(hipMemcpy(copy.data(), p->dev, p->bytes, hipMemcpyDeviceToHost));
+        buf = copy.data();
+    }
+    const int32_t *tok_list = reinterpret_cast<const int32_t *>(buf);
+    const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(buf + p->off_tiles);
+    const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(buf + p->off_gs);
+    const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(buf + p->off_ge);
+    const int32_t *lin_tok = reinterpret_cast<const int32_t *>(buf + p->off_lin_tok);
+    const lora::DevItem *lin_tiles = reinterpret_cast<const lora::DevItem *>(buf + p->off_lin_tiles);
+
+    int32_t nu = 0, nt = 0;
+    auto slot_of_row = [&](int32_t row) -> int32_t {
+        auto it = std::upper_bound(c->slot_row.begin(), c->slot_row.end(), row);
+        return (int32_t)(it - c->slot_row.begin()) - 1;
+    };
+    auto put_tok = [&](int32_t t) {
+        if (nt < cap_toks) toks[nt] = t;
+        ++nt;
+    };
+    auto put_unit = [&](int32_t kind, int32_t tok_off, int32_t n_tok, int32_t row, int32_t rank, int32_t lo, int32_t hi,
+                        int32_t where, float alpha) {
+        if (nu < cap_units) units[nu] = lora_plan_unit_t{kind, tok_off, n_tok, row >= 0 ? slot_of_row(row) : -1, rank, lo, hi, where, alpha};
+        ++nu;
+    };
+    // tokens of a tile as the tile kernels find them: a run from tok0, or through the token list
+    auto tile_tokens = [&](const lora::DevItem &it, const int32_t *list) {
+        for (int32_t i = 0; i < it.n_tok; ++i) put_tok(lora::tile_token_of(list, it, i));
+    };
+    for (int32_t i = 0; i < p->n_tiles; ++i) {
+        int32_t xcd = 0;
+        while (xcd < 7 && i >= p->xcd_tile[xcd + 1]) ++xcd;
+        const int32_t off = nt;
+        tile_tokens(tiles[i], tok_list);
+        put_unit(LORA_UNIT_TILE, off, tiles[i].n_tok, tiles[i].row, tiles[i].rank, 0, 0, xcd, tiles[i].alpha);
+    }
+    auto gemv_tokens = [&](const lora::GemvItem &it) -> int32_t {
+        int32_t n = 0;
+        for (int t = 0; t < lora::GEMV_BATCH; ++t)
+            if (it.tok[t] >= 0) {
+                put_tok(it.tok[t]);
+                ++n;
+            }
+        return n;
+    };
+    for (int32_t i = 0; i < p->n_gs; ++i) {
+        int32_t j0, n;
+        lora::gemv_shrink_rows(gs[i], j0, n);
+        const int32_t off = nt, cnt = gemv_tokens(gs[i]);
+        put_unit(LORA_UNIT_GEMV_SHRINK, off, cnt, gs[i].row, gs[i].rank, j0, j0 + n, i, gs[i].alpha);
+    }
+    const int32_t h_out = c->proj[proj].h_out, n_super = (h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
+    for (int32_t i = 0; i < p->n_ge; ++i)
+        for (int32_t sc = 0; sc < n_super; ++sc) {
+            int32_t c0, c1;
+            lora::gemv_expand_cols(ge[i], sc, h_out, c0, c1);
+            if (c0 >= c1) continue;  // the wavefront returns at once
+            const int32_t off = nt, cnt = gemv_tokens(ge[i]);
+            put_unit(LORA_UNIT_GEMV_EXPAND, off, cnt, ge[i].row, ge[i].rank, c0, c1, 0, ge[i].alpha);
+        }
+    for (int32_t i = 0; i < p->n_lin_tiles; ++i) {
+        const int32_t off = nt;
+        tile_tokens(lin_tiles[i], lin_tok);
+        const bool tile = i < p->n_tiles;
+        put_unit(LORA_UNIT_LINEAR_ROWS, off, lin_tiles[i].n_tok, tile ? lin_tiles[i].row : -1, tile ? lin_tiles[i].rank : 0, 0, 0,
+                 tile ? 2 : lin_tiles[i].a, tile ? lin_tiles[i].alpha : 0.f);
+    }
+    *n_units = nu;
+    *n_toks = nt;
+    return LORA_OK;
+}
+
 static int validate_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out)
 {
+    if (c->fault_host && __atomic_load_n(c->fault_host, __ATOMIC_ACQUIRE)) return LORA_E_FAULT;
     if (layer < 0 || layer >= c->n_layers || proj < 0 || proj >= (int32_t)c->proj.size()) return LORA_E_INVAL;
     if (p->T > 0 && (!x || !base_out || !aligned16(x) || !aligned16(base_out))) return LORA_E_INVAL;
     const size_t part = (size_t)layer * c->proj.size() + proj;
@@ -1166,6 +1329,17 @@ constexpr int FUSED_GEMV_MAX_ITEMS = 8192;
 // then their expands.
 static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int n, float scale, hipStream_t st)
 {
+    // the work lists may have been uploaded on another stream
+    if (p->upload_pending) {
+        if (is_capturing(st)) {  // a wait on an event from outside the capture would not become part of the graph
+            HIP_TRY(hipEventSynchronize(p->ev_upload));
+            p->upload_pending = false;
+        } else if (hipEventQuery(p->ev_upload) == hipSuccess) {
+            p->upload_pending = false;
+        } else {
+            HIP_TRY(hipStreamWaitEvent(st, p->ev_upload, 0));
+        }
+    }
     for (int32_t sl : p->slots) {
         Slot &s = c->slots[sl];
         if (s.fill_pending) {
@@ -1223,7 +1397,7 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
             ++c->tag_epoch;
             HIP_TRY(lora::launch_gemv_fused(c->dtype, a[i], gs, p->n_gs, ge, p->n_ge,
                                             reinterpret_cast<unsigned long long *>(c->pool + c->off_vtag), c->tag_epoch,
-                                            reinterpret_cast<int32_t *>(c->pool + c->off_fault), st, tm));
+                                            c->fault_dev, st, tm));
         } else {
             HIP_TRY(lora::launch_gemv_shrink(c->dtype, a[i], gs, p->n_gs, st, tm));
         }
@@ -1256,6 +1430,9 @@ static int fence_applies(lora_cache_t *c, lora_plan_t *p, hipStream_t st)
     const int64_t seq = c->apply_seq;
     HIP_TRY(hipEventRecord(c->apply_ev[seq % N_APPLY_EVENTS], st));
     c->apply_ev_seq[seq % N_APPLY_EVENTS] = seq;
+    hipEvent_t &own = c->stream_fence[st];
+    if (!own) HIP_TRY(hipEventCreateWithFlags(&own, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(own, st));
     HIP_TRY(hipEventRecord(p->ev_last_use, st));
     p->use_pending = true;
     return LORA_OK;

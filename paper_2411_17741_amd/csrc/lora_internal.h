@@ -31,19 +31,50 @@ struct DevItem {
     int32_t tok0;            // tok_list[tok_off], so one-token items need no second lookup
 };
 static_assert(sizeof(DevItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
+// token id of row ti (0 <= ti < n_tok) of a tile (tile kernels and lora_plan_dump alike)
+inline __host__ __device__ int32_t tile_token_of(const int32_t *tok_list, const DevItem &it, int32_t ti)
+{
+    return (it.consecutive || ti == 0) ? it.tok0 + ti : tok_list[it.tok_off + ti];
+}
 
-// GEMV work item: a batch of up to LORA_GEMV_BATCH tokens of one slot, named directly so that
+// GEMV work item: a batch of up to GEMV_BATCH tokens of one slot, named directly so that
 // the kernels reach their data with one lookup.  `a` packs, for a shrink item, the first rank
 // row (bits 0-7) and the number of rows (bits 8+); for an expand item the column offset in the
-// super-chunk divided by 64.
+// super-chunk divided by 64.  Kernels and lora_plan_dump read `a` through the two routines below.
+constexpr int GEMV_BATCH = 4;              // tokens one GEMV work item handles
+constexpr int GEMV_SHRINK_ROWS = 4;        // rank rows of a shrink item
+constexpr int GEMV_SUPER_COLS = 1024;      // an expand item stands for one run of columns in every super-chunk of this width
 struct GemvItem {
-    int32_t tok[LORA_GEMV_BATCH];  // token ids, -1 = unused
-    int32_t row;                   // first storage row of the slot
+    int32_t tok[GEMV_BATCH];  // token ids, -1 = unused
+    int32_t row;              // first storage row of the slot
     int32_t rank;
     int32_t a;
-    float alpha;                   // expand: the cache entry's own factor
+    float alpha;              // expand: the cache entry's own factor
 };
-static_assert(sizeof(GemvItem) == sizeof(lora_item_t), "device items are uploaded in place of lora_item_t");
+static_assert(sizeof(GemvItem) == 32, "items are read with two 16-byte loads");
+
+// columns one expand wavefront covers: 16 KB of Bp whatever the rank
+inline __host__ __device__ int32_t gemv_expand_width(int32_t rank)
+{
+    const int32_t q = 128 / rank_storage(rank);
+    return 64 * (q > 1 ? q : 1);
+}
+inline __host__ __device__ int32_t gemv_pack_shrink(int32_t j0, int32_t n_rows) { return j0 | (n_rows << 8); }
+inline __host__ __device__ int32_t gemv_pack_expand(int32_t col_in_super) { return col_in_super / 64; }
+// rank rows [j0, j0 + n) of a shrink item
+inline __host__ __device__ void gemv_shrink_rows(const GemvItem &it, int32_t &j0, int32_t &n)
+{
+    j0 = it.a & 0xff;
+    n = it.a >> 8;
+}
+// output columns [c0, c1) of expand item `it` in super-chunk `sc` of a projection h_out wide (empty if c0 >= c1)
+inline __host__ __device__ void gemv_expand_cols(const GemvItem &it, int32_t sc, int32_t h_out, int32_t &c0, int32_t &c1)
+{
+    c0 = sc * GEMV_SUPER_COLS + (it.a & 0xf) * 64;
+    const int32_t end = c0 + gemv_expand_width(it.rank), super_end = (sc + 1) * GEMV_SUPER_COLS;
+    c1 = end < super_end ? end : super_end;
+    if (c1 > h_out) c1 = h_out;
+}
 
 // Arguments common to the apply kernels of one (layer, projection).
 struct ApplyArgs {

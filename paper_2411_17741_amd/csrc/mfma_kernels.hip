@@ -58,7 +58,7 @@ constexpr int NSTAGE = 3;
 // token id of row ti (>= 0) of a tile
 __device__ __forceinline__ int tile_token(const ApplyArgs &a, const DevItem &it, int ti)
 {
-    return (it.consecutive || ti == 0) ? it.tok0 + ti : a.tok_list[it.tok_off + ti];
+    return tile_token_of(a.tok_list, it, ti);
 }
 
 template <bool NSPLIT, int NBW>  // NBW: rank blocks (of 16) a wavefront works on

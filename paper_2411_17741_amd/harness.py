@@ -86,12 +86,14 @@ class PooledInstance:
         self.pool.close()
 
 
-def error_metrics(y_gpu: np.ndarray, y_ref: np.ndarray, base: np.ndarray, out_eps: float = 2.0**-9) -> Dict[str, float]:
+def error_metrics(y_gpu: np.ndarray, y_ref: np.ndarray, base: np.ndarray, out_dtype: str = "bf16") -> Dict[str, float]:
     """Relative Frobenius error and worst element error (in units of RMS(y_ref)) on y, and the
     error measured against the adapter delta y - base alone (a kernel that does nothing nearly
-    passes the first two).  The delta figure allows for the one rounding of the stored output,
-    at most out_eps * |y| per element (2^-9 for bf16, 2^-24 for fp32), which no kernel can avoid:
-        delta_rel_fro = max(0, |y_gpu - y_ref|_F - out_eps * |y_ref|_F) / |y_ref - base|_F
+    passes the first two).  The delta figure takes out what no kernel can avoid, the one rounding of
+    the stored output: e_round = |round_to_out_dtype(y_ref) - y_ref|_F is computed from the reference
+    itself (not a worst-case bound), and since the rounding of a result and the arithmetic error before
+    it are independent they add in quadrature:
+        delta_rel_fro = sqrt(max(0, |y_gpu - y_ref|_F^2 - e_round^2)) / |y_ref - base|_F
     """
     y_gpu, y_ref, base = (np.asarray(v, np.float64) for v in (y_gpu, y_ref, base))
     d = y_gpu - y_ref
@@ -99,8 +101,12 @@ def error_metrics(y_gpu: np.ndarray, y_ref: np.ndarray, base: np.ndarray, out_ep
     fro = np.linalg.norm(y_ref)
     rms = np.sqrt(np.mean(y_ref**2)) if y_ref.size else 0.0
     dn = np.linalg.norm(y_ref - base)
+    t = torch.from_numpy(np.ascontiguousarray(y_ref))
+    rounded = t.to(torch.bfloat16 if out_dtype == "bf16" else torch.float32).to(torch.float64).numpy()
+    e_round = np.linalg.norm(rounded - y_ref)
+    excess = float(np.sqrt(max(0.0, err * err - e_round * e_round)))
     return {
         "rel_fro": float(err / fro) if fro > 0 else float(err),
         "max_abs_over_rms": float(np.max(np.abs(d)) / rms) if rms > 0 and d.size else 0.0,
-        "delta_rel_fro": float(max(0.0, err - out_eps * fro) / dn) if dn > 0 else float(err),
+        "delta_rel_fro": excess / float(dn) if dn > 0 else excess,
     }

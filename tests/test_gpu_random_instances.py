@@ -13,7 +13,6 @@ torch = pytest.importorskip("torch")
 
 TOL = {"bf16": dict(rel_fro=1e-2, max_abs_over_rms=2e-2, delta_rel_fro=2e-2),
        "f32": dict(rel_fro=1e-5, max_abs_over_rms=1e-4, delta_rel_fro=1e-4)}
-EPS = {"bf16": 2.0**-9, "f32": 2.0**-24}
 
 
 def _draw(case):
@@ -55,7 +54,7 @@ def test_random_instance(case):
             y = yd.float().cpu().numpy()
             ads = {int(a): (*inst.adapter_weights(int(a), p), float(inst.alpha[a])) for a in inst.used_adapters()}
             ref = oracle.lora_apply(x, base, inst.seg_offsets, inst.seg_adapter, ads, inst.scale)
-            m = H.error_metrics(y, ref, base, EPS[inst.dtype])
+            m = H.error_metrics(y, ref, base, inst.dtype)
             for k, lim in TOL[inst.dtype].items():
                 assert m[k] <= lim, f"{what}, proj {p}: {k} = {m[k]:.3e} > {lim}"
             assert np.array_equal(y[ta < 0], base[ta < 0]), f"{what}: tokens without adapter must be untouched"

@@ -37,7 +37,7 @@ def _index_both(T, off, slot, rank, m0):
     rc, got = B.lora_index(T, off, slot, rank, m0)
     assert rc == B.LORA_OK
     want = oracle.index(T, off, slot, rank, m0)
-    for k in ("tok_list", "tiles", "groups", "gs_items", "ge_items"):
+    for k in ("tok_list", "tiles", "groups"):
         assert got[k] == [tuple(v) if not isinstance(v, int) else v for v in want[k]], k
 
 
@@ -61,6 +61,86 @@ def test_indexer_matches_oracle_on_random_batches():
         rank = np.where(slot >= 0, slot_rank[np.maximum(slot, 0)], 0).astype(np.int32)
         m0 = int(rng.choice([0, 1, 8, 16, 64]))
         _index_both(int(off[-1]), off, slot, rank, m0)
+
+
+# ---------------------------------------------------------------------------------------
+# The lists the kernels read (lora_plan_dump of a host-only cache: the staged copy of the plan), checked
+# against the oracle's token map through coverage properties -- no kernel item shape is restated here.
+def _host_plan_check(T, off, slot_of_seg, rank, projs, dtype=B.LORA_BF16, m0=0, seed=0):
+    from plan_checks import check_plan_units
+
+    slot_of_seg = np.asarray(slot_of_seg, np.int32)
+    rank = np.asarray(rank, np.int32)
+    # one slot per distinct name, in a pool of one class per distinct storage size; alpha differs per slot
+    names = sorted({int(s) for s in slot_of_seg if s >= 0})
+    name_rank = {int(s): int(r) for s, r in zip(slot_of_seg, rank) if s >= 0}
+    class_rank = [8, 16, 32, 64, 128]
+    cls_of = lambda r: next(i for i, c in enumerate(class_rank) if c >= r)
+    class_slots = [0] * 5
+    for n in names:
+        class_slots[cls_of(name_rank[n])] += 1
+    class_slots = [c + 1 for c in class_slots]  # a spare slot per class, left empty
+    first = np.concatenate([[0], np.cumsum(class_slots)[:-1]])
+    nxt = list(first)
+    real = {}
+    for n in names:
+        k = cls_of(name_rank[n])
+        real[n] = int(nxt[k])
+        nxt[k] += 1
+    cfg = B.make_config(projs, 1, class_rank, class_slots, dtype, max(1, T), max(1, len(slot_of_seg)), mfma_min_tokens=m0,
+                        flags=B.LORA_CACHE_HOST_ONLY)
+    rc, h = B.lora_cache_create(cfg, 0, 0)
+    assert rc == B.LORA_OK
+    alpha = {}
+    for n in names:
+        alpha[real[n]] = 0.5 + 0.25 * (real[n] % 7)
+        for p in range(len(projs)):
+            assert B.lora_cache_fill_slot(h, real[n], 1000 + n, name_rank[n], alpha[real[n]], 0, p, 0, 0) == B.LORA_OK
+    seg_slot = np.array([real[int(s)] if s >= 0 else -1 for s in slot_of_seg], np.int32)
+    rc, plan = B.lora_plan_create(h, T, off, seg_slot, rank)
+    assert rc == B.LORA_OK
+    counts = check_plan_units(h, plan, T, off, seg_slot, rank, projs, alpha, bf16=dtype == B.LORA_BF16)
+    assert B.lora_plan_destroy(h, plan) == B.LORA_OK
+    assert B.lora_cache_destroy(h) == B.LORA_OK
+    return counts
+
+
+@pytest.mark.parametrize("name", ["tiny", "decode", "prefill", "small_mixed", "stress", "mixed"])
+def test_plan_work_units_cover_every_token_row_and_column_once(name):
+    inst = wl.CONFIGS[name]()
+    projs = [(p.h_in, p.h_out) for p in inst.projs]
+    dtype = B.LORA_BF16 if inst.dtype == "bf16" else B.LORA_F32
+    for m0 in (0, 16):  # the library's own choice of the threshold, and a fixed one
+        counts = _host_plan_check(inst.T, inst.seg_offsets, inst.seg_adapter, inst.seg_rank, projs, dtype, m0)
+        assert counts[0]["gemv_shrink"] + counts[0]["tiles"] > 0
+
+
+def test_plan_work_units_on_random_batches():
+    rng = np.random.default_rng(1)
+    for trial in range(60):
+        n_seg = int(rng.integers(0, 40))
+        lens = rng.choice([0, 1, 1, 1, 2, 3, 5, 9, 15, 16, 17, 63, 64, 65, 130], size=n_seg)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        n_names = int(rng.integers(1, 12))
+        name_rank = rng.choice([1, 3, 4, 8, 12, 16, 24, 32, 40, 64, 100, 128], size=n_names)
+        slot = rng.integers(-1, n_names, size=n_seg).astype(np.int32)
+        rank = np.where(slot >= 0, name_rank[np.maximum(slot, 0)], 0).astype(np.int32)
+        projs = [(64 * int(rng.integers(1, 5)), 64 * int(rng.choice([1, 2, 15, 16, 17, 33]))) for _ in range(int(rng.integers(1, 4)))]
+        _host_plan_check(int(off[-1]), off, slot, rank, projs, B.LORA_BF16, int(rng.choice([0, 1, 8, 16, 64])))
+
+
+def test_slot_state_call():
+    h = _host_cache()
+    assert B.lora_cache_slot_state(h, 2) == (B.LORA_OK, B.LORA_SLOT_EMPTY)
+    assert B.lora_cache_fill_slot(h, 2, 77, 16, 0.5, 0, 0, 0, 0) == B.LORA_OK
+    assert B.lora_cache_slot_state(h, 2) == (B.LORA_OK, B.LORA_SLOT_FILLING)
+    for l, p in [(0, 1), (1, 0), (1, 1)]:
+        assert B.lora_cache_fill_slot(h, 2, 77, 16, 0.5, l, p, 0, 0) == B.LORA_OK
+    assert B.lora_cache_slot_state(h, 2) == (B.LORA_OK, B.LORA_SLOT_READY)
+    assert B.lora_cache_release_slot(h, 2) == B.LORA_OK
+    assert B.lora_cache_slot_state(h, 2) == (B.LORA_OK, B.LORA_SLOT_EMPTY)
+    assert B.lora_cache_slot_state(h, 9)[0] == B.LORA_E_INVAL
+    assert B.lora_cache_destroy(h) == B.LORA_OK
 
 
 def test_indexer_rejects_malformed_batches():

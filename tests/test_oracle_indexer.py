@@ -16,14 +16,11 @@ def test_handworked_index():
     assert w["tok_list"] == [6, 7, 8, 9, 10, 1, 2, 3, 0, 5]
     assert w["tiles"] == [(0, 4, 7, 8, 0, 0), (4, 1, 7, 8, 1, 0)]
     assert w["groups"] == [(5, 3, 2, 16, 0, 0), (8, 2, 7, 8, 0, 0)]
-    assert w["gs_items"] == [(5, 3, 2, 16, j, 4) for j in (0, 4, 8, 12)] + [(8, 2, 7, 8, 0, 4), (8, 2, 7, 8, 4, 4)]
-    # rank 16 -> 512 columns per item -> 2 items per 1024; rank 8 -> 1024 columns -> 1 item
-    assert w["ge_items"] == [(5, 3, 2, 16, 0, 512), (5, 3, 2, 16, 512, 512), (8, 2, 7, 8, 0, 1024)]
-    # a group of 6 tokens is worked on in batches of 4 and 2
+    # six decode tokens of one slot stay one group below the threshold and become a gathered tile at it
     w = oracle.index(6, [0, 1, 2, 3, 4, 5, 6], [9] * 6, [8] * 6, mfma_min_tokens=16)
-    assert w["groups"] == [(0, 6, 9, 8, 0, 0)]
-    assert w["gs_items"] == [(0, 4, 9, 8, 0, 4), (0, 4, 9, 8, 4, 4), (4, 2, 9, 8, 0, 4), (4, 2, 9, 8, 4, 4)]
-    assert w["ge_items"] == [(0, 4, 9, 8, 0, 1024), (4, 2, 9, 8, 0, 1024)]
+    assert w["groups"] == [(0, 6, 9, 8, 0, 0)] and w["tiles"] == []
+    w = oracle.index(6, [0, 1, 2, 3, 4, 5, 6], [9, 4, 9, 9, 4, 9], [8, 32, 8, 8, 32, 8], mfma_min_tokens=4)
+    assert w["tiles"] == [(0, 4, 9, 8, 0, 0)] and w["groups"] == [(4, 2, 4, 32, 0, 0)] and w["tok_list"] == [0, 2, 3, 5, 1, 4]
     ts, tr = oracle.token_map(11, off, slot, rank)
     assert ts == [7, 2, 2, 2, -1, 7, 7, 7, 7, 7, 7]
     assert tr == [8, 16, 16, 16, 0, 8, 8, 8, 8, 8, 8]
@@ -44,14 +41,8 @@ def _check_cover(inst, m0):
     assert sorted(w["tok_list"]) == list(np.flatnonzero(active))
     for (o, n, s, r, _, _) in w["groups"]:
         assert m0 == 0 or n < m0
-        for b0 in range(o, o + n, 4):
-            bn = min(4, o + n - b0)
-            rows = sorted(j for (o2, n2, _, _, j0, nr) in w["gs_items"] if o2 == b0 for j in range(j0, j0 + nr))
-            assert rows == list(range(r))
-            assert all(n2 == bn for (o2, n2, *_rest) in w["gs_items"] + w["ge_items"] if o2 == b0)
-            cols = sorted((c, nc) for (o2, _, _, _, c, nc) in w["ge_items"] if o2 == b0)
-            assert cols[0][0] == 0 and all(cols[i][0] + cols[i][1] == cols[i + 1][0] for i in range(len(cols) - 1))
-            assert cols[-1][0] + cols[-1][1] >= 1024
+    for (o, n, s, r, k, _) in w["tiles"]:
+        assert m0 > 0 and 1 <= n <= 64
     return w
 
 
