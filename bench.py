@@ -32,6 +32,7 @@ WORKLOAD_TEXT = {
     "mixed": "mixed: 224 decode + 32 prompts, 7B-shaped layer (q,k,v,o,gate,up,down) bf16, pool of 500, Zipf(1.2)",
     "stress": "stress: 512 decode + 4x512 prompt tokens, 13B-shaped layer bf16, pool of 1000 in 4 layer copies, Zipf(1.2)",
     "decode_heavy": "decode_heavy (extra, not one of the task's configurations): 1024 one-token requests, one 4096->4096 bf16 projection, pool of 500 adapters (ranks 8..128), Zipf(1.0)",
+    "decode_qkv": "decode_qkv (extra): the decode configuration's batch on the projections q, k, v (4096->4096 bf16 each, same activations), applied as one group",
     "decode_paper": "decode_paper (extra): one-token requests, one 4096->4096 bf16 projection, the paper's adapter population: --adapters N_a, N_a/5 of each rank 8..128, rank uniform, power law within the rank",
 }
 # HBM bytes per launch of a workload's dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs, scaled
@@ -40,8 +41,8 @@ WORKLOAD_TEXT = {
 # measured for the same commands are carried here.
 MEASURED_TRAFFIC = {("decode", "gemv_fused"): 25.37e6, ("prefill", "mfma_shrink"): 63.8e6, ("prefill", "mfma_expand"): 146.8e6, ("mixed", "mfma_expand"): 662.8e6,
                     ("stress", "gemv_fused"): 218.2e6, ("decode_heavy", "gemv_expand"): 139.2e6}  # (decode_heavy: measured for the two-launch form, --gemv split)
-DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32}
-DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100}
+DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32, "decode_qkv": 16}
+DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100, "decode_qkv": 100}
 
 
 def algorithmic_bytes(inst, w, esize=2):
@@ -72,7 +73,7 @@ def algorithmic_bytes(inst, w, esize=2):
 MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 
-def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
+def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> dict:
     """y = x.W + s.(x.A).B in one pass per projection (lora_linear_plan), next to the same work done as a
     vendor-library matmul followed by the apply on its output."""
     import torch
@@ -136,9 +137,7 @@ def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> int:
         "cpu_baseline": None,
         "kernels": kernels,
     }
-    print(json.dumps(out))
-    pi.close()
-    return 0
+    return out
 
 
 def prefetch_sweep(args) -> int:
@@ -450,58 +449,19 @@ def serve_replay(args) -> int:
 
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="decode", choices=list(WORKLOAD_TEXT))
-    ap.add_argument("--layers", type=int, default=0, help="layer copies of the pool to rotate over")
-    ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
-    ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
-    ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
-    ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
-    ap.add_argument("--adapters", type=int, default=100, help="decode_paper: number of adapters N_a (a multiple of 5)")
-    ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
-    ap.add_argument("--fused-base", action="store_true", help="time lora_linear_plan (base projection and adapter update in one pass; "
-                    "random base weights) instead of the apply on a given base output; prints its own JSON line")
-    ap.add_argument("--prefetch-depths", default="", help="e.g. 0,1,2,4: run the queue-driven prefetch experiment instead (own JSON line); "
-                    "uses --tokens (default 256), --adapters (default 200), --layers (default 8), --slots-per-rank, --direct-fill, --fill-by-part")
-    ap.add_argument("--serve", action="store_true", help="replay Poisson arrivals through scheduler, cache manager, loads and applies (own JSON line); "
-                    "uses --arrivals, --token-budget, --prefetch, --adapters (default 200), --layers (default 4), --slots-per-rank, --steps (iterations)")
-    ap.add_argument("--arrivals", type=float, default=1.0, help="--serve: mean requests arriving per iteration")
-    ap.add_argument("--token-budget", type=int, default=65536, help="--serve: tokens the scheduler's queues share")
-    ap.add_argument("--prefetch", type=int, default=8, help="--serve: adapters of waiting requests prefetched per iteration")
-    ap.add_argument("--fill-by-part", action="store_true", help="prefetch experiment: one lora_cache_fill_slot call per (layer, projection) "
-                    "instead of one lora_cache_fill_slot_parts call per adapter")
-    ap.add_argument("--slots-per-rank", type=int, default=0, help="prefetch experiment: pool slots per rank class (default: all but 3 of the 40 adapters of a rank)")
-    ap.add_argument("--prewarm-s", type=float, default=1.0, help="seconds of untimed steps before the warm-up steps (a cold GPU ramps its clocks)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.stderr.write("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1\n")
-        return 2
-
+def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True, fused_base_only: bool = False, extras: bool = True) -> dict:
+    """One workload measured: the record the JSON line is made of."""
     import torch
-
-    if not torch.cuda.is_available():
-        sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
-        return 2
     import workloads as wl
     from paper_2411_17741_amd import binding as B
     from paper_2411_17741_amd import harness as H
 
-    if args.prefetch_depths:
-        return prefetch_sweep(args)
-    if args.serve:
-        return serve_replay(args)
-    steps = args.steps or DEFAULT_STEPS[args.workload]
-    n_layers = args.layers or DEFAULT_LAYERS[args.workload]
-    if args.workload == "decode_paper":
+    steps = steps or DEFAULT_STEPS[workload]
+    n_layers = args.layers or DEFAULT_LAYERS[workload]
+    if workload == "decode_paper":
         inst = wl.decode_paper(seed=0, n_adapters=args.adapters, n_decode=args.tokens)
     else:
-        inst = wl.CONFIGS[args.workload](seed=0)
+        inst = wl.CONFIGS[workload](seed=0)
     t_setup = time.time()
     pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv] | (B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0))
     h = pi.pool.handle
@@ -525,8 +485,10 @@ def main() -> int:
     B.check(B.lora_cache_set_fencing(h, 1))
     n_proj = len(inst.projs)
 
-    if args.fused_base:
-        return fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream)
+    if fused_base_only:
+        out = fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream)
+        pi.close()
+        return out
 
     descs = B.make_descs([(l, p, xs[l % n_sets][inst.projs[p].x_key].data_ptr(), ys[l % n_sets][p].data_ptr())
                           for l in range(n_layers) for p in range(n_proj)])
@@ -631,7 +593,7 @@ def main() -> int:
         roofline = {
             "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get((args.workload, dom)) if args.gemv == "auto" and not args.mfma_min_tokens else None,
+            "traffic": MEASURED_TRAFFIC.get((workload, dom)) if args.gemv == "auto" and not args.mfma_min_tokens else None,
             "avg_launch_us": kernels[dom]["avg_us"], "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
         }
 
@@ -639,7 +601,7 @@ def main() -> int:
     # Loaded here are pool adapters the batch does not name (no ordering between the two streams), over and over,
     # for as long as a few steps take; reported: the fill rate alone and overlapped, the step time overlapped.
     fill_overlap = None
-    if args.workload == "stress":
+    if workload == "stress":
         unused = [a for a in range(len(inst.ranks)) if a not in set(int(u) for u in inst.used_adapters())][:6]
         host = []
         for a in unused:
@@ -684,11 +646,11 @@ def main() -> int:
         }
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
 
         # bounded sample: evenly spaced tokens of the batch, each as its own one-token segment
-        n_samp = min(inst.T, 64 if args.workload == "decode" else 256)
+        n_samp = min(inst.T, 64 if workload == "decode" else 256)
         rows = np.unique(np.linspace(0, inst.T - 1, n_samp).astype(np.int64))
         ta = inst.token_adapter()[rows]
         off = np.arange(len(rows) + 1, dtype=np.int32)
@@ -710,7 +672,7 @@ def main() -> int:
         "metric": "lora_apply_tokens_per_s_per_layer", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
+        "config": {"workload": WORKLOAD_TEXT[workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
                    "pool_adapters": int(inst.n_adapters), "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
                    "host_index_us": index_us, "host_plan_create_us": plan_us,
@@ -724,6 +686,81 @@ def main() -> int:
                   "achieved_TFLOPs": step_flops / (ms_per_layer * 1e-3) / 1e12, "setup_s": t_setup},
         "kernels": kernels,
     }
+    pi.close()
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="", choices=[""] + list(WORKLOAD_TEXT),
+                    help="one workload alone; default: the decode configuration as the headline with the prefill, mixed and stress "
+                         "configurations (and the decode batch on q,k,v as one group) as sub-records of the same line")
+    ap.add_argument("--layers", type=int, default=0, help="layer copies of the pool to rotate over")
+    ap.add_argument("--sets", type=int, default=0, help="activation buffer sets to rotate over")
+    ap.add_argument("--gemv", default="auto", choices=["auto", "fused", "split"], help="GEMV shrink and expand as one launch, two, or chosen by size")
+    ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
+    ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
+    ap.add_argument("--adapters", type=int, default=100, help="decode_paper: number of adapters N_a (a multiple of 5)")
+    ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
+    ap.add_argument("--fused-base", action="store_true", help="time lora_linear_plan (base projection and adapter update in one pass; "
+                    "random base weights) instead of the apply on a given base output; prints its own JSON line")
+    ap.add_argument("--prefetch-depths", default="", help="e.g. 0,1,2,4: run the queue-driven prefetch experiment instead (own JSON line); "
+                    "uses --tokens (default 256), --adapters (default 200), --layers (default 8), --slots-per-rank, --direct-fill, --fill-by-part")
+    ap.add_argument("--serve", action="store_true", help="replay Poisson arrivals through scheduler, cache manager, loads and applies (own JSON line); "
+                    "uses --arrivals, --token-budget, --prefetch, --adapters (default 200), --layers (default 4), --slots-per-rank, --steps (iterations)")
+    ap.add_argument("--arrivals", type=float, default=1.0, help="--serve: mean requests arriving per iteration")
+    ap.add_argument("--token-budget", type=int, default=65536, help="--serve: tokens the scheduler's queues share")
+    ap.add_argument("--prefetch", type=int, default=8, help="--serve: adapters of waiting requests prefetched per iteration")
+    ap.add_argument("--fill-by-part", action="store_true", help="prefetch experiment: one lora_cache_fill_slot call per (layer, projection) "
+                    "instead of one lora_cache_fill_slot_parts call per adapter")
+    ap.add_argument("--slots-per-rank", type=int, default=0, help="prefetch experiment: pool slots per rank class (default: all but 3 of the 40 adapters of a rank)")
+    ap.add_argument("--prewarm-s", type=float, default=1.0, help="seconds of untimed steps before the warm-up steps (a cold GPU ramps its clocks)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1\n")
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; the library has no CPU path\n")
+        return 2
+    import workloads as wl
+    from paper_2411_17741_amd import binding as B
+    from paper_2411_17741_amd import harness as H
+
+    if args.prefetch_depths:
+        return prefetch_sweep(args)
+    if args.serve:
+        return serve_replay(args)
+    if args.workload:  # one workload, as named
+        out = run_workload(args, args.workload, args.steps, cpu_baseline=not args.no_cpu_baseline, fused_base_only=args.fused_base)
+        print(json.dumps(out))
+        return 0
+    # default: the decode configuration is the headline (the metric's bandwidth half is quoted on it); the other
+    # configurations ride along as sub-records of the same line, each measured the same way with fewer steps
+    out = run_workload(args, "decode", args.steps, cpu_baseline=not args.no_cpu_baseline)
+    keep = ("value", "ms_per_step", "steps", "roofline", "kernels", "layer", "fill_overlap")
+    out["configs"] = {}
+    for name in ("prefill", "mixed", "stress", "decode_qkv"):
+        rec = run_workload(args, name, 0, cpu_baseline=False)
+        sub = {k: rec[k] for k in keep if rec.get(k) is not None}
+        sub["workload"] = rec["config"]["workload"]
+        for k in ("tokens", "projections", "layers_per_step", "ms_per_layer", "distinct_adapters", "tiles", "gemv_shrink_items", "graph_replay"):
+            if k in rec["config"]:
+                sub[k] = rec["config"][k]
+        sub["tokens_per_s_per_layer"] = sub.pop("value")
+        if name == "prefill":  # the metric's matrix-core half: base projection and adapter update in one kernel
+            fb = run_workload(args, name, 0, cpu_baseline=False, fused_base_only=True)
+            sub["fused_base"] = {"ms_per_layer": fb["config"]["ms_per_layer"],
+                                 "vendor_matmul_then_apply_ms_per_layer": fb["config"]["vendor_matmul_then_apply_ms_per_layer"],
+                                 "roofline": fb["roofline"], "kernels": fb["kernels"]}
+        out["configs"][name] = sub
     print(json.dumps(out))
     pi.close()
     return 0

@@ -33,6 +33,28 @@ constexpr double TILE_PATH_L2_BYTES_PER_US = 10e6;  // rate at which repeated pa
 constexpr int N_VSETS = lora::MAX_SHRINK_PROJS;  // applies that share their input run shrink-first, each with its own intermediate
 
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
+
+// Device memory an apply needs beside its inputs and outputs: the shrink results (one set per
+// projection of a group), the partial sums of a k-split tile shrink, and the tagged words through
+// which the one-launch GEMV form hands its intermediate over.
+struct Scratch {
+    char *v;
+    size_t v_set_bytes;
+    int n_sets;
+    char *vpart;
+    size_t vpart_set_bytes;
+    int64_t vpart_rows;
+    char *vtag;                // hand-over words of the GEMV phases, one set per projection of a group
+    size_t vtag_set_bytes;
+    uint32_t *epoch;           // host counter of the one-launch GEMV launches that have used vtag
+    // the latest one-launch GEMV enqueued under stream capture with this scratch: capture, plan and sets
+    // (a replayed launch finds its own number in the words it wrote the last time, unless another launch
+    // of the graph has written them since)
+    unsigned long long *cap_id;
+    uint64_t *cap_plan;
+    int *cap_sets;
+};
+
 int esize_of(int dtype) { return dtype == LORA_BF16 ? 2 : 4; }
 
 struct Slot {
@@ -72,6 +94,7 @@ struct lora_plan {
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
     int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
     int32_t mfma_min_used = 0;  // the threshold the work lists were made with
+    uint64_t build_seq = 0;     // changes whenever the plan's lists are rebuilt
     size_t off_tiles = 0, off_gs = 0, off_ge = 0, bytes = 0;
     // for lora_linear_plan: every token of the batch in row tiles -- the tiles above, then runs of up
     // to 64 of the other tokens (rank 0) -- over a token list of its own
@@ -97,8 +120,11 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
-    size_t off_fault = 0, off_vpart = 0, off_vtag = 0, v_set_bytes = 0, vpart_set_bytes = 0;
-    uint32_t tag_epoch = 0;  // fused GEMV launches so far; the tag of the words of the latest one
+    size_t off_fault = 0, off_vpart = 0, off_vtag = 0, v_set_bytes = 0, vpart_set_bytes = 0, vtag_set_bytes = 0;
+    uint32_t tag_epoch = 0;  // one-launch GEMV launches so far; the number the words of the latest one carry
+    unsigned long long cap_id = 0;
+    uint64_t cap_plan = 0;  // build number of the plan
+    int cap_sets = 0;
     int64_t vpart_rows = 0;  // rows of the k-split partial scratch
     int fused_gemv = 0;  // 0 never, 1 by size, 2 always
     size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
@@ -106,11 +132,12 @@ struct lora_cache {
     std::vector<Slot> slots;
     std::unordered_map<int64_t, int32_t> id2slot;
     std::vector<lora_plan> plans;  // user plans first, then the internal ring
-    uint64_t internal_next = 0;
+    uint64_t internal_next = 0, plan_builds = 0;
     Stage stage[N_STAGES];
     bool direct_fill = false;
     uint64_t stage_next = 0;
 
+    int device = 0;  // the device that was current at lora_cache_create
     bool fencing = true;
     int64_t apply_seq = 0;
     hipEvent_t apply_ev[N_APPLY_EVENTS] = {};
@@ -222,9 +249,10 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.off_vpart = cur;
     c.vpart_set_bytes = align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
     cur += c.vpart_set_bytes * N_VSETS;
-    // fused GEMV launches hand v over as tagged 64-bit words, one row per token
+    // the GEMV phases hand their intermediate over as 64-bit words, one row per token and projection of a group
     c.off_vtag = cur;
-    cur += c.fused_gemv ? align_up(sizeof(uint64_t) * (size_t)c.max_tokens * c.v_stride) : 0;
+    c.vtag_set_bytes = align_up(lora::gemv_handover_bytes(c.dtype, c.max_tokens));
+    cur += c.vtag_set_bytes * N_VSETS;
     c.off_plans = cur;
     cur += c.plan_cap * (size_t)(c.n_user_plans + N_INTERNAL_PLANS);
     c.off_stage = cur;
@@ -440,7 +468,7 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     }
     // GEMV work items.  A group is worked on in token batches (runs of up to GEMV_BATCH entries of its
     // part of tok_list), every batch with items of its own so that batches run side by side: per batch
-    // one shrink item per GEMV_SHRINK_ROWS rank rows, and one expand item per run of
+    // one shrink item per GEMV_SHRINK_ROWS stored rank rows, and one expand item per run of
     // gemv_expand_width(rank) columns of a super-chunk (the launch repeats it for every super-chunk of
     // the projection).
     std::vector<lora::GemvItem> gs, ge;
@@ -455,8 +483,8 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
             for (int32_t b0 = 0; b0 < gr.n_tok; b0 += lora::GEMV_BATCH) {
                 for (int t = 0; t < lora::GEMV_BATCH; ++t) d.tok[t] = b0 + t < gr.n_tok ? w.tok_list[gr.tok_off + b0 + t] : -1;
                 if (pass == 0) {
-                    for (int32_t j0 = 0; j0 < gr.rank; j0 += lora::GEMV_SHRINK_ROWS) {
-                        d.a = lora::gemv_pack_shrink(j0, std::min(lora::GEMV_SHRINK_ROWS, gr.rank - j0));
+                    for (int32_t j0 = 0; j0 < lora::rank_storage(gr.rank); j0 += lora::GEMV_SHRINK_ROWS) {
+                        d.a = lora::gemv_pack_shrink(j0);
                         gs.push_back(d);
                     }
                 } else {
@@ -534,22 +562,12 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     std::memcpy(p.pinned, w.tok_list, sizeof(int32_t) * (size_t)w.n_tok_list);
     std::memcpy(p.pinned + p.off_tiles, w.tiles, sizeof(lora_item_t) * (size_t)w.n_tiles);
     lora_worklists_free(&w);
-    {
-        // One block works on one shrink item and block b runs on XCD b % 8, each XCD behind its own
-        // L2.  The items of a token batch (4 slab rows each, all reading the batch's x rows) follow
-        // each other in the list: XCD j gets a run of consecutive items, the i-th of them as block
-        // 8i + j, so that a batch's x rows are fetched from memory by one XCD, not by all eight.
-        lora::GemvItem *dst = reinterpret_cast<lora::GemvItem *>(p.pinned + p.off_gs);
-        const int n = (int)gs.size();
-        for (int b = 0; b < n; ++b) {
-            const int j = b & 7;
-            dst[b] = gs[j * (n >> 3) + std::min(j, n & 7) + (b >> 3)];
-        }
-    }
+    if (!gs.empty()) std::memcpy(p.pinned + p.off_gs, gs.data(), sizeof(lora::GemvItem) * gs.size());
     if (!ge.empty()) std::memcpy(p.pinned + p.off_ge, ge.data(), sizeof(lora::GemvItem) * ge.size());
     if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
     if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
     p.bytes = bytes;
+    p.build_seq = ++c.plan_builds;
     if (!c.host_only && bytes) {
         if (p.use_pending) {
             HIP_TRY(hipStreamWaitEvent(st, p.ev_last_use, 0));
@@ -600,7 +618,7 @@ void timer_pair(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop)
     *stop = t.stop;
 }
 
-int choose_k_splits(const lora_cache &c, int n_tiles, int n_tile_tok, int h_in)
+int choose_k_splits(int64_t vpart_rows, int n_tiles, int n_tile_tok, int h_in)
 {
     // One round of blocks (2 per CU) when there are few tiles.  From half a round of whole-row blocks
     // up, about two rounds of shorter ones: with 330 tiles, three k ranges took 10 % less than one
@@ -610,7 +628,7 @@ int choose_k_splits(const lora_cache &c, int n_tiles, int n_tile_tok, int h_in)
     const int n = std::max(1, n_tiles);
     const int fill = n <= 256 ? 512 / n : (1100 + n / 2) / n;
     int want = std::max(1, std::min({fill, h_in / 512, MAX_K_SPLITS}));
-    while (want > 1 && (int64_t)lora::mfma_shrink_splits(h_in, want) * n_tile_tok > c.vpart_rows) --want;
+    while (want > 1 && (int64_t)lora::mfma_shrink_splits(h_in, want) * n_tile_tok > vpart_rows) --want;
     return lora::mfma_shrink_splits(h_in, want);
 }
 
@@ -686,14 +704,18 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
     }
     c->pool = static_cast<char *>(dev_pool);
     c->pool_bytes = dev_pool_bytes;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        g_last_hip = (int)hipGetLastError();
+        delete c;
+        return LORA_E_HIP;
+    }
 
     int rc = LORA_OK;
     // the tagged words must not carry a future launch number by accident: numbers start at 1
     if (hipHostMalloc(reinterpret_cast<void **>(&c->fault_host), 64, hipHostMallocMapped) != hipSuccess ||
         hipHostGetDevicePointer(reinterpret_cast<void **>(&c->fault_dev), c->fault_host, 0) != hipSuccess ||
         (*c->fault_host = 0, false) ||
-        (c->fused_gemv &&
-         hipMemset(c->pool + c->off_vtag, 0, sizeof(uint64_t) * (size_t)c->max_tokens * c->v_stride) != hipSuccess)) {
+        hipMemset(c->pool + c->off_vtag, 0, c->vtag_set_bytes * N_VSETS) != hipSuccess) {
         g_last_hip = (int)hipGetLastError();
         delete c;
         return LORA_E_HIP;
@@ -1279,21 +1301,29 @@ int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_pla
             }
         return n;
     };
-    for (int32_t i = 0; i < p->n_gs; ++i) {
+    // the GEMV launch of this projection alone: blocks and units mapped to items as the kernel maps them
+    for (uint32_t b = 0; b < (uint32_t)p->n_gs; ++b) {
+        uint32_t item, pj;
+        lora::gemv_shrink_block(b, (uint32_t)p->n_gs, 1u, 0u, item, pj);
         int32_t j0, n;
-        lora::gemv_shrink_rows(gs[i], j0, n);
-        const int32_t off = nt, cnt = gemv_tokens(gs[i]);
-        put_unit(LORA_UNIT_GEMV_SHRINK, off, cnt, gs[i].row, gs[i].rank, j0, j0 + n, i, gs[i].alpha);
+        lora::gemv_shrink_rows(gs[item], j0, n);
+        const int32_t off = nt, cnt = gemv_tokens(gs[item]);
+        put_unit(LORA_UNIT_GEMV_SHRINK, off, cnt, gs[item].row, gs[item].rank, j0, j0 + n, (int32_t)b, gs[item].alpha);
     }
-    const int32_t h_out = c->proj[proj].h_out, n_super = (h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
-    for (int32_t i = 0; i < p->n_ge; ++i)
-        for (int32_t sc = 0; sc < n_super; ++sc) {
-            int32_t c0, c1;
-            lora::gemv_expand_cols(ge[i], sc, h_out, c0, c1);
-            if (c0 >= c1) continue;  // the wavefront returns at once
-            const int32_t off = nt, cnt = gemv_tokens(ge[i]);
-            put_unit(LORA_UNIT_GEMV_EXPAND, off, cnt, ge[i].row, ge[i].rank, c0, c1, 0, ge[i].alpha);
-        }
+    lora::GemvProj gp{};
+    gp.h_out = c->proj[proj].h_out;
+    gp.n_super = (gp.h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
+    gp.super_magic = lora::gemv_magic((uint32_t)gp.n_super);
+    gp.unit_end = p->n_ge * gp.n_super;
+    for (uint32_t u = 0; u < (uint32_t)gp.unit_end; ++u) {
+        uint32_t pj, item, sc;
+        lora::gemv_expand_unit(u, &gp, 1u, pj, item, sc);
+        int32_t c0, c1;
+        lora::gemv_expand_cols(ge[item], (int32_t)sc, gp.h_out, c0, c1);
+        if (c0 >= c1) continue;  // the wavefront returns at once
+        const int32_t off = nt, cnt = gemv_tokens(ge[item]);
+        put_unit(LORA_UNIT_GEMV_EXPAND, off, cnt, ge[item].row, ge[item].rank, c0, c1, 0, ge[item].alpha);
+    }
     for (int32_t i = 0; i < p->n_lin_tiles; ++i) {
         const int32_t off = nt;
         tile_tokens(lin_tiles[i], lin_tok);
@@ -1327,7 +1357,79 @@ constexpr int FUSED_GEMV_MAX_ITEMS = 8192;
 // write to it.  Those run shrink-first, each with its own copy of the intermediate buffers: one
 // tile-shrink launch for all of them (x is then fetched from memory once), their GEMV launches,
 // then their expands.
-static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int n, float scale, hipStream_t st)
+static Scratch pool_scratch(lora_cache_t *c)
+{
+    return Scratch{c->pool + c->off_v, c->v_set_bytes, N_VSETS, c->pool + c->off_vpart, c->vpart_set_bytes, c->vpart_rows,
+                   c->pool + c->off_vtag, c->vtag_set_bytes, &c->tag_epoch, &c->cap_id, &c->cap_plan, &c->cap_sets};
+}
+
+// The GEMV part of a group of n projections that read the same x: one launch with the in-kernel
+// hand-over when the part is small (the launch in between then costs more than the hand-over), else a
+// shrink and an expand launch.  y32[i], when set, receives projection i's update as fp32 instead of y.
+static int enqueue_gemv(lora_cache_t *c, lora_plan_t *p, const lora::ApplyArgs *a, float *const *y32, int n, bool allow_one_launch,
+                        hipStream_t st, const Scratch &sc, const lora::KernelTimer *tm)
+{
+    if (p->n_gs <= 0) return LORA_OK;
+    lora::GemvArgs ga{};
+    ga.x = a[0].x;
+    ga.gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
+    ga.ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
+    ga.fault = c->fault_dev;
+    ga.h_in = a[0].h_in;
+    ga.n_proj = n;
+    ga.n_gs = p->n_gs;
+    ga.n_ge = p->n_ge;
+    ga.proj_magic = lora::gemv_magic((uint32_t)n);
+    ga.scale = a[0].scale;
+    int64_t units = 0;
+    for (int i = 0; i < lora::GEMV_MAX_PROJS; ++i) {
+        const int k = std::min(i, n - 1);  // entries past the group repeat its last
+        lora::GemvProj &q = ga.p[i];
+        q.proj_base = a[k].proj_base;
+        q.row_bytes = a[k].row_bytes;
+        q.y = a[k].y;
+        q.y32 = y32 ? y32[k] : nullptr;
+        q.vw = reinterpret_cast<unsigned long long *>(sc.vtag + (size_t)k * sc.vtag_set_bytes);
+        q.h_out = a[k].h_out;
+        q.n_super = (a[k].h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
+        q.super_magic = lora::gemv_magic((uint32_t)q.n_super);
+        if (i < n) units += (int64_t)p->n_ge * q.n_super;
+        q.unit_end = (int32_t)units;
+    }
+    if (units >= (1 << 24) || (int64_t)p->n_gs * n >= (1 << 24)) return LORA_E_INVAL;  // beyond the kernels' unit arithmetic
+    // (after 2^32 - 1 one-launch applies the numbers would repeat: two launches from then on)
+    const bool one = allow_one_launch && *sc.epoch < UINT32_MAX - 1 &&
+                     (c->fused_gemv == 2 || (c->fused_gemv == 1 && (int64_t)p->n_gs * n <= FUSED_GEMV_MAX_ITEMS));
+    if (one) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        unsigned long long cap = 0;
+        if (hipStreamGetCaptureInfo(st, &cs, &cap) != hipSuccess) {
+            (void)hipGetLastError();
+            cs = hipStreamCaptureStatusNone;
+        }
+        if (cs != hipStreamCaptureStatusNone) {
+            // A graph freezes the launch number, so a replay could take the words its own launch wrote in the
+            // replay before for fresh ones.  Not when another launch of the same graph has written the same
+            // words in between (its number differs): that holds for every launch after the first of a capture
+            // that works on the same plan with at least as many projections.  Otherwise the words are cleared
+            // first, by a small kernel that becomes part of the graph.
+            const bool covered = cap == *sc.cap_id && p->build_seq == *sc.cap_plan && n <= *sc.cap_sets;
+            if (!covered) {
+                const int32_t *toks = reinterpret_cast<const int32_t *>(p->dev) + p->n_tile_tok;
+                for (int i = 0; i < n; ++i) HIP_TRY(lora::launch_gemv_clear(c->dtype, ga.p[i].vw, toks, p->n_tok_list - p->n_tile_tok, st));
+            }
+            *sc.cap_id = cap;
+            *sc.cap_plan = p->build_seq;
+            *sc.cap_sets = n;
+        }
+        ga.epoch = ++*sc.epoch;
+    }
+    HIP_TRY(lora::launch_gemv(c->dtype, ga, st, tm));
+    return LORA_OK;
+}
+
+static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_t *descs, int n, float scale, hipStream_t st,
+                         const Scratch &sc)
 {
     // the work lists may have been uploaded on another stream
     if (p->upload_pending) {
@@ -1350,8 +1452,6 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
     const lora::KernelTimer timer{c, timer_pair};
     const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
     const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(p->dev + p->off_tiles);
-    const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
-    const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
 
     lora::ApplyArgs a[N_VSETS];
     lora::ShrinkProjs ps;
@@ -1364,7 +1464,7 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
         a[i].tok_list = reinterpret_cast<const int32_t *>(p->dev);
         a[i].x = descs[i].x;
         a[i].y = descs[i].base_out;
-        a[i].v = reinterpret_cast<float *>(c->pool + c->off_v + (size_t)i * c->v_set_bytes);
+        a[i].v = reinterpret_cast<float *>(sc.v + (size_t)i * sc.v_set_bytes);
         a[i].h_in = c->proj[proj].h_in;
         a[i].h_out = c->proj[proj].h_out;
         a[i].v_stride = c->v_stride;
@@ -1372,40 +1472,23 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
         ps.proj_base[i] = a[i].proj_base;
         ps.row_bytes[i] = a[i].row_bytes;
         ps.v[i] = a[i].v;
-        ps.part[i] = reinterpret_cast<float *>(c->pool + c->off_vpart + (size_t)i * c->vpart_set_bytes);
+        ps.part[i] = reinterpret_cast<float *>(sc.vpart + (size_t)i * sc.vpart_set_bytes);
     }
     for (int i = n; i < N_VSETS; ++i) {
         ps.proj_base[i] = nullptr;
         ps.row_bytes[i] = 0;
         ps.v[i] = ps.part[i] = nullptr;
     }
-    // (after 2^32 - 1 fused launches the numbers would repeat: two launches from then on)
-    // one launch pays off while the GEMV part is small enough for the launch gap to matter
-    // and never under stream capture: the launch number would be frozen into the graph, and a replay
-    // could take the previous replay's values for its own
-    const bool fused = p->n_gs > 0 && c->tag_epoch < UINT32_MAX - N_VSETS && !is_capturing(st) &&
-                       (c->fused_gemv == 2 || (c->fused_gemv == 1 && p->n_gs <= FUSED_GEMV_MAX_ITEMS));
-
     // everything that reads x
     if (p->n_tiles > 0) {
         // the scratch of the partials is sized for about 640 blocks of 64 tokens per projection
-        const int splits = choose_k_splits(*c, p->n_tiles * n, p->n_tile_tok, a[0].h_in);
+        const int splits = choose_k_splits(sc.vpart_rows, p->n_tiles * n, p->n_tile_tok, a[0].h_in);
         HIP_TRY(lora::launch_mfma_shrink(a[0], ps, tiles, p->n_tiles, p->n_tile_tok, splits, st, tm));
     }
-    for (int i = 0; i < n; ++i) {
-        if (fused) {
-            ++c->tag_epoch;
-            HIP_TRY(lora::launch_gemv_fused(c->dtype, a[i], gs, p->n_gs, ge, p->n_ge,
-                                            reinterpret_cast<unsigned long long *>(c->pool + c->off_vtag), c->tag_epoch,
-                                            c->fault_dev, st, tm));
-        } else {
-            HIP_TRY(lora::launch_gemv_shrink(c->dtype, a[i], gs, p->n_gs, st, tm));
-        }
-    }
+    if (const int rc = enqueue_gemv(c, p, a, nullptr, n, true, st, sc, tm)) return rc;
     // the updates of base_out
     for (int i = 0; i < n; ++i) {
         HIP_TRY(lora::launch_mfma_expand(a[i], tiles, p->n_tiles, st, tm));
-        if (!fused) HIP_TRY(lora::launch_gemv_expand(c->dtype, a[i], ge, p->n_ge, st, tm));
         const int64_t seq = ++c->apply_seq;
         ++c->stats.applies;
         for (int32_t sl : p->slots) {
@@ -1420,7 +1503,7 @@ static int enqueue_apply(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t
                          float scale, hipStream_t st)
 {
     const lora_apply_desc_t d{layer, proj, x, base_out};
-    return enqueue_group(c, p, &d, 1, scale, st);
+    return enqueue_group(c, p, &d, 1, scale, st, pool_scratch(c));
 }
 
 // One event pair per call (not per apply): fills that come later wait for it.
@@ -1481,8 +1564,6 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
     const lora::KernelTimer timer{c, timer_pair};
     const lora::KernelTimer *tm = c->timing && !is_capturing(st) ? &timer : nullptr;
     const lora::DevItem *tiles = reinterpret_cast<const lora::DevItem *>(p->dev + p->off_tiles);
-    const lora::GemvItem *gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
-    const lora::GemvItem *ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
     lora::ApplyArgs a;
     a.proj_base = c->pool + (size_t)layer * c->layer_stride + c->proj_off[proj];
     a.row_bytes = (int64_t)c->row_bytes[proj];
@@ -1505,15 +1586,15 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
             ps.v[i] = i ? nullptr : a.v;
             ps.part[i] = i ? nullptr : reinterpret_cast<float *>(c->pool + c->off_vpart);
         }
-        HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, p->n_tile_tok, choose_k_splits(*c, p->n_tiles, p->n_tile_tok, a.h_in), st, tm));
+        HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, p->n_tile_tok, choose_k_splits(c->vpart_rows, p->n_tiles, p->n_tile_tok, a.h_in), st, tm));
     }
     // the adapter term of the GEMV tokens: as fp32 into the caller's workspace (row = token), or, without
     // one, into their zeroed output rows (rounded to the output type on the way)
     if (p->n_tok_list > p->n_tile_tok) {
         a.y32 = static_cast<float *>(workspace);
         if (!a.y32) HIP_TRY(lora::launch_zero_rows(y, a.tok_list + p->n_tile_tok, p->n_tok_list - p->n_tile_tok, a.h_out, st));
-        HIP_TRY(lora::launch_gemv_shrink(c->dtype, a, gs, p->n_gs, st, tm));
-        HIP_TRY(lora::launch_gemv_expand(c->dtype, a, ge, p->n_ge, st, tm));
+        float *const y32 = a.y32;
+        if (const int rc_g = enqueue_gemv(c, p, &a, &y32, 1, false, st, pool_scratch(c), tm)) return rc_g;
     }
     // base product of every token + adapter product of the tiles (+ the term just computed for the others)
     lora::ApplyArgs lin = a;
@@ -1552,7 +1633,7 @@ int lora_apply_plan_multi(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc
                    c->proj[descs[i + g].proj].h_in == c->proj[descs[i].proj].h_in && !writes_x(descs[i + g]))
                 ++g;
         }
-        const int rc = enqueue_group(c, p, descs + i, g, scale, st);
+        const int rc = enqueue_group(c, p, descs + i, g, scale, st, pool_scratch(c));
         if (rc != LORA_OK) return rc;
         i += g;
     }

@@ -95,31 +95,62 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Sums N = 2^K values per lane over the 64 lanes with N - 1 + (6 - K) shuffles instead of 6 N:
-// every step folds the wavefront in half and halves the number of values a lane carries (the
-// lower half of the lanes keeps the first half of the values).  On return v[0] of lane l holds
-// the total of value l >> (6 - K).
+// Sums N = 2^K values per lane (N = 4, 8 or 16) over the 64 lanes: every step folds the wavefront in
+// half and halves the number of values a lane carries (the lanes whose bit `off` is clear keep the
+// first half of the values).  On return v[0] of lane l holds the total of value l >> (6 - K).
+// The halves 32 and 16 lanes apart change places with the lane-swap instructions (one swap and one
+// add per pair of values), the nearer ones with DPP moves (a row rotated by 8, a mirrored half row,
+// quads permuted): no step goes through LDS.
 template <int N>
-__device__ __forceinline__ void wave_sum_fold(float (&v)[N])
+__device__ __forceinline__ void wave_fold(float (&v)[N])
 {
-    static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "power of two up to 16");
+    static_assert(N == 4 || N == 8 || N == 16, "4, 8 or 16 values");
     const int lane = threadIdx.x & 63;
-    auto from = [&](float x, int off) {
-        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ off) << 2, __builtin_bit_cast(int, x)));
-    };
-    int off = 32;
+    typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
+    int m = N;
+    // 32 lanes apart: after the swap the first register holds [first.low, second.low], the second [first.high, second.high]
 #pragma unroll
-    for (int m = N; m > 1; m >>= 1, off >>= 1) {
-        const bool upper = (lane & off) != 0;
-#pragma unroll
-        for (int i = 0; i < m / 2; ++i) {
-            const float lo = v[i], hi = v[i + m / 2];  // named, so that the selects stay selects of values
-            const float give = upper ? lo : hi;
-            const float keep = upper ? hi : lo;
-            v[i] = keep + from(give, off);
-        }
+    for (int i = 0; i < N / 2; ++i) {
+        const uint2_t sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + N / 2]), false, false);
+        v[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
-    for (; off > 0; off >>= 1) v[0] += from(v[0], off);
+    m = N / 2;
+    // 16 lanes apart: odd rows of the first register change places with even rows of the second
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+        const uint2_t sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[i]), __float_as_uint(v[i + N / 4]), false, false);
+        v[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    m = N / 4;
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    struct Ror8 { enum { value = 0x128 }; };        // row rotated right by 8: lane ^ 8
+    struct HalfMirror { enum { value = 0x141 }; };  // lanes of every 8 reversed: pairs 0..3 with 7..4
+    struct Xor2 { enum { value = 0x4E }; };         // quad_perm [2, 3, 0, 1]
+    struct Xor1 { enum { value = 0xB1 }; };         // quad_perm [1, 0, 3, 2]
+    if constexpr (N >= 8) {  // 8 lanes apart
+        const bool upper = (lane & 8) != 0;
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) {
+            const float lo = v[i], hi = v[i + N / 8];
+            const float give = upper ? lo : hi, keep = upper ? hi : lo;
+            v[i] = keep + dpp(give, Ror8{});
+        }
+    } else {
+        v[0] += dpp(v[0], Ror8{});
+    }
+    if constexpr (N >= 16) {  // 4 lanes apart
+        const bool upper = (lane & 4) != 0;
+        const float lo = v[0], hi = v[1];
+        const float give = upper ? lo : hi, keep = upper ? hi : lo;
+        v[0] = keep + dpp(give, HalfMirror{});
+    } else {
+        v[0] += dpp(v[0], HalfMirror{});
+    }
+    v[0] += dpp(v[0], Xor2{});
+    v[0] += dpp(v[0], Xor1{});
+    (void)m;
 }
 
 }  // namespace lora

@@ -37,43 +37,102 @@ inline __host__ __device__ int32_t tile_token_of(const int32_t *tok_list, const 
     return (it.consecutive || ti == 0) ? it.tok0 + ti : tok_list[it.tok_off + ti];
 }
 
-// GEMV work item: a batch of up to GEMV_BATCH tokens of one slot, named directly so that
-// the kernels reach their data with one lookup.  `a` packs, for a shrink item, the first rank
-// row (bits 0-7) and the number of rows (bits 8+); for an expand item the column offset in the
-// super-chunk divided by 64.  Kernels and lora_plan_dump read `a` through the two routines below.
+// GEMV work item: a batch of up to GEMV_BATCH tokens of one slot, named directly so that the kernels
+// reach their data with one lookup.  A shrink item stands for GEMV_SHRINK_ROWS stored rank rows from
+// `a` on (stored rows past the rank hold zeros, so an item is always whole); an expand item for one
+// run of gemv_expand_width(rank) columns in every super-chunk of the projection, `a` being the
+// run's offset inside the super-chunk in units of 64 columns.  Items name no projection: a launch
+// runs them for every projection of its group.  Kernels and lora_plan_dump read `a` through the
+// routines below.
 constexpr int GEMV_BATCH = 4;              // tokens one GEMV work item handles
 constexpr int GEMV_SHRINK_ROWS = 4;        // rank rows of a shrink item
 constexpr int GEMV_SUPER_COLS = 1024;      // an expand item stands for one run of columns in every super-chunk of this width
 struct GemvItem {
-    int32_t tok[GEMV_BATCH];  // token ids, -1 = unused
+    int32_t tok[GEMV_BATCH];  // token ids, -1 = unused; used ones come first
     int32_t row;              // first storage row of the slot
     int32_t rank;
     int32_t a;
-    float alpha;              // expand: the cache entry's own factor
+    float alpha;              // the cache entry's own factor
 };
-static_assert(sizeof(GemvItem) == 32, "items are read with two 16-byte loads");
+static_assert(sizeof(GemvItem) == 32, "items are read with one 32-byte scalar load");
 
-// columns one expand wavefront covers: 16 KB of Bp whatever the rank
+// columns one expand wavefront covers: 64 times the largest power of two that keeps it within 16 KB of Bp
 inline __host__ __device__ int32_t gemv_expand_width(int32_t rank)
 {
     const int32_t q = 128 / rank_storage(rank);
-    return 64 * (q > 1 ? q : 1);
+    return q >= 16 ? 1024 : q >= 8 ? 512 : q >= 4 ? 256 : q >= 2 ? 128 : 64;
 }
-inline __host__ __device__ int32_t gemv_pack_shrink(int32_t j0, int32_t n_rows) { return j0 | (n_rows << 8); }
+inline __host__ __device__ int32_t gemv_pack_shrink(int32_t j0) { return j0; }
 inline __host__ __device__ int32_t gemv_pack_expand(int32_t col_in_super) { return col_in_super / 64; }
-// rank rows [j0, j0 + n) of a shrink item
+// stored rank rows [j0, j0 + n) of a shrink item
 inline __host__ __device__ void gemv_shrink_rows(const GemvItem &it, int32_t &j0, int32_t &n)
 {
-    j0 = it.a & 0xff;
-    n = it.a >> 8;
+    j0 = it.a;
+    n = GEMV_SHRINK_ROWS;
 }
 // output columns [c0, c1) of expand item `it` in super-chunk `sc` of a projection h_out wide (empty if c0 >= c1)
 inline __host__ __device__ void gemv_expand_cols(const GemvItem &it, int32_t sc, int32_t h_out, int32_t &c0, int32_t &c1)
 {
-    c0 = sc * GEMV_SUPER_COLS + (it.a & 0xf) * 64;
+    c0 = sc * GEMV_SUPER_COLS + it.a * 64;
     const int32_t end = c0 + gemv_expand_width(it.rank), super_end = (sc + 1) * GEMV_SUPER_COLS;
     c1 = end < super_end ? end : super_end;
     if (c1 > h_out) c1 = h_out;
+}
+
+// One GEMV launch serves up to GEMV_MAX_PROJS projections that read the same activations (q, k, v;
+// gate, up): block and unit numbers map to (projection, item) by the two routines below, which the
+// kernels and lora_plan_dump share.
+constexpr int GEMV_MAX_PROJS = 4;
+struct GemvProj {
+    const char *proj_base;    // device: first slab of this (layer, projection)
+    int64_t row_bytes;        // (h_in + h_out) * element size
+    void *y;                  // device [T][h_out], in/out
+    float *y32;               // when set, the update s.v.B goes there as fp32 ([token][h_out]) instead of into y
+    unsigned long long *vw;   // hand-over words of this projection's intermediate (see gemv_kernels.hip)
+    int32_t h_out;
+    int32_t n_super;          // super-chunks: ceil(h_out / GEMV_SUPER_COLS)
+    uint32_t super_magic;     // ceil(2^32 / n_super) (unused when n_super == 1)
+    int32_t unit_end;         // expand units of projections 0 .. this one
+};
+struct GemvArgs {
+    const void *x;            // device [T][h_in]
+    const GemvItem *gs, *ge;  // device: shrink and expand items
+    int32_t *fault;           // raised when a bounded wait gives up
+    int32_t h_in, n_proj, n_gs, n_ge;
+    uint32_t proj_magic;      // ceil(2^32 / n_proj) (unused when n_proj == 1)
+    uint32_t epoch;           // one launch: the number its hand-over words carry (never 0); 0: two launches, no waiting
+    float scale;
+    int32_t phase;            // 0: shrink blocks then expand blocks in one launch; 1: shrink only; 2: expand only
+    GemvProj p[GEMV_MAX_PROJS];
+};
+// floor(v / n) for v < 2^24 and n <= 16 with magic = ceil(2^32 / n), n > 1
+inline __host__ __device__ uint32_t gemv_div(uint32_t v, uint32_t n, uint32_t magic)
+{
+    return n == 1 ? v : (uint32_t)(((uint64_t)v * magic) >> 32);
+}
+inline uint32_t gemv_magic(uint32_t n) { return n > 1 ? (uint32_t)((((uint64_t)1 << 32) + n - 1) / n) : 0; }
+// Shrink block b of a launch with n_proj * n_gs shrink blocks -> (item, projection).  Block b runs on
+// XCD b % 8, each XCD behind its own L2: XCD j takes a run of consecutive (item, projection) pairs,
+// items in list order with their projections side by side, the i-th pair of the run as block 8i + j --
+// the items of a token batch and all their projections read the batch's x rows, which are then
+// fetched from memory by one XCD instead of eight.
+inline __host__ __device__ void gemv_shrink_block(uint32_t b, uint32_t n_gs, uint32_t n_proj, uint32_t proj_magic,
+                                                  uint32_t &item, uint32_t &proj)
+{
+    const uint32_t nb = n_gs * n_proj, j = b & 7;
+    const uint32_t pos = j * (nb >> 3) + (j < (nb & 7) ? j : (nb & 7)) + (b >> 3);
+    item = gemv_div(pos, n_proj, proj_magic);
+    proj = pos - item * n_proj;
+}
+// Expand unit u (over all projections of the launch) -> (projection, item, super-chunk)
+inline __host__ __device__ void gemv_expand_unit(uint32_t u, const GemvProj *p, uint32_t n_proj, uint32_t &proj, uint32_t &item,
+                                                 uint32_t &sc)
+{
+    proj = 0;
+    for (uint32_t q = 1; q < n_proj; ++q) proj += u >= (uint32_t)p[q - 1].unit_end;
+    const uint32_t r = u - (proj ? (uint32_t)p[proj - 1].unit_end : 0u);
+    item = gemv_div(r, (uint32_t)p[proj].n_super, p[proj].super_magic);
+    sc = r - item * (uint32_t)p[proj].n_super;
 }
 
 // Arguments common to the apply kernels of one (layer, projection).
@@ -109,16 +168,13 @@ inline void launch_k(const KernelTimer *tm, int kind, K kernel, dim3 grid, dim3 
 }
 
 // launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16; tm may be null
-hipError_t launch_gemv_shrink(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
-                              const KernelTimer *tm);
-hipError_t launch_gemv_expand(int dtype, const ApplyArgs &a, const GemvItem *items, int n_items, hipStream_t st,
-                              const KernelTimer *tm);
-// shrink and expand in one launch: expand wavefronts load their slab part at once and then poll
-// the intermediate, which travels as 64-bit words {epoch, fp32 bits} in vtag (device, max_tokens
-// rows of v_stride words, never holding a number >= epoch on entry); epoch != 0; `fault` (device
-// int32) is set if a wait gives up
-hipError_t launch_gemv_fused(int dtype, const ApplyArgs &a, const GemvItem *gs, int n_gs, const GemvItem *ge, int n_ge,
-                             unsigned long long *vtag, uint32_t epoch, int32_t *fault, hipStream_t st, const KernelTimer *tm);
+// GEMV shrink and expand of the group's projections: phase 0 as one launch (a.epoch != 0: the expand
+// wavefronts wait for the hand-over words to carry that number), phases 1 and 2 as two
+hipError_t launch_gemv(int dtype, const GemvArgs &a, hipStream_t st, const KernelTimer *tm);
+// bytes of one projection's hand-over words for max_tokens tokens
+size_t gemv_handover_bytes(int dtype, int64_t max_tokens);
+// zeroes the hand-over words of tokens toks[0 .. n) (device list) in `vw`
+hipError_t launch_gemv_clear(int dtype, unsigned long long *vw, const int32_t *toks, int n, hipStream_t st);
 // The projections one tile-shrink launch serves (they read the same x): slab base and row pitch,
 // destination of the intermediate, scratch for k-split partials (splits * n_tile_tok rows of
 // v_stride floats each, unused when the launch does not split).

@@ -22,6 +22,7 @@ from .gen import (  # noqa: F401
     decode,
     decode_heavy,
     decode_paper,
+    decode_qkv,
     prefill,
     mixed,
     stress,

@@ -307,6 +307,17 @@ def decode_heavy(seed: int = 0, n_layers: int = 1) -> Instance:
     )
 
 
+def decode_qkv(seed: int = 0, n_layers: int = 1, n_decode: int = 64) -> Instance:
+    """Not one of the task's configurations: the decode configuration's batch and pool on the three
+    projections q, k, v of the layer, which read the same activations (section 3.1: the adapter
+    work of a layer is that of all its adapted projections) -- what a serving iteration hands to the
+    library as one group."""
+    return make_instance(
+        "decode_qkv", dtype="bf16", seed=seed, projs=[Projection(n, 4096, 4096, 0) for n in ("q", "k", "v")], n_adapters=100,
+        rank_choices=[8, 16, 32, 64, 128], n_decode=n_decode, prompt_lens=[], zipf_alpha=1.0, n_layers=n_layers,
+    )
+
+
 def decode_paper(seed: int = 0, n_layers: int = 1, n_adapters: int = 100, n_decode: int = 64) -> Instance:
     """Not one of the task's configurations: the decode configuration with the paper's own adapter
     population (section 5.1: N_a adapters, N_a / 5 of each of the five ranks, rank drawn uniformly,
@@ -367,4 +378,5 @@ CONFIGS = {
     "small_mixed": small_mixed,
     "decode_heavy": decode_heavy,
     "decode_paper": decode_paper,
+    "decode_qkv": decode_qkv,
 }
