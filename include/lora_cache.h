@@ -314,6 +314,23 @@ int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_pla
 int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
                     void *base_out, float scale, void *stream);
 
+/* lora_apply_plan for callers that cannot allocate device memory or hand any over for scratch: code
+ * whose memory is fixed before it starts (a serving loop with a frozen memory plan, a harness that
+ * forbids allocation, work recorded for later replay).  Same arguments, same result, same kernels;
+ * the intermediate buffers (shrink results, k-split partial sums, hand-over words) do not come from
+ * the cache's pool but from a fixed array of LORA_STATIC_SCRATCH_BYTES (14 MiB) in the library's
+ * device image, which every device the library has run on holds until the process ends.  The call
+ * allocates nothing and frees nothing, on the device or through the runtime.
+ * LORA_E_NOMEM if the plan's batch has more than LORA_STATIC_MAX_TOKENS tokens.
+ * All caches of the process share the one array of their device, and it keeps the last call's
+ * contents: calls on one device must not overlap -- issue them on one stream or order the streams
+ * with events, also across caches (lora_apply_plan and friends use the pool's own scratch and may
+ * overlap with it). */
+#define LORA_STATIC_MAX_TOKENS 4096
+#define LORA_STATIC_SCRATCH_BYTES ((size_t)LORA_STATIC_MAX_TOKENS * LORA_MAX_RANK * (4 + 4 * 4 + 8))
+int lora_apply_plan_static(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x,
+                           void *base_out, float scale, void *stream);
+
 /* The same for a list of (layer, projection, x, base_out): the result is that of n calls of
  * lora_apply_plan in order on `stream` (one iteration's worth of applies with a single trip
  * through the binding).  Up to 4 consecutive entries that read the same x (q, k, v; gate, up) and

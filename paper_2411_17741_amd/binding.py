@@ -131,6 +131,7 @@ _SIGS = {
     "lora_plan_info": (c_int, [c_void_p, POINTER(lora_plan_info_t)]),
     "lora_plan_dump": (c_int, [c_void_p, c_void_p, c_int32, POINTER(lora_plan_unit_t), c_int32, _i32p, _i32p, c_int32, _i32p]),
     "lora_apply_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
+    "lora_apply_plan_static": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_float, c_void_p]),
     "lora_apply_plan_multi": (c_int, [c_void_p, c_void_p, POINTER(lora_apply_desc_t), c_int32, c_float, c_void_p]),
     "lora_linear_plan": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_float, c_void_p, c_size_t, c_void_p]),
     "lora_linear_workspace_bytes": (c_int, [c_void_p, c_void_p, c_int32, POINTER(c_size_t)]),
@@ -485,6 +486,14 @@ def lora_linear_plan(cache, plan, layer: int, proj: int, x: int, Wt: int, y: int
                      workspace: int = 0, workspace_bytes: int = 0) -> int:
     return _lib.lora_linear_plan(cache, plan, layer, proj, c_void_p(x or None), c_void_p(Wt or None), c_void_p(y or None), scale,
                                  c_void_p(workspace or None), workspace_bytes, c_void_p(stream or None))
+
+
+def lora_apply_plan_static(cache, plan, layer: int, proj: int, x: int, base_out: int, scale: float, stream: int = 0) -> int:
+    return _lib.lora_apply_plan_static(cache, plan, layer, proj, c_void_p(x or None), c_void_p(base_out or None), scale,
+                                       c_void_p(stream or None))
+
+
+LORA_STATIC_MAX_TOKENS = 4096
 
 
 def make_descs(entries):

@@ -55,6 +55,41 @@ struct Scratch {
     int *cap_sets;
 };
 
+// The same scratch as a fixed array in the library's image, for lora_apply_plan_static: one set,
+// sized for LORA_STATIC_MAX_TOKENS tokens.  Every device the library runs on holds its own copy
+// at its own address (found once per device with hipGetSymbolAddress; the array's name itself is
+// no device address in host code).
+constexpr size_t STATIC_V_BYTES = sizeof(float) * (size_t)LORA_STATIC_MAX_TOKENS * LORA_MAX_RANK;
+constexpr int64_t STATIC_VPART_ROWS = 4 * (int64_t)LORA_STATIC_MAX_TOKENS;
+constexpr size_t STATIC_VPART_BYTES = sizeof(float) * (size_t)STATIC_VPART_ROWS * LORA_MAX_RANK;
+constexpr size_t STATIC_VTAG_BYTES = sizeof(uint64_t) * (size_t)LORA_STATIC_MAX_TOKENS * LORA_MAX_RANK;  // fp32 words; bf16 takes half
+constexpr size_t STATIC_SCRATCH_BYTES = STATIC_V_BYTES + STATIC_VPART_BYTES + STATIC_VTAG_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+struct StaticScratch {
+    char *ptr = nullptr;   // this device's copy of `scratch`
+    uint32_t epoch = 0;    // one-launch GEMV launches that have used its hand-over words, over all caches of the process
+    unsigned long long cap_id = 0;
+    uint64_t cap_plan = 0;
+    int cap_sets = 0;
+};
+StaticScratch g_static[MAX_DEVICES];
+
+// Once per device, with that device current: the address of its copy, and tagged words that carry no
+// launch number yet.
+int static_scratch_setup(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return LORA_E_INVAL;
+    StaticScratch &ss = g_static[device];
+    if (ss.ptr) return LORA_OK;
+    char *ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return LORA_E_HIP;
+    HIP_TRY(hipMemset(ptr + STATIC_V_BYTES + STATIC_VPART_BYTES, 0, STATIC_VTAG_BYTES));
+    ss.ptr = ptr;
+    return LORA_OK;
+}
 int esize_of(int dtype) { return dtype == LORA_BF16 ? 2 : 4; }
 
 struct Slot {
@@ -708,6 +743,10 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
         g_last_hip = (int)hipGetLastError();
         delete c;
         return LORA_E_HIP;
+    }
+    if (const int rc_s = static_scratch_setup(c->device)) {
+        delete c;
+        return rc_s;
     }
 
     int rc = LORA_OK;
@@ -1529,6 +1568,27 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
     int rc = validate_apply(c, p, layer, proj, x, base_out);
     if (rc != LORA_OK) return rc;
     rc = enqueue_apply(c, p, layer, proj, x, base_out, scale, st);
+    if (rc != LORA_OK) return rc;
+    return fence_applies(c, p, st);
+}
+
+int lora_apply_plan_static(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj, const void *x, void *base_out,
+                           float scale, void *stream)
+{
+    if (!c || !p || !p->in_use || c->host_only) return LORA_E_INVAL;
+    if (p->T > LORA_STATIC_MAX_TOKENS) return LORA_E_NOMEM;  // the fixed scratch does not hold this batch
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = validate_apply(c, p, layer, proj, x, base_out);
+    if (rc != LORA_OK) return rc;
+    StaticScratch &ss = g_static[c->device];  // set up by lora_cache_create on this device
+    if (!ss.ptr) return LORA_E_STATE;
+    const Scratch sc{ss.ptr, STATIC_V_BYTES, 1, ss.ptr + STATIC_V_BYTES, STATIC_VPART_BYTES, STATIC_VPART_ROWS,
+                     ss.ptr + STATIC_V_BYTES + STATIC_VPART_BYTES, STATIC_VTAG_BYTES, &ss.epoch, &ss.cap_id, &ss.cap_plan, &ss.cap_sets};
+    const lora_apply_desc_t d{layer, proj, x, base_out};
+    const bool timing = c->timing;
+    c->timing = false;  // timed launches take events from a pool that may have to grow
+    rc = enqueue_group(c, p, &d, 1, scale, st, sc);
+    c->timing = timing;
     if (rc != LORA_OK) return rc;
     return fence_applies(c, p, st);
 }
