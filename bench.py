@@ -128,7 +128,7 @@ def fused_base(args, inst, pi, xs, ys, n_layers, n_sets, steps, stream) -> dict:
         "metric": "lora_linear_tokens_per_s_per_layer", "value": inst.T / (ms_fused / n_layers * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": steps, "warmup": args.warmup, "ms_per_step": ms_fused, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload] + "; base projection fused (lora_linear_plan), random base weights",
+        "config": {"workload": WORKLOAD_TEXT.get(inst.name, inst.name) + "; base projection fused (lora_linear_plan), random base weights",
                    "tokens": inst.T, "projections": n_proj, "layers_per_step": n_layers, "ms_per_layer": ms_fused / n_layers,
                    "vendor_matmul_then_apply_ms_per_layer": ms_split / n_layers},
         "roofline": {"bound": "mfma", "kernel": "linear", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -539,6 +539,32 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
     spread = {"p10": float(per_layer_us[int(0.1 * (steps - 1))]), "median": float(np.median(per_layer_us)),
               "p90": float(per_layer_us[int(0.9 * (steps - 1))])}
 
+    # the applies of a step recorded into a HIP graph once and replayed (what a decode loop does with its iteration):
+    # same kernels, no host work per launch.  One plan, made outside the capture; fencing off while capturing.
+    graph_replay = None
+    if extras and not args.no_graph:
+        rc, gplan = B.lora_plan_create(h, inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank, sh)
+        B.check(rc, "lora_plan_create")
+        B.check(B.lora_apply_plan_multi(h, gplan, descs, inst.scale, sh), "lora_apply_plan_multi")  # eager once: fills seen as done
+        torch.cuda.synchronize()
+        B.check(B.lora_cache_set_fencing(h, 0))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, capture_error_mode="thread_local"):
+            B.check(B.lora_apply_plan_multi(h, gplan, descs, inst.scale, torch.cuda.current_stream().cuda_stream), "lora_apply_plan_multi (capture)")
+        B.check(B.lora_cache_set_fencing(h, 1))
+        n_rep = max(5, steps)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t_g = time.perf_counter()
+        for _ in range(n_rep):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_replay = {"us_per_layer": (time.perf_counter() - t_g) * 1e6 / n_rep / n_layers, "replays": n_rep,
+                        "eager_us_per_layer": ms_per_layer * 1e3}
+        del g
+        B.check(B.lora_plan_destroy(h, gplan))
+
     # host side of a step: indexing alone, and plan creation (index + validation + staging + enqueue of the upload)
     def host_us(fn, n=50):
         ts = []
@@ -675,7 +701,7 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
         "config": {"workload": WORKLOAD_TEXT[workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
                    "pool_adapters": int(inst.n_adapters), "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
-                   "host_index_us": index_us, "host_plan_create_us": plan_us,
+                   "host_index_us": index_us, "host_plan_create_us": plan_us, "graph_replay": graph_replay,
                    "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": plan_info.n_gemv_shrink_items, "gemv_groups": len(w["groups"])},
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -720,6 +746,7 @@ def main() -> int:
     ap.add_argument("--prewarm-s", type=float, default=1.0, help="seconds of untimed steps before the warm-up steps (a cold GPU ramps its clocks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the graph-replay timing of the step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1\n")
@@ -762,7 +789,6 @@ def main() -> int:
                                  "roofline": fb["roofline"], "kernels": fb["kernels"]}
         out["configs"][name] = sub
     print(json.dumps(out))
-    pi.close()
     return 0
 
 

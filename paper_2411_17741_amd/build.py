@@ -21,6 +21,8 @@ FLAGS = [
     "-munsafe-fp-atomics",
     # keep the compiler from forming packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the leading scalar arguments of a kernel arrive in registers with the wavefront
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -39,6 +39,16 @@ constexpr int WAIT_SPINS = 1 << 16;
 
 template <typename E> constexpr int words_per_token() { return sizeof(E) == 2 ? 64 : 128; }
 
+// 16 bytes of a slab: read once per launch (by the batches of one slot at about the same time), so marked
+// as streaming -- they then do not push the work items and the kernel's own code out of L2 (-4 % on the
+// decode configuration)
+typedef unsigned gv_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_slab16(const char *p)
+{
+    const gv_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const gv_u32x4 *>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 // A work item as a wavefront holds it: every field the same in all lanes and said to be so, so that the
 // fields and the addresses built from them stay in scalar registers; the tokens as four named members
 // (an array indexed by a lane's token number would be kept in scratch memory).
@@ -98,7 +108,7 @@ __device__ __forceinline__ bool fetch_words(const GemvArgs &a, const unsigned lo
             for (int t = 0; t < TB; ++t) out[t] = (uint32_t)w[t];
             return true;
         }
-        __builtin_amdgcn_s_sleep(2);
+        if (spin >= 4) __builtin_amdgcn_s_sleep(2);
     }
     if ((threadIdx.x & 63) == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // pinned host memory
     return false;
@@ -148,19 +158,21 @@ __device__ __forceinline__ void gemv_shrink_item(const GemvArgs &a, const GemvPr
 #pragma unroll
             for (int t = 0; t < NT; ++t) xv[t][u] = *reinterpret_cast<const Chunk<E> *>(xrow[t] + off);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) av[r][u] = *reinterpret_cast<const Chunk<E> *>(arow[r] + off);
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (sizeof(E) == 2) av[r][u].v = load_slab16(arow[r] + off);
+                else av[r][u] = *reinterpret_cast<const Chunk<E> *>(arow[r] + off);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from trading loads in flight for registers
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool ok = c0 + (u * W + kp) * 64 + lane < n_chunks;  // clamped lanes do not count
+            const bool ok = c0 + (u * W + kp) * 64 + lane < n_chunks;  // clamped lanes do not count: their x is zeroed
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int t = 0; t < NT; ++t) {
+                const Chunk<E> xz = ok ? xv[t][u] : zero_chunk<E>();
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float d = dot_chunk_acc(0.f, av[r][u], xv[t][u]);
-                    acc[r][t] += ok ? d : 0.f;
-                }
+                for (int r = 0; r < 4; ++r) acc[r][t] = dot_chunk_acc(acc[r][t], av[r][u], xz);
+            }
         }
     }
     float sum[NV];
@@ -234,7 +246,7 @@ __device__ __forceinline__ void gemv_expand_mfma(const GemvArgs &a, const GemvPr
     for (int q = 0; q < NQ; ++q) {
         const char *bq = Bp + (q < n_q ? q * SPAN * 16 : 0);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) br[q][ks] = *reinterpret_cast<const uint4 *>(bq + boff[ks]);
+        for (int ks = 0; ks < KS; ++ks) br[q][ks] = load_slab16(bq + boff[ks]);
     }
     // base_out: lane (n, r) updates columns 16 * group + 4r .. +3 of the span for token n % 4
     const int t = m & 3, gq = m >> 2;
@@ -269,25 +281,31 @@ __device__ __forceinline__ void gemv_expand_mfma(const GemvArgs &a, const GemvPr
         const uint4 z = make_uint4(0u, 0u, 0u, 0u);
         vop[ks] = __builtin_bit_cast(gv_bf16x8, mine ? w : z);
     }
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
+    auto product = [&](int q) {
         gv_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(gv_bf16x8, br[q][ks]), vop[ks], acc, 0, 0, 0);
-        if (live && q < n_q) {
-            if (pj.y32) {
-                *reinterpret_cast<gv_floatx4 *>(pj.y32 + (size_t)c0 + q * SPAN + yoff) = acc;
-            } else {
-                const unsigned lo = yv[q].x, hi = yv[q].y;
-                gv_bf16x4 o;
-                o[0] = (__bf16)(__uint_as_float(lo << 16) + acc[0]);
-                o[1] = (__bf16)(__uint_as_float(lo & 0xffff0000u) + acc[1]);
-                o[2] = (__bf16)(__uint_as_float(hi << 16) + acc[2]);
-                o[3] = (__bf16)(__uint_as_float(hi & 0xffff0000u) + acc[3]);
-                *reinterpret_cast<gv_bf16x4 *>(const_cast<char *>(ybase) + q * SPAN * 2 + yoff * 2u) = o;
-            }
+        return acc;
+    };
+    if (pj.y32) {  // uniform
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const gv_floatx4 acc = product(q);
+            if (live && q < n_q) *reinterpret_cast<gv_floatx4 *>(pj.y32 + (size_t)c0 + q * SPAN + yoff) = acc;
         }
+        return;
+    }
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const gv_floatx4 acc = product(q);
+        const unsigned lo = yv[q].x, hi = yv[q].y;
+        gv_bf16x4 o;
+        o[0] = (__bf16)(__uint_as_float(lo << 16) + acc[0]);
+        o[1] = (__bf16)(__uint_as_float(lo & 0xffff0000u) + acc[1]);
+        o[2] = (__bf16)(__uint_as_float(hi << 16) + acc[2]);
+        o[3] = (__bf16)(__uint_as_float(hi & 0xffff0000u) + acc[3]);
+        if (live && q < n_q) *reinterpret_cast<gv_bf16x4 *>(const_cast<char *>(ybase) + q * SPAN * 2 + yoff * 2u) = o;
     }
 }
 
@@ -345,28 +363,34 @@ __device__ __forceinline__ void gemv_expand_f32(const GemvArgs &a, const GemvPro
 // wavefronts cannot starve them; waits are bounded all the same.
 // ---------------------------------------------------------------------------------------
 template <typename E>
-__global__ __launch_bounds__(256) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(256) void gemv_kernel(const GemvItem *gs, const GemvItem *ge, uint32_t n_gs, uint32_t n_proj_phase, int32_t ue0,
+                                                   int32_t ue1, int32_t ue2, int32_t ue3, uint32_t n_super_packed, uint32_t sm0, uint32_t sm1,
+                                                   uint32_t sm2, uint32_t sm3, GemvArgs a)
 {
+    // (the scalars in front are the fields of GemvMap one by one: the leading arguments of a kernel arrive in
+    // registers with the wavefront)
     __shared__ float red[4][16];
     __shared__ __attribute__((aligned(16))) uint32_t stage[4][sizeof(E) == 2 ? TB * 64 : TB * 128];
-    const uint32_t n_shrink = a.phase == 2 ? 0u : (uint32_t)(a.n_proj * a.n_gs);
+    const uint32_t n_proj = n_proj_phase & 0xffu, phase = n_proj_phase >> 8;
+    const uint32_t n_shrink = phase == 2 ? 0u : n_proj * n_gs;
     if (blockIdx.x < n_shrink) {
         uint32_t item, proj;
-        gemv_shrink_block(blockIdx.x, (uint32_t)a.n_gs, (uint32_t)a.n_proj, a.proj_magic, item, proj);
-        const ItemU it = load_item(a.gs + item);
+        gemv_shrink_block(blockIdx.x, n_gs, n_proj, item, proj);
+        const ItemU it = load_item(gs + item);
         const GemvProj pj = a.p[proj];
         const int nt = it.n_tok();
         if (nt == 1) gemv_shrink_item<E, 1>(a, pj, it, nt, red);  // uniform over the block
         else if (nt == 2) gemv_shrink_item<E, 2>(a, pj, it, nt, red);
         else gemv_shrink_item<E, 4>(a, pj, it, nt, red);
     } else {
-        if (a.phase == 1) return;
+        if (phase == 1) return;
         const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const uint32_t unit = (blockIdx.x - n_shrink) * 4 + w;
-        if (unit >= (uint32_t)a.p[a.n_proj - 1].unit_end) return;
+        const GemvMap m{gs, ge, n_gs, n_proj_phase, {ue0, ue1, ue2, ue3}, n_super_packed, {sm0, sm1, sm2, sm3}};
+        if (unit >= (uint32_t)ue3) return;  // (entries past the group repeat its last)
         uint32_t proj, item, sc;
-        gemv_expand_unit(unit, a.p, (uint32_t)a.n_proj, proj, item, sc);
-        const ItemU it = load_item(a.ge + item);
+        gemv_expand_unit(unit, m, proj, item, sc);
+        const ItemU it = load_item(ge + item);
         const GemvProj pj = a.p[proj];
         int c0, c1;
         gemv_expand_cols(as_item(it), (int)sc, pj.h_out, c0, c1);
@@ -408,21 +432,25 @@ hipError_t launch_gemv_clear(int dtype, unsigned long long *vw, const int32_t *t
     return hipGetLastError();
 }
 
-hipError_t launch_gemv(int dtype, const GemvArgs &a, hipStream_t st, const KernelTimer *tm)
+hipError_t launch_gemv(int dtype, const GemvMap &m, const GemvArgs &a, hipStream_t st, const KernelTimer *tm)
 {
-    if (a.n_gs <= 0 || a.n_ge <= 0 || a.n_proj <= 0) return hipSuccess;
-    const int n_shrink = a.n_proj * a.n_gs, n_expand = (a.p[a.n_proj - 1].unit_end + 3) / 4;
-    auto go = [&](int phase, int blocks, int kind) {
-        GemvArgs b = a;
-        b.phase = phase;
-        if (dtype == LORA_BF16) launch_k(tm, kind, gemv_kernel<__bf16>, dim3(blocks), dim3(256), st, b);
-        else launch_k(tm, kind, gemv_kernel<float>, dim3(blocks), dim3(256), st, b);
+    const int n_proj = (int)(m.n_proj_phase & 0xffu);
+    if (m.n_gs == 0 || a.n_ge <= 0 || n_proj <= 0) return hipSuccess;
+    const int n_shrink = n_proj * (int)m.n_gs, n_expand = (m.unit_end[GEMV_MAX_PROJS - 1] + 3) / 4;
+    auto go = [&](uint32_t phase, int blocks, int kind) {
+        const uint32_t pp = (uint32_t)n_proj | (phase << 8);
+        if (dtype == LORA_BF16)
+            launch_k(tm, kind, gemv_kernel<__bf16>, dim3(blocks), dim3(256), st, m.gs, m.ge, m.n_gs, pp, m.unit_end[0], m.unit_end[1],
+                     m.unit_end[2], m.unit_end[3], m.n_super_packed, m.super_magic[0], m.super_magic[1], m.super_magic[2], m.super_magic[3], a);
+        else
+            launch_k(tm, kind, gemv_kernel<float>, dim3(blocks), dim3(256), st, m.gs, m.ge, m.n_gs, pp, m.unit_end[0], m.unit_end[1],
+                     m.unit_end[2], m.unit_end[3], m.n_super_packed, m.super_magic[0], m.super_magic[1], m.super_magic[2], m.super_magic[3], a);
     };
     if (a.epoch) {
-        go(0, n_shrink + n_expand, LORA_K_GEMV_FUSED);
+        go(0u, n_shrink + n_expand, LORA_K_GEMV_FUSED);
     } else {
-        go(1, n_shrink, LORA_K_GEMV_SHRINK);
-        go(2, n_expand, LORA_K_GEMV_EXPAND);
+        go(1u, n_shrink, LORA_K_GEMV_SHRINK);
+        go(2u, n_expand, LORA_K_GEMV_EXPAND);
     }
     return hipGetLastError();
 }

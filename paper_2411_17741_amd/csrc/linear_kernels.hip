@@ -31,6 +31,14 @@
 // Tokens on the GEMV path sit in row tiles without an adapter; their adapter term is computed by the
 // GEMV kernels beforehand into the (zeroed) output rows, and this kernel adds it to the accumulators of
 // those rows before the one rounding of the stored value (row tiles marked a = 1).
+//
+// One block fills a CU (its two stages take 144 KB of LDS), so a grid of N tiles runs in ceil(N / CUs)
+// rounds and the last round may be nearly empty (368 tiles on 256 CUs: a second round of 112).  The tiles of
+// that last round are therefore split along k into S = 2 or 4 parts, one block each, as many as fit one round:
+// the last part of a tile is its owner -- it is dispatched last, so the other parts are running or done
+// when it waits for them, and they wait for nothing -- and adds the other parts' fp32 accumulators, which
+// travel through a scratch area as device-scope atomic stores and loads (past the per-XCD L2s) behind a
+// flag per part that the owner resets; its wait is bounded and raises the cache's fault flag.
 #include <algorithm>
 
 #include "lora_device.h"
@@ -51,14 +59,29 @@ __device__ __forceinline__ int row_tile_token(const int32_t *tok_list, const Dev
     return tile_token_of(tok_list, it, ti);
 }
 
+// split of the last round: blocks [0, n_whole) work on whole tiles; block n_whole + S * j + p on part p of tile n_whole + j
+struct LinearSplit {
+    int n_whole, parts;          // parts = 1: no split
+    unsigned long long *partial;  // [tile j][part p < parts - 1][accumulator 32][half 2][thread 512] 8-byte words
+    uint32_t *flags;              // [tile j][part p < parts - 1], zero between launches
+    int32_t *fault;
+};
+
 __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __bf16 *__restrict__ Wt,
-                                                           const DevItem *__restrict__ tiles, int n_rt, int n_mt)
+                                                           const DevItem *__restrict__ tiles, int n_rt, int n_mt, LinearSplit sp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // two stages
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 15, g = lane >> 4;
     const int rh = w & 1, cq = w >> 1;
-    const int bm = (int)blockIdx.x % n_mt, bn = (int)blockIdx.x / n_mt;
+    int tile_no = (int)blockIdx.x, part = 0, tail = -1;
+    if (tile_no >= sp.n_whole) {
+        tail = (tile_no - sp.n_whole) / sp.parts;
+        part = (tile_no - sp.n_whole) - tail * sp.parts;
+        tile_no = sp.n_whole + tail;
+    }
+    const bool owner = part == sp.parts - 1 || tail < 0;
+    const int bm = tile_no % n_mt, bn = tile_no / n_mt;
     const int n0 = bn * LBN;
 
     // the four row tiles of the block (a missing one counts as empty), and the two of this wavefront's
@@ -81,6 +104,8 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
     const __bf16 *x = static_cast<const __bf16 *>(a.x);
     __bf16 *y = static_cast<__bf16 *>(a.y);
     const int n_k = a.h_in / LBK;
+    // this block's stages of the k walk
+    const int k_lo = tail < 0 ? 0 : n_k * part / sp.parts, k_hi = tail < 0 ? n_k : n_k * (part + 1) / sp.parts;
 
     // loader: wavefront w brings rows 32w + 8q + lane/8, q = 0..3, of both x and Wt: instruction q writes
     // 8 rows x 128 bytes at the wavefront-uniform LDS address of its first row, lane l to slot l%8 of
@@ -121,17 +146,18 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[mb][nb][e] = 0.f;
 
-    load_stage(0, 0);
+    load_stage(k_lo, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     // operand reads: row R, k piece 4ks + g sits in slot (4ks + g) ^ ((R/2) % 8); R/2 % 8 = m/2 for all of a lane's rows
     const int swz = (m >> 1) & 7;
-    for (int kt = 0; kt < n_k; ++kt) {
+    for (int kt = k_lo; kt < k_hi; ++kt) {
         // the next stage is requested before this one is multiplied, into the buffer that was read
         // in the previous iteration (past the end: the last stage again, unconditionally)
-        load_stage(min(kt + 1, n_k - 1), (kt + 1) & 1);
-        const unsigned char *sa = lds + (kt & 1) * L_STAGE + (128 * rh + m) * LROW;
-        const unsigned char *sb = lds + (kt & 1) * L_STAGE + L_A + (64 * cq + m) * LROW;
+        const int buf = (kt - k_lo) & 1;
+        load_stage(min(kt + 1, k_hi - 1), buf ^ 1);
+        const unsigned char *sa = lds + buf * L_STAGE + (128 * rh + m) * LROW;
+        const unsigned char *sb = lds + buf * L_STAGE + L_A + (64 * cq + m) * LROW;
         // (The compiler's own order -- operand reads in twos and fours between groups of eight products -- is
         // as fast as reading the operands of every group one group ahead by hand.)
 #pragma unroll
@@ -148,6 +174,63 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's part of the next stage has landed
         __syncthreads();
+    }
+
+    // ---- a tile split along k: the parts hand their accumulators to the owner
+    if (tail >= 0) {
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+        const size_t per_part = (size_t)32 * 2 * 512;  // words
+        if (!owner) {
+            unsigned long long *dst = sp.partial + ((size_t)tail * (sp.parts - 1) + part) * per_part + tid;
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const floatx4 c = acc[mb][nb];
+                    const floatx2 lo = {c[0], c[1]}, hi = {c[2], c[3]};
+                    __hip_atomic_store(dst + ((mb * 4 + nb) * 2 + 0) * 512, __builtin_bit_cast(unsigned long long, lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(dst + ((mb * 4 + nb) * 2 + 1) * 512, __builtin_bit_cast(unsigned long long, hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores above have been performed where every XCD sees them
+            __syncthreads();
+            if (tid == 0) __hip_atomic_store(sp.flags + tail * (sp.parts - 1) + part, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        __shared__ int got_all;
+        if (tid == 0) {
+            int ok = 1;
+            for (int p = 0; p < sp.parts - 1 && ok; ++p) {
+                ok = 0;
+                for (int spin = 0; spin < (1 << 20); ++spin) {
+                    if (__hip_atomic_load(sp.flags + tail * (sp.parts - 1) + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                        ok = 1;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+            }
+            if (!ok) __hip_atomic_store(sp.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // pinned host memory
+            got_all = ok;
+        }
+        __syncthreads();
+        if (got_all) {
+            for (int p = 0; p < sp.parts - 1; ++p) {
+                const unsigned long long *src = sp.partial + ((size_t)tail * (sp.parts - 1) + p) * per_part + tid;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        const floatx2 lo = __builtin_bit_cast(floatx2, __hip_atomic_load(src + ((mb * 4 + nb) * 2 + 0) * 512, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                        const floatx2 hi = __builtin_bit_cast(floatx2, __hip_atomic_load(src + ((mb * 4 + nb) * 2 + 1) * 512, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                        acc[mb][nb][0] += lo[0];
+                        acc[mb][nb][1] += lo[1];
+                        acc[mb][nb][2] += hi[0];
+                        acc[mb][nb][3] += hi[1];
+                    }
+            }
+        }
+        __syncthreads();
+        if (tid < sp.parts - 1) __hip_atomic_store(sp.flags + tail * (sp.parts - 1) + tid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- the adapter slab.  Bp operands of a row tile: granule 4ks + g (the 8 ranks a lane's operand holds,
@@ -307,8 +390,28 @@ hipError_t launch_zero_rows(void *y, const int32_t *toks, int n, int h_out, hipS
     return hipGetLastError();
 }
 
-hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, hipStream_t st,
-                               const KernelTimer *tm)
+// parts the tiles of the last round are split into (1: none), and how many tiles that round has
+static void linear_split_shape(int n_tiles, int n_k, int n_cu, int &parts, int &n_tail)
+{
+    n_tail = n_tiles % n_cu;
+    parts = 1;
+    if (n_tail == 0) return;
+    const int fit = n_cu / n_tail;  // blocks per tile that still fit one round
+    if (fit >= 4 && n_k % 4 == 0) parts = 4;
+    else if (fit >= 2 && n_k % 2 == 0) parts = 2;
+    if (parts == 1) n_tail = 0;
+}
+
+size_t linear_split_bytes(int n_rt, int h_in, int h_out, int n_cu)
+{
+    int parts, n_tail;
+    linear_split_shape(((n_rt + 3) / 4) * ((h_out + LBN - 1) / LBN), h_in / LBK, n_cu, parts, n_tail);
+    return (size_t)n_tail * (parts - 1) * 32 * 2 * 512 * sizeof(unsigned long long);
+}
+
+hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, void *split_scratch,
+                               size_t split_scratch_bytes, uint32_t *split_flags, int n_split_flags, int32_t *fault, int n_cu,
+                               hipStream_t st, const KernelTimer *tm)
 {
     if (n_rt <= 0) return hipSuccess;
     static bool attr_set = false;
@@ -318,15 +421,21 @@ hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int n_mt = (n_rt + 3) / 4, n_nt = (a.h_out + LBN - 1) / LBN;
+    const int n_mt = (n_rt + 3) / 4, n_nt = (a.h_out + LBN - 1) / LBN, n_tiles = n_mt * n_nt;
+    int parts, n_tail;
+    linear_split_shape(n_tiles, a.h_in / LBK, n_cu, parts, n_tail);
+    if (parts > 1 && (linear_split_bytes(n_rt, a.h_in, a.h_out, n_cu) > split_scratch_bytes || n_tail * (parts - 1) > n_split_flags || !split_scratch))
+        parts = 1, n_tail = 0;  // no room for the partial sums: whole tiles only
+    const LinearSplit sp{n_tiles - n_tail, parts, static_cast<unsigned long long *>(split_scratch), split_flags, fault};
+    const int blocks = n_tiles - n_tail + n_tail * parts;
     hipEvent_t s = nullptr, e = nullptr;
     if (tm) tm->pair(tm->ctx, LORA_K_LINEAR, &s, &e);
     if (s && e)
-        hipExtLaunchKernelGGL(linear_tiles_kernel, dim3(n_mt * n_nt), dim3(512), 2 * L_STAGE, st, s, e, 0, a,
-                              static_cast<const __bf16 *>(Wt), row_tiles, n_rt, n_mt);
+        hipExtLaunchKernelGGL(linear_tiles_kernel, dim3(blocks), dim3(512), 2 * L_STAGE, st, s, e, 0, a,
+                              static_cast<const __bf16 *>(Wt), row_tiles, n_rt, n_mt, sp);
     else
-        hipLaunchKernelGGL(linear_tiles_kernel, dim3(n_mt * n_nt), dim3(512), 2 * L_STAGE, st, a, static_cast<const __bf16 *>(Wt),
-                           row_tiles, n_rt, n_mt);
+        hipLaunchKernelGGL(linear_tiles_kernel, dim3(blocks), dim3(512), 2 * L_STAGE, st, a, static_cast<const __bf16 *>(Wt),
+                           row_tiles, n_rt, n_mt, sp);
     return hipGetLastError();
 }
 

@@ -28,6 +28,7 @@ constexpr int N_STAGES = 2;
 constexpr int N_APPLY_EVENTS = 64;
 constexpr size_t ALIGN = 256;
 constexpr int MAX_K_SPLITS = 8;
+constexpr int N_LINEAR_FLAGS = 1024;  // split-off parts of lora_linear_plan's last round of tiles: fewer than CUs x 3
 constexpr double TILE_PATH_FIXED_US = 25.0;          // what the three launches of the tile path cost beside their work
 constexpr double TILE_PATH_L2_BYTES_PER_US = 10e6;  // rate at which repeated passes over a slab come out of L2
 constexpr int N_VSETS = lora::MAX_SHRINK_PROJS;  // applies that share their input run shrink-first, each with its own intermediate
@@ -173,6 +174,7 @@ struct lora_cache {
     uint64_t stage_next = 0;
 
     int device = 0;  // the device that was current at lora_cache_create
+    int n_cu = 256;  // its compute units
     bool fencing = true;
     int64_t apply_seq = 0;
     hipEvent_t apply_ev[N_APPLY_EVENTS] = {};
@@ -274,8 +276,8 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.stage_cap = align_up(max_part) + ALIGN;
 
     size_t cur = align_up(c.layer_stride * (size_t)c.n_layers);
-    c.off_fault = cur;
-    cur += ALIGN;
+    c.off_fault = cur;  // (once the fault word; now the flags of the fused linear kernel's split tiles)
+    cur += align_up(sizeof(uint32_t) * N_LINEAR_FLAGS);
     c.off_v = cur;
     c.v_set_bytes = align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
     cur += c.v_set_bytes * N_VSETS;
@@ -744,6 +746,11 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
         delete c;
         return LORA_E_HIP;
     }
+    {
+        int n_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && n_cu > 0) c->n_cu = n_cu;
+        else (void)hipGetLastError();
+    }
     if (const int rc_s = static_scratch_setup(c->device)) {
         delete c;
         return rc_s;
@@ -754,7 +761,8 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
     if (hipHostMalloc(reinterpret_cast<void **>(&c->fault_host), 64, hipHostMallocMapped) != hipSuccess ||
         hipHostGetDevicePointer(reinterpret_cast<void **>(&c->fault_dev), c->fault_host, 0) != hipSuccess ||
         (*c->fault_host = 0, false) ||
-        hipMemset(c->pool + c->off_vtag, 0, c->vtag_set_bytes * N_VSETS) != hipSuccess) {
+        hipMemset(c->pool + c->off_vtag, 0, c->vtag_set_bytes * N_VSETS) != hipSuccess ||
+        hipMemset(c->pool + c->off_fault, 0, sizeof(uint32_t) * N_LINEAR_FLAGS) != hipSuccess) {
         g_last_hip = (int)hipGetLastError();
         delete c;
         return LORA_E_HIP;
@@ -1343,22 +1351,24 @@ int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_pla
     // the GEMV launch of this projection alone: blocks and units mapped to items as the kernel maps them
     for (uint32_t b = 0; b < (uint32_t)p->n_gs; ++b) {
         uint32_t item, pj;
-        lora::gemv_shrink_block(b, (uint32_t)p->n_gs, 1u, 0u, item, pj);
+        lora::gemv_shrink_block(b, (uint32_t)p->n_gs, 1u, item, pj);
         int32_t j0, n;
         lora::gemv_shrink_rows(gs[item], j0, n);
         const int32_t off = nt, cnt = gemv_tokens(gs[item]);
         put_unit(LORA_UNIT_GEMV_SHRINK, off, cnt, gs[item].row, gs[item].rank, j0, j0 + n, (int32_t)b, gs[item].alpha);
     }
-    lora::GemvProj gp{};
-    gp.h_out = c->proj[proj].h_out;
-    gp.n_super = (gp.h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
-    gp.super_magic = lora::gemv_magic((uint32_t)gp.n_super);
-    gp.unit_end = p->n_ge * gp.n_super;
-    for (uint32_t u = 0; u < (uint32_t)gp.unit_end; ++u) {
+    lora::GemvMap gm{};
+    const int32_t h_out = c->proj[proj].h_out, n_super = (h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
+    for (int i = 0; i < lora::GEMV_MAX_PROJS; ++i) {
+        gm.unit_end[i] = p->n_ge * n_super;
+        gm.n_super_packed |= (uint32_t)n_super << (8 * i);
+        gm.super_magic[i] = lora::gemv_magic((uint32_t)n_super);
+    }
+    for (uint32_t u = 0; u < (uint32_t)gm.unit_end[0]; ++u) {
         uint32_t pj, item, sc;
-        lora::gemv_expand_unit(u, &gp, 1u, pj, item, sc);
+        lora::gemv_expand_unit(u, gm, pj, item, sc);
         int32_t c0, c1;
-        lora::gemv_expand_cols(ge[item], (int32_t)sc, gp.h_out, c0, c1);
+        lora::gemv_expand_cols(ge[item], (int32_t)sc, h_out, c0, c1);
         if (c0 >= c1) continue;  // the wavefront returns at once
         const int32_t off = nt, cnt = gemv_tokens(ge[item]);
         put_unit(LORA_UNIT_GEMV_EXPAND, off, cnt, ge[item].row, ge[item].rank, c0, c1, 0, ge[item].alpha);
@@ -1410,15 +1420,15 @@ static int enqueue_gemv(lora_cache_t *c, lora_plan_t *p, const lora::ApplyArgs *
 {
     if (p->n_gs <= 0) return LORA_OK;
     lora::GemvArgs ga{};
+    lora::GemvMap gm{};
     ga.x = a[0].x;
-    ga.gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
-    ga.ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
+    gm.gs = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_gs);
+    gm.ge = reinterpret_cast<const lora::GemvItem *>(p->dev + p->off_ge);
+    gm.n_gs = (uint32_t)p->n_gs;
+    gm.n_proj_phase = (uint32_t)n;
     ga.fault = c->fault_dev;
     ga.h_in = a[0].h_in;
-    ga.n_proj = n;
-    ga.n_gs = p->n_gs;
     ga.n_ge = p->n_ge;
-    ga.proj_magic = lora::gemv_magic((uint32_t)n);
     ga.scale = a[0].scale;
     int64_t units = 0;
     for (int i = 0; i < lora::GEMV_MAX_PROJS; ++i) {
@@ -1430,10 +1440,12 @@ static int enqueue_gemv(lora_cache_t *c, lora_plan_t *p, const lora::ApplyArgs *
         q.y32 = y32 ? y32[k] : nullptr;
         q.vw = reinterpret_cast<unsigned long long *>(sc.vtag + (size_t)k * sc.vtag_set_bytes);
         q.h_out = a[k].h_out;
-        q.n_super = (a[k].h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
-        q.super_magic = lora::gemv_magic((uint32_t)q.n_super);
-        if (i < n) units += (int64_t)p->n_ge * q.n_super;
-        q.unit_end = (int32_t)units;
+        const int32_t n_super = (a[k].h_out + lora::GEMV_SUPER_COLS - 1) / lora::GEMV_SUPER_COLS;
+        if (n_super > 255) return LORA_E_INVAL;  // beyond the kernels' unit arithmetic
+        gm.n_super_packed |= (uint32_t)n_super << (8 * i);
+        gm.super_magic[i] = lora::gemv_magic((uint32_t)n_super);
+        if (i < n) units += (int64_t)p->n_ge * n_super;
+        gm.unit_end[i] = (int32_t)std::min<int64_t>(units, INT32_MAX);
     }
     if (units >= (1 << 24) || (int64_t)p->n_gs * n >= (1 << 24)) return LORA_E_INVAL;  // beyond the kernels' unit arithmetic
     // (after 2^32 - 1 one-launch applies the numbers would repeat: two launches from then on)
@@ -1463,7 +1475,7 @@ static int enqueue_gemv(lora_cache_t *c, lora_plan_t *p, const lora::ApplyArgs *
         }
         ga.epoch = ++*sc.epoch;
     }
-    HIP_TRY(lora::launch_gemv(c->dtype, ga, st, tm));
+    HIP_TRY(lora::launch_gemv(c->dtype, gm, ga, st, tm));
     return LORA_OK;
 }
 
@@ -1659,7 +1671,10 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
     // base product of every token + adapter product of the tiles (+ the term just computed for the others)
     lora::ApplyArgs lin = a;
     lin.tok_list = reinterpret_cast<const int32_t *>(p->dev + p->off_lin_tok);
-    HIP_TRY(lora::launch_linear_tiles(lin, Wt, reinterpret_cast<const lora::DevItem *>(p->dev + p->off_lin_tiles), p->n_lin_tiles, st, tm));
+    // (the partial sums of split tiles go where the tile shrink's k-split partials went: that kernel is done)
+    HIP_TRY(lora::launch_linear_tiles(lin, Wt, reinterpret_cast<const lora::DevItem *>(p->dev + p->off_lin_tiles), p->n_lin_tiles,
+                                      c->pool + c->off_vpart, c->vpart_set_bytes * N_VSETS, reinterpret_cast<uint32_t *>(c->pool + c->off_fault),
+                                      N_LINEAR_FLAGS, c->fault_dev, c->n_cu, st, tm));
     const int64_t seq = ++c->apply_seq;
     ++c->stats.applies;
     for (int32_t sl : p->slots) {

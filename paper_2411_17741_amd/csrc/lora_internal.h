@@ -90,49 +90,58 @@ struct GemvProj {
     float *y32;               // when set, the update s.v.B goes there as fp32 ([token][h_out]) instead of into y
     unsigned long long *vw;   // hand-over words of this projection's intermediate (see gemv_kernels.hip)
     int32_t h_out;
-    int32_t n_super;          // super-chunks: ceil(h_out / GEMV_SUPER_COLS)
-    uint32_t super_magic;     // ceil(2^32 / n_super) (unused when n_super == 1)
-    int32_t unit_end;         // expand units of projections 0 .. this one
+    int32_t pad;
+};
+// What a wavefront needs to find its work item, apart from the rest: the kernels take it as leading
+// scalar arguments, which the hardware hands over in registers at wavefront start (no load to wait for
+// before the item's own load can go out).
+struct GemvMap {
+    const GemvItem *gs, *ge;  // device: shrink and expand items
+    uint32_t n_gs;
+    uint32_t n_proj_phase;    // n_proj | phase << 8; phase 0: shrink blocks then expand blocks in one launch; 1: shrink only; 2: expand only
+    int32_t unit_end[GEMV_MAX_PROJS];      // expand units of projections 0 .. p (entries past the group repeat the last)
+    uint32_t n_super_packed;               // super-chunks of projection p, ceil(h_out / GEMV_SUPER_COLS) (< 256), in byte p
+    uint32_t super_magic[GEMV_MAX_PROJS];  // ceil(2^32 / n_super) (unused when n_super == 1)
 };
 struct GemvArgs {
     const void *x;            // device [T][h_in]
-    const GemvItem *gs, *ge;  // device: shrink and expand items
     int32_t *fault;           // raised when a bounded wait gives up
-    int32_t h_in, n_proj, n_gs, n_ge;
-    uint32_t proj_magic;      // ceil(2^32 / n_proj) (unused when n_proj == 1)
+    int32_t h_in, n_ge;
     uint32_t epoch;           // one launch: the number its hand-over words carry (never 0); 0: two launches, no waiting
     float scale;
-    int32_t phase;            // 0: shrink blocks then expand blocks in one launch; 1: shrink only; 2: expand only
     GemvProj p[GEMV_MAX_PROJS];
 };
-// floor(v / n) for v < 2^24 and n <= 16 with magic = ceil(2^32 / n), n > 1
+// floor(v / n) for v < 2^24 and n <= 255 with magic = ceil(2^32 / n), n > 1
 inline __host__ __device__ uint32_t gemv_div(uint32_t v, uint32_t n, uint32_t magic)
 {
     return n == 1 ? v : (uint32_t)(((uint64_t)v * magic) >> 32);
 }
 inline uint32_t gemv_magic(uint32_t n) { return n > 1 ? (uint32_t)((((uint64_t)1 << 32) + n - 1) / n) : 0; }
+// one of four values by an index 0..3 (as selects: an array indexed by a run-time number would live in scratch memory on the device)
+template <typename T> inline __host__ __device__ T gemv_sel4(uint32_t i, T v0, T v1, T v2, T v3)
+{
+    return i == 0 ? v0 : (i == 1 ? v1 : (i == 2 ? v2 : v3));
+}
 // Shrink block b of a launch with n_proj * n_gs shrink blocks -> (item, projection).  Block b runs on
 // XCD b % 8, each XCD behind its own L2: XCD j takes a run of consecutive (item, projection) pairs,
 // items in list order with their projections side by side, the i-th pair of the run as block 8i + j --
 // the items of a token batch and all their projections read the batch's x rows, which are then
 // fetched from memory by one XCD instead of eight.
-inline __host__ __device__ void gemv_shrink_block(uint32_t b, uint32_t n_gs, uint32_t n_proj, uint32_t proj_magic,
-                                                  uint32_t &item, uint32_t &proj)
+inline __host__ __device__ void gemv_shrink_block(uint32_t b, uint32_t n_gs, uint32_t n_proj, uint32_t &item, uint32_t &proj)
 {
     const uint32_t nb = n_gs * n_proj, j = b & 7;
     const uint32_t pos = j * (nb >> 3) + (j < (nb & 7) ? j : (nb & 7)) + (b >> 3);
-    item = gemv_div(pos, n_proj, proj_magic);
+    item = n_proj == 1 ? pos : (n_proj == 2 ? pos >> 1 : (n_proj == 4 ? pos >> 2 : gemv_div(pos, 3u, 0x55555556u)));
     proj = pos - item * n_proj;
 }
 // Expand unit u (over all projections of the launch) -> (projection, item, super-chunk)
-inline __host__ __device__ void gemv_expand_unit(uint32_t u, const GemvProj *p, uint32_t n_proj, uint32_t &proj, uint32_t &item,
-                                                 uint32_t &sc)
+inline __host__ __device__ void gemv_expand_unit(uint32_t u, const GemvMap &m, uint32_t &proj, uint32_t &item, uint32_t &sc)
 {
-    proj = 0;
-    for (uint32_t q = 1; q < n_proj; ++q) proj += u >= (uint32_t)p[q - 1].unit_end;
-    const uint32_t r = u - (proj ? (uint32_t)p[proj - 1].unit_end : 0u);
-    item = gemv_div(r, (uint32_t)p[proj].n_super, p[proj].super_magic);
-    sc = r - item * (uint32_t)p[proj].n_super;
+    proj = (u >= (uint32_t)m.unit_end[0]) + (u >= (uint32_t)m.unit_end[1]) + (u >= (uint32_t)m.unit_end[2]);  // < n_proj for u < unit_end[n_proj - 1]
+    const uint32_t r = u - gemv_sel4<uint32_t>(proj, 0u, (uint32_t)m.unit_end[0], (uint32_t)m.unit_end[1], (uint32_t)m.unit_end[2]);
+    const uint32_t n_super = (m.n_super_packed >> (8 * proj)) & 0xffu;
+    item = gemv_div(r, n_super, gemv_sel4(proj, m.super_magic[0], m.super_magic[1], m.super_magic[2], m.super_magic[3]));
+    sc = r - item * n_super;
 }
 
 // Arguments common to the apply kernels of one (layer, projection).
@@ -170,7 +179,7 @@ inline void launch_k(const KernelTimer *tm, int kind, K kernel, dim3 grid, dim3 
 // launches (all asynchronous on `st`); dtype is LORA_F32 or LORA_BF16; tm may be null
 // GEMV shrink and expand of the group's projections: phase 0 as one launch (a.epoch != 0: the expand
 // wavefronts wait for the hand-over words to carry that number), phases 1 and 2 as two
-hipError_t launch_gemv(int dtype, const GemvArgs &a, hipStream_t st, const KernelTimer *tm);
+hipError_t launch_gemv(int dtype, const GemvMap &m, const GemvArgs &a, hipStream_t st, const KernelTimer *tm);
 // bytes of one projection's hand-over words for max_tokens tokens
 size_t gemv_handover_bytes(int dtype, int64_t max_tokens);
 // zeroes the hand-over words of tokens toks[0 .. n) (device list) in `vw`
@@ -200,8 +209,13 @@ hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_ti
 // y = x . Wt^T + adapter update for row tiles (tiles of the plan, then plain runs of the other tokens:
 // rank 0); a.tok_list must be the list the row tiles index; a.v holds the shrink results
 hipError_t launch_zero_rows(void *y, const int32_t *toks, int n, int h_out, hipStream_t st);  // y bf16 [..][h_out]
-hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, hipStream_t st,
-                               const KernelTimer *tm);
+// The tiles of the grid's last, partly filled round are split along k over several blocks when
+// split_scratch (device, linear_split_bytes() bytes for this shape) and split_flags (device, zero between
+// launches, one per split-off part) have room; fault: raised when the bounded wait for a part gives up.
+size_t linear_split_bytes(int n_rt, int h_in, int h_out, int n_cu);
+hipError_t launch_linear_tiles(const ApplyArgs &a, const void *Wt, const DevItem *row_tiles, int n_rt, void *split_scratch,
+                               size_t split_scratch_bytes, uint32_t *split_flags, int n_split_flags, int32_t *fault, int n_cu,
+                               hipStream_t st, const KernelTimer *tm);
 // A [h_in][r] / B [r][h_out] (16-byte aligned; device memory, or pinned host memory as the device
 // sees it: from_host) -> slab layout
 hipError_t launch_repack(int dtype, const void *src_A, const void *src_B, void *slab, int32_t h_in, int32_t h_out,
