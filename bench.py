@@ -35,12 +35,15 @@ WORKLOAD_TEXT = {
     "decode_qkv": "decode_qkv (extra): the decode configuration's batch on the projections q, k, v (4096->4096 bf16 each, same activations), applied as one group",
     "decode_paper": "decode_paper (extra): one-token requests, one 4096->4096 bf16 projection, the paper's adapter population: --adapters N_a, N_a/5 of each rank 8..128, rank uniform, power law within the rank",
 }
-# HBM bytes per launch of a workload's dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs, scaled
-# by what the same counters read for a plain copy; figures and commands in profiles/gemv_fused_decode_traffic.txt and
-# profiles/tile_and_gemv_kernels_traffic.txt).  A counter run cannot happen inside this process, so the figures
-# measured for the same commands are carried here.
-MEASURED_TRAFFIC = {("decode", "gemv_fused"): 25.37e6, ("prefill", "mfma_shrink"): 63.8e6, ("prefill", "mfma_expand"): 146.8e6, ("mixed", "mfma_expand"): 662.8e6,
-                    ("stress", "gemv_fused"): 218.2e6, ("decode_heavy", "gemv_expand"): 139.2e6}  # (decode_heavy: measured for the two-launch form, --gemv split)
+# HBM bytes per launch (average over a layer's launches of that kernel) from rocprofv3 counter runs of this same
+# script (FETCH_SIZE and WRITE_SIZE, each in a run of its own, scaled by what the same counters read for a plain
+# 256 MiB copy).  A counter run cannot happen inside this process, so the figures measured for the same workloads
+# are carried here; the line names their source, and they are left out when the flags change what is launched.
+TRAFFIC_SOURCE = "profiles/kernel_traffic_all_workloads.txt"
+MEASURED_TRAFFIC = {("decode", "gemv_fused"): 24.94e6, ("decode_qkv", "gemv_fused"): 72.16e6, ("prefill", "mfma_shrink"): 63.82e6,
+                    ("prefill", "mfma_expand"): 147.43e6, ("mixed", "mfma_expand"): 661.87e6, ("mixed", "mfma_shrink"): 374.25e6,
+                    ("mixed", "gemv_fused"): 178.28e6, ("stress", "gemv_fused"): 357.29e6, ("stress", "mfma_expand"): 138.43e6,
+                    ("stress", "mfma_shrink"): 72.46e6}
 DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32, "decode_qkv": 16}
 DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100, "decode_qkv": 100}
 
@@ -620,6 +623,7 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
             "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get((workload, dom)) if args.gemv == "auto" and not args.mfma_min_tokens else None,
+            "traffic_source": TRAFFIC_SOURCE if args.gemv == "auto" and not args.mfma_min_tokens and (workload, dom) in MEASURED_TRAFFIC else None,
             "avg_launch_us": kernels[dom]["avg_us"], "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
         }
 
