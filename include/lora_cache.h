@@ -63,6 +63,9 @@ enum {
      * else as two launches.  These two flags take the choice away: */
     LORA_CACHE_FUSED_GEMV = 2,    /* always one launch (except under stream capture, where it is always two) */
     LORA_CACHE_SPLIT_GEMV = 4,    /* always two launches (and no hand-over buffer in the pool) */
+    LORA_CACHE_NO_OVERLAP = 16,   /* every kernel of an apply on the caller's stream: by default the GEMV launch of a batch that
+                                     also has tiles runs on a stream of the cache's own, forked off the caller's stream and
+                                     joined to it again inside the call, side by side with the tile kernels (different tokens) */
     LORA_CACHE_DIRECT_FILL = 8    /* fills read pinned host memory from the repack kernel itself instead of copying it
                                      to a staging buffer first: about twice the fill rate on an idle device, but applies
                                      that run at the same time are slowed down much more (measured 1.6x against 1.1x) */
@@ -289,18 +292,24 @@ int lora_plan_info(const lora_plan_t *p, lora_plan_info_t *out);
  * adapter; every unit names the slot and rank of its tokens' segments; for every GEMV token the
  * SHRINK units cover rank rows [0, rank) exactly once and the EXPAND units cover output columns
  * [0, h_out) exactly once; the LINEAR_ROWS units (bf16 caches: the row tiles of lora_linear_plan)
- * cover every token of the batch exactly once.
+ * cover every token of the batch exactly once; for every tile and run table the TILE_SHRINK units
+ * (the pieces the tile's input columns are worked on in) cover [0, h_in) exactly once, the pieces
+ * that are not whole tiles leave their partial sums in distinct scratch slots, and the TILE_SUM
+ * units (the slots the reduce kernel adds up for the tile) name exactly those slots.
  * Writes at most cap_units units and cap_toks tokens; *n_units and *n_toks return the full counts
  * (call with zero capacities to size the arrays). */
-enum { LORA_UNIT_TILE = 0, LORA_UNIT_GEMV_SHRINK = 1, LORA_UNIT_GEMV_EXPAND = 2, LORA_UNIT_LINEAR_ROWS = 3 };
+enum { LORA_UNIT_TILE = 0, LORA_UNIT_GEMV_SHRINK = 1, LORA_UNIT_GEMV_EXPAND = 2, LORA_UNIT_LINEAR_ROWS = 3, LORA_UNIT_TILE_SHRINK = 4, LORA_UNIT_TILE_SUM = 5 };
 typedef struct {
     int32_t kind;
     int32_t tok_off, n_tok; /* the unit's tokens: toks[tok_off .. tok_off + n_tok) */
     int32_t slot, rank;     /* slot found back from the storage row the kernels address; -1, 0: rows without adapter */
-    int32_t lo, hi;         /* GEMV_SHRINK: rank rows [lo, hi); GEMV_EXPAND: output columns [lo, hi); else 0, 0 */
-    int32_t where;          /* TILE: the XCD share (0..7) whose blocks run its shrink; GEMV_SHRINK: position in launch
-                               order; LINEAR_ROWS: 2 = a tile, 1 = rows of GEMV tokens, 0 = rows without adapter */
-    float alpha;            /* the cache entry's own factor as the kernels will apply it */
+    int32_t lo, hi;         /* GEMV_SHRINK: rank rows [lo, hi); GEMV_EXPAND: output columns [lo, hi); TILE_SHRINK: input
+                               columns [lo, hi); TILE_SUM: slot number lo of hi; else 0, 0 */
+    int32_t where;          /* GEMV_SHRINK: position in launch order; LINEAR_ROWS: 2 = a tile, 1 = rows of GEMV tokens,
+                               0 = rows without adapter; TILE_SHRINK, TILE_SUM: run table << 20 | run (run tables 0..3:
+                               launches for 1..4 projections; 4: the one of lora_apply_plan_static); TILE: 0 */
+    float alpha;            /* the cache entry's own factor as the kernels will apply it; TILE_SHRINK, TILE_SUM: the
+                               scratch slot of the partial sum (-1: the piece is the whole tile and leaves none) */
 } lora_plan_unit_t;
 int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_plan_unit_t *units, int32_t cap_units,
                    int32_t *n_units, int32_t *toks, int32_t cap_toks, int32_t *n_toks);

@@ -21,7 +21,7 @@ LIB_PATH = os.environ.get("LORA_CACHE_LIB") or os.path.join(_HERE, "liblora_cach
 LORA_OK, LORA_E_INVAL, LORA_E_STATE, LORA_E_NOMEM, LORA_E_HIP, LORA_E_NOTFOUND, LORA_E_FAULT = 0, -1, -2, -3, -4, -5, -6
 LORA_F32, LORA_BF16 = 0, 1
 LORA_SLOT_EMPTY, LORA_SLOT_FILLING, LORA_SLOT_READY = 0, 1, 2
-LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV, LORA_CACHE_DIRECT_FILL = 1, 2, 4, 8
+LORA_CACHE_HOST_ONLY, LORA_CACHE_FUSED_GEMV, LORA_CACHE_SPLIT_GEMV, LORA_CACHE_DIRECT_FILL, LORA_CACHE_NO_OVERLAP = 1, 2, 4, 8, 16
 LORA_MAX_RANK, LORA_TILE_TOKENS, LORA_MFMA_MIN_TOKENS, LORA_MFMA_MIN_TOKENS_MIXED = 128, 64, 16, 8
 
 
@@ -87,7 +87,7 @@ class lora_worklists_t(ctypes.Structure):
     ]
 
 
-LORA_UNIT_TILE, LORA_UNIT_GEMV_SHRINK, LORA_UNIT_GEMV_EXPAND, LORA_UNIT_LINEAR_ROWS = 0, 1, 2, 3
+LORA_UNIT_TILE, LORA_UNIT_GEMV_SHRINK, LORA_UNIT_GEMV_EXPAND, LORA_UNIT_LINEAR_ROWS, LORA_UNIT_TILE_SHRINK, LORA_UNIT_TILE_SUM = 0, 1, 2, 3, 4, 5
 
 
 class lora_plan_unit_t(ctypes.Structure):

@@ -27,7 +27,12 @@ constexpr int N_INTERNAL_PLANS = 4;
 constexpr int N_STAGES = 2;
 constexpr int N_APPLY_EVENTS = 64;
 constexpr size_t ALIGN = 256;
-constexpr int MAX_K_SPLITS = 8;
+// Tile shrink: at most this many runs per launch (two resident blocks per compute unit of a 256-unit part), and
+// the variants of the run tables a plan carries: one per number of projections served by one launch, and one with
+// few runs for the small fixed scratch.
+constexpr int SHRINK_MAX_RUNS = 512;
+constexpr int SHRINK_VARIANTS = lora::MAX_SHRINK_PROJS + 1;
+constexpr int SHRINK_VARIANT_SMALL = lora::MAX_SHRINK_PROJS;
 constexpr int N_LINEAR_FLAGS = 1024;  // split-off parts of lora_linear_plan's last round of tiles: fewer than CUs x 3
 constexpr double TILE_PATH_FIXED_US = 25.0;          // what the three launches of the tile path cost beside their work
 constexpr double TILE_PATH_L2_BYTES_PER_US = 10e6;  // rate at which repeated passes over a slab come out of L2
@@ -43,8 +48,8 @@ struct Scratch {
     size_t v_set_bytes;
     int n_sets;
     char *vpart;
-    size_t vpart_set_bytes;
-    int64_t vpart_rows;
+    int64_t vpart_rows;        // rows of the partial-sum scratch, shared by the projections of a group
+    bool small;                // the scratch holds the partial sums of the small run table only
     char *vtag;                // hand-over words of the GEMV phases, one set per projection of a group
     size_t vtag_set_bytes;
     uint32_t *epoch;           // host counter of the one-launch GEMV launches that have used vtag
@@ -61,7 +66,8 @@ struct Scratch {
 // at its own address (found once per device with hipGetSymbolAddress; the array's name itself is
 // no device address in host code).
 constexpr size_t STATIC_V_BYTES = sizeof(float) * (size_t)LORA_STATIC_MAX_TOKENS * LORA_MAX_RANK;
-constexpr int64_t STATIC_VPART_ROWS = 4 * (int64_t)LORA_STATIC_MAX_TOKENS;
+constexpr int STATIC_SHRINK_RUNS = 128;
+constexpr int64_t STATIC_VPART_ROWS = 2 * (int64_t)lora::SHRINK_SLOT_ROWS * STATIC_SHRINK_RUNS;  // = 4 x LORA_STATIC_MAX_TOKENS
 constexpr size_t STATIC_VPART_BYTES = sizeof(float) * (size_t)STATIC_VPART_ROWS * LORA_MAX_RANK;
 constexpr size_t STATIC_VTAG_BYTES = sizeof(uint64_t) * (size_t)LORA_STATIC_MAX_TOKENS * LORA_MAX_RANK;  // fp32 words; bf16 takes half
 constexpr size_t STATIC_SCRATCH_BYTES = STATIC_V_BYTES + STATIC_VPART_BYTES + STATIC_VTAG_BYTES;
@@ -128,7 +134,11 @@ struct lora_plan {
     int32_t T = 0;
     int32_t n_tok_list = 0, n_tiles = 0, n_gs = 0, n_ge = 0;
     int32_t n_tile_tok = 0;  // tokens of all tiles = leading entries of tok_list
-    int32_t xcd_tile[9] = {0};  // tile ranges of the 8 XCDs for the tile shrink
+    // the tile shrink's run tables (cuts, then the tiles' piece records), per variant
+    int32_t shrink_quanta = 1;
+    int32_t shrink_runs[SHRINK_VARIANTS] = {0};
+    bool shrink_pieces[SHRINK_VARIANTS] = {false};
+    size_t off_cuts[SHRINK_VARIANTS] = {0}, off_sums[SHRINK_VARIANTS] = {0};
     int32_t mfma_min_used = 0;  // the threshold the work lists were made with
     uint64_t build_seq = 0;     // changes whenever the plan's lists are rebuilt
     size_t off_tiles = 0, off_gs = 0, off_ge = 0, bytes = 0;
@@ -156,12 +166,13 @@ struct lora_cache {
     std::vector<size_t> proj_off;   // [n_proj] byte offset of the projection's slabs inside a layer
     std::vector<size_t> row_bytes;  // [n_proj] (h_in + h_out) * element size
     int64_t total_rows = 0;
-    size_t off_fault = 0, off_vpart = 0, off_vtag = 0, v_set_bytes = 0, vpart_set_bytes = 0, vtag_set_bytes = 0;
+    size_t off_fault = 0, off_vpart = 0, off_vtag = 0, v_set_bytes = 0, vtag_set_bytes = 0;
     uint32_t tag_epoch = 0;  // one-launch GEMV launches so far; the number the words of the latest one carry
     unsigned long long cap_id = 0;
     uint64_t cap_plan = 0;  // build number of the plan
     int cap_sets = 0;
-    int64_t vpart_rows = 0;  // rows of the k-split partial scratch
+    int64_t vpart_rows = 0;  // rows of the tile shrink's partial-sum scratch
+    size_t vpart_bytes = 0;
     int fused_gemv = 0;  // 0 never, 1 by size, 2 always
     size_t off_v = 0, off_plans = 0, off_stage = 0, plan_cap = 0, stage_cap = 0, total = 0;
 
@@ -173,6 +184,11 @@ struct lora_cache {
     bool direct_fill = false;
     uint64_t stage_next = 0;
 
+    // Within a group the GEMV launch (decode tokens) and the tile kernels (prompts) touch different tokens and
+    // different scratch: they run side by side, the GEMV launch on a stream of the cache's own between a fork
+    // and a join event (default priority, like every stream here)
+    hipStream_t side_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int device = 0;  // the device that was current at lora_cache_create
     int n_cu = 256;  // its compute units
     bool fencing = true;
@@ -272,7 +288,8 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.plan_cap = align_up(sizeof(int32_t) * (size_t)c.max_tokens) + align_up(sizeof(lora_item_t) * max_items) +
                  align_up(sizeof(int32_t) * max_batches) + 4 * ALIGN +
                  align_up(sizeof(int32_t) * (size_t)c.max_tokens) +
-                 align_up(sizeof(lora_item_t) * (max_tiles + (size_t)c.max_tokens / LORA_TILE_TOKENS + 2));
+                 align_up(sizeof(lora_item_t) * (max_tiles + (size_t)c.max_tokens / LORA_TILE_TOKENS + 2)) +
+                 SHRINK_VARIANTS * (align_up(sizeof(lora::ShrinkCut) * (SHRINK_MAX_RUNS + 1)) + align_up(sizeof(lora::ShrinkSum) * max_tiles));
     c.stage_cap = align_up(max_part) + ALIGN;
 
     size_t cur = align_up(c.layer_stride * (size_t)c.n_layers);
@@ -281,11 +298,19 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.off_v = cur;
     c.v_set_bytes = align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
     cur += c.v_set_bytes * N_VSETS;
-    // k-split partials: splits are only used while tiles * splits stays near 512 blocks of 64 tokens
-    c.vpart_rows = c.dtype == LORA_BF16 ? std::min<int64_t>((int64_t)MAX_K_SPLITS * c.max_tokens, 640 * 64 + c.max_tokens) : 0;
+    // partial sums of the tile shrink: two slots per run; a batch of few tiles has few runs (a run is at least an
+    // eighth of a tile)
+    {
+        const int64_t runs = std::min<int64_t>(SHRINK_MAX_RUNS, 8 * std::max<int64_t>(N_VSETS, ((int64_t)c.max_tokens + LORA_TILE_TOKENS - 1) / LORA_TILE_TOKENS));
+        c.vpart_rows = c.dtype == LORA_BF16 ? 2 * lora::SHRINK_SLOT_ROWS * runs : 0;
+    }
     c.off_vpart = cur;
-    c.vpart_set_bytes = align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
-    cur += c.vpart_set_bytes * N_VSETS;
+    c.vpart_bytes = align_up(sizeof(float) * (size_t)c.vpart_rows * c.v_stride);
+    // (the fused linear kernel parks the partial sums of its split tiles in the same region: at most 48 MB,
+    // less for caches of small batches)
+    if (c.dtype == LORA_BF16)
+        c.vpart_bytes = std::max(c.vpart_bytes, std::min<size_t>((size_t)48 << 20, align_up(sizeof(float) * (size_t)c.v_stride * 8 * (size_t)c.max_tokens)));
+    cur += c.vpart_bytes;
     // the GEMV phases hand their intermediate over as 64-bit words, one row per token and projection of a group
     c.off_vtag = cur;
     c.vtag_set_bytes = align_up(lora::gemv_handover_bytes(c.dtype, c.max_tokens));
@@ -410,6 +435,105 @@ bool is_capturing(hipStream_t st)
     return cs != hipStreamCaptureStatusNone;
 }
 
+// The tile shrink's run table for `max_runs` runs (header of ShrinkCut in lora_internal.h): cuts[0 .. n_runs] and one
+// piece record per tile.  A tile's cost per part of its k range: its x rows (absent rows are still loaded) plus its
+// stored At rows (measured: a rank-128 tile takes 1.8 times as long as a rank-16 one).
+struct ShrinkRuns {
+    std::vector<lora::ShrinkCut> cuts;
+    std::vector<lora::ShrinkSum> sums;
+    int n_runs = 0;
+    bool any_pieces = false;
+};
+bool shrink_pieces_of(const lora::DevItem *tiles, int n_tiles, int quanta, ShrinkRuns &out)
+{
+    out.sums.assign((size_t)n_tiles, lora::ShrinkSum{0, 0});
+    out.any_pieces = false;
+    for (int r = 0; r < out.n_runs; ++r) {
+        const lora::ShrinkCut from = out.cuts[r], to = out.cuts[r + 1];
+        const int last_tile = std::min(to.part > 0 ? to.tile : to.tile - 1, n_tiles - 1);
+        for (int t = from.tile; t <= last_tile; ++t) {
+            const int lo = t == from.tile ? from.part : 0, hi = t == to.tile ? to.part : quanta;
+            if (lo >= hi) continue;
+            lora::ShrinkSum &sm = out.sums[t];
+            const int32_t slot = lora::shrink_slot(r, from.tile, t);
+            if (sm.n_pieces == 0) sm.first_slot = (lo == 0 && hi == quanta) ? 0 : slot;
+            else if (slot != 2 * (sm.first_slot / 2 + sm.n_pieces)) return false;  // (cannot happen: later pieces start their runs)
+            ++sm.n_pieces;
+            if (sm.n_pieces > 1) out.any_pieces = true;
+        }
+    }
+    for (int t = 0; t < n_tiles; ++t)
+        if (out.sums[t].n_pieces < 1) return false;
+    (void)tiles;
+    return true;
+}
+// Runs of about equal cost, at most max_runs of them (a multiple of 8).  A piece costs its parts times its tile's
+// weight, plus a fixed amount.  Measured with every block of a launch resident from the start (two per compute unit):
+// a block spends about 7 us beside its k loop (the item, the first loads, the write of the result); a stage of 128 k
+// takes it 1.75 us at rank 16, 2.1 us at rank 32, 2.3 us at rank 64 and 3.0 to 3.3 us at rank 128 when the launch is
+// long (x arrives at the rate the memory gives, the higher ranks add their At loads and products), and 1.0 against 2.4 us
+// at ranks 16 and 128 when it is short.  For a cost limit the sequence is walked once, every run taking pieces until
+// the limit is reached; the smallest limit that needs no more than max_runs runs is found by bisection.
+void build_shrink_runs(const lora::DevItem *tiles, int n_tiles, int quanta, int max_runs, ShrinkRuns &out)
+{
+    constexpr int64_t MINP = lora::SHRINK_MIN_PARTS, PIECE = 6 * (44 + LORA_TILE_TOKENS + 16);  // six stages at rank 16
+    std::vector<int64_t> weight((size_t)n_tiles);
+    int64_t total = 0, w_max = 1;
+    for (int t = 0; t < n_tiles; ++t) {
+        weight[t] = 44 + (int64_t)tiles[t].n_tok + lora::rank_storage(tiles[t].rank);  // rank 128 : rank 16 = 1.9
+        total += weight[t] * quanta + PIECE;
+        w_max = std::max(w_max, weight[t]);
+    }
+    // one walk: the number of runs; their starts go to `cuts` when given
+    auto walk = [&](int64_t limit, std::vector<lora::ShrinkCut> *cuts) -> int64_t {
+        int t = 0, q = 0;
+        int64_t runs = 0;
+        while (t < n_tiles) {
+            if (cuts) cuts->push_back(lora::ShrinkCut{t, q});
+            ++runs;
+            int64_t cost = 0;
+            bool first = true;
+            while (t < n_tiles) {
+                const int64_t w = weight[t], rem = quanta - q;
+                if (cost + w * rem + PIECE <= limit) {  // the rest of the tile
+                    cost += w * rem + PIECE;
+                    ++t, q = 0, first = false;
+                    continue;
+                }
+                int64_t parts = (limit - cost - PIECE) / w;  // what still fits (rounded towards zero: never negative parts >= MINP)
+                if (parts < MINP) {
+                    if (!first) break;  // the run ends on the tile boundary
+                    parts = MINP;       // a run takes something
+                }
+                if (rem - parts < MINP) ++t, q = 0;  // no slivers: the rest of the tile
+                else q += (int)parts;
+                break;
+            }
+        }
+        return runs;
+    };
+    int64_t lo = w_max * std::min<int64_t>(MINP, quanta) + PIECE, hi = std::max(total, lo);  // hi: one run takes everything
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (walk(mid, nullptr) <= max_runs) hi = mid;
+        else lo = mid + 1;
+    }
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        out.cuts.clear();
+        // second attempt (never needed as far as the walk goes): whole tiles only, as many per run as it takes
+        int64_t used;
+        if (attempt == 0) used = walk(hi, &out.cuts);
+        else {
+            const int per_run = (n_tiles + max_runs - 1) / max_runs;
+            for (int t = 0; t < n_tiles; t += per_run) out.cuts.push_back(lora::ShrinkCut{t, 0});
+            used = (int64_t)out.cuts.size();
+        }
+        out.n_runs = (int)((used + 7) / 8 * 8);
+        out.cuts.resize((size_t)out.n_runs + 1, lora::ShrinkCut{n_tiles, 0});
+        if (used <= max_runs && shrink_pieces_of(tiles, n_tiles, quanta, out)) return;
+    }
+}
+
 // Validates a batch against the slot table and writes its work lists into plan `p`
 // (pinned copy + upload on `st`).
 int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offsets, const int32_t *seg_slot,
@@ -489,20 +613,6 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     };
     p.n_tile_tok = 0;
     for (int i = 0; i < w.n_tiles; ++i) p.n_tile_tok += w.tiles[i].n_tok;
-    // the tile shrink's XCD shares: 8 contiguous runs of tiles of about equal cost, where a tile
-    // costs its x rows plus its At rows (measured: rank 128 takes 1.76x as long as rank 16)
-    {
-        std::vector<int64_t> upto(w.n_tiles + 1, 0);
-        for (int i = 0; i < w.n_tiles; ++i) upto[i + 1] = upto[i] + 2 * w.tiles[i].n_tok + w.tiles[i].rank;
-        p.xcd_tile[0] = 0;
-        for (int j = 1; j < 8; ++j) {
-            const int64_t want = upto[w.n_tiles] * j / 8;
-            int t = p.xcd_tile[j - 1];
-            while (t < w.n_tiles && upto[t + 1] - want <= want - upto[t]) ++t;  // the cut nearest to the share
-            p.xcd_tile[j] = t;
-        }
-        p.xcd_tile[8] = w.n_tiles;
-    }
     // GEMV work items.  A group is worked on in token batches (runs of up to GEMV_BATCH entries of its
     // part of tok_list), every batch with items of its own so that batches run side by side: per batch
     // one shrink item per GEMV_SHRINK_ROWS stored rank rows, and one expand item per run of
@@ -533,6 +643,21 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
             }
     }
     stamp(w.tiles, w.n_tiles);
+    // the tile shrink's run tables
+    ShrinkRuns shrink_runs[SHRINK_VARIANTS];
+    {
+        int32_t quanta = INT32_MAX;
+        for (const auto &pr : c.proj) quanta = std::min(quanta, (pr.h_in + lora::SHRINK_STAGE_K - 1) / lora::SHRINK_STAGE_K);
+        p.shrink_quanta = std::max(1, std::min(quanta, 1 << 14));
+        const int64_t slots = std::min<int64_t>(SHRINK_MAX_RUNS, 2 * (int64_t)c.n_cu);
+        const lora::DevItem *dev_tiles = reinterpret_cast<const lora::DevItem *>(w.tiles);  // stamped above
+        for (int v = 0; v < SHRINK_VARIANTS && w.n_tiles > 0 && c.vpart_rows > 0; ++v) {
+            const int n = v == SHRINK_VARIANT_SMALL ? 1 : v + 1;
+            int64_t max_runs = slots / 8 / n * 8;
+            max_runs = std::min(max_runs, (v == SHRINK_VARIANT_SMALL ? STATIC_VPART_ROWS : c.vpart_rows) / (2 * lora::SHRINK_SLOT_ROWS) / n / 8 * 8);
+            build_shrink_runs(dev_tiles, w.n_tiles, p.shrink_quanta, (int)std::max<int64_t>(8, max_runs), shrink_runs[v]);
+        }
+    }
 
     p.T = T;
     p.n_tok_list = w.n_tok_list;
@@ -575,7 +700,15 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     p.n_lin_tiles = (int32_t)lin_tiles.size();
     p.off_lin_tok = p.off_ge + align_up(sizeof(lora::GemvItem) * ge.size());
     p.off_lin_tiles = p.off_lin_tok + align_up(sizeof(int32_t) * lin_tok.size());
-    const size_t bytes = p.off_lin_tiles + align_up(sizeof(lora::DevItem) * lin_tiles.size());
+    size_t bytes = p.off_lin_tiles + align_up(sizeof(lora::DevItem) * lin_tiles.size());
+    for (int v = 0; v < SHRINK_VARIANTS; ++v) {
+        p.shrink_runs[v] = shrink_runs[v].n_runs;
+        p.shrink_pieces[v] = shrink_runs[v].any_pieces;
+        p.off_cuts[v] = bytes;
+        bytes += align_up(sizeof(lora::ShrinkCut) * shrink_runs[v].cuts.size());
+        p.off_sums[v] = bytes;
+        bytes += align_up(sizeof(lora::ShrinkSum) * shrink_runs[v].sums.size());
+    }
     if (bytes > c.plan_cap) {
         lora_worklists_free(&w);
         return LORA_E_NOMEM;
@@ -603,6 +736,10 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
     if (!ge.empty()) std::memcpy(p.pinned + p.off_ge, ge.data(), sizeof(lora::GemvItem) * ge.size());
     if (!lin_tok.empty()) std::memcpy(p.pinned + p.off_lin_tok, lin_tok.data(), sizeof(int32_t) * lin_tok.size());
     if (!lin_tiles.empty()) std::memcpy(p.pinned + p.off_lin_tiles, lin_tiles.data(), sizeof(lora::DevItem) * lin_tiles.size());
+    for (int v = 0; v < SHRINK_VARIANTS; ++v) {
+        if (!shrink_runs[v].cuts.empty()) std::memcpy(p.pinned + p.off_cuts[v], shrink_runs[v].cuts.data(), sizeof(lora::ShrinkCut) * shrink_runs[v].cuts.size());
+        if (!shrink_runs[v].sums.empty()) std::memcpy(p.pinned + p.off_sums[v], shrink_runs[v].sums.data(), sizeof(lora::ShrinkSum) * shrink_runs[v].sums.size());
+    }
     p.bytes = bytes;
     p.build_seq = ++c.plan_builds;
     if (!c.host_only && bytes) {
@@ -653,20 +790,6 @@ void timer_pair(void *ctx, int kind, hipEvent_t *start, hipEvent_t *stop)
     c.timed.push_back(t);
     *start = t.start;
     *stop = t.stop;
-}
-
-int choose_k_splits(int64_t vpart_rows, int n_tiles, int n_tile_tok, int h_in)
-{
-    // One round of blocks (2 per CU) when there are few tiles.  From half a round of whole-row blocks
-    // up, about two rounds of shorter ones: with 330 tiles, three k ranges took 10 % less than one
-    // (short blocks hide each other's start and end; the partials and the reduce launch cost a third
-    // of that back), four or more gained nothing further.  k ranges of at least 512 elements; and the
-    // partials of all splits must fit their scratch.
-    const int n = std::max(1, n_tiles);
-    const int fill = n <= 256 ? 512 / n : (1100 + n / 2) / n;
-    int want = std::max(1, std::min({fill, h_in / 512, MAX_K_SPLITS}));
-    while (want > 1 && (int64_t)lora::mfma_shrink_splits(h_in, want) * n_tile_tok > vpart_rows) --want;
-    return lora::mfma_shrink_splits(h_in, want);
 }
 
 }  // namespace
@@ -785,6 +908,11 @@ int lora_cache_create(const lora_cache_config_t *cfg, void *dev_pool, size_t dev
         fail(hipEventCreateWithFlags(&c->stage[i].ev, hipEventDisableTiming));
     }
     for (int i = 0; i < N_APPLY_EVENTS && rc == LORA_OK; ++i) fail(hipEventCreateWithFlags(&c->apply_ev[i], hipEventDisableTiming));
+    if (rc == LORA_OK && !(c->flags & LORA_CACHE_NO_OVERLAP)) {
+        fail(hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
+        fail(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+        fail(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+    }
     if (rc != LORA_OK) {
         lora_cache_destroy(c);
         return rc;
@@ -810,6 +938,9 @@ int lora_cache_destroy(lora_cache_t *c)
             if (e) (void)hipEventDestroy(e);
         for (auto &kv : c->stream_fence)
             if (kv.second) (void)hipEventDestroy(kv.second);
+        if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+        if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+        if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
         if (c->fault_host) (void)hipHostFree(c->fault_host);
         for (auto &s : c->slots)
             if (s.fill_ev) (void)hipEventDestroy(s.fill_ev);
@@ -1332,12 +1463,35 @@ int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_pla
     auto tile_tokens = [&](const lora::DevItem &it, const int32_t *list) {
         for (int32_t i = 0; i < it.n_tok; ++i) put_tok(lora::tile_token_of(list, it, i));
     };
+    std::vector<int32_t> tile_off((size_t)p->n_tiles, 0);
     for (int32_t i = 0; i < p->n_tiles; ++i) {
-        int32_t xcd = 0;
-        while (xcd < 7 && i >= p->xcd_tile[xcd + 1]) ++xcd;
-        const int32_t off = nt;
+        tile_off[i] = nt;
         tile_tokens(tiles[i], tok_list);
-        put_unit(LORA_UNIT_TILE, off, tiles[i].n_tok, tiles[i].row, tiles[i].rank, 0, 0, xcd, tiles[i].alpha);
+        put_unit(LORA_UNIT_TILE, tile_off[i], tiles[i].n_tok, tiles[i].row, tiles[i].rank, 0, 0, 0, tiles[i].alpha);
+    }
+    // the tile shrink's pieces for this projection's h_in, per run table, walked as the kernel walks them; and the
+    // scratch slots the reduce adds up per tile
+    for (int v = 0; v < SHRINK_VARIANTS && p->n_tiles > 0; ++v) {
+        const lora::ShrinkCut *cuts = reinterpret_cast<const lora::ShrinkCut *>(buf + p->off_cuts[v]);
+        const lora::ShrinkSum *sums = reinterpret_cast<const lora::ShrinkSum *>(buf + p->off_sums[v]);
+        const int32_t quanta = p->shrink_quanta, h_in = c->proj[proj].h_in, SK = lora::SHRINK_STAGE_K;
+        for (int32_t r = 0; r < p->shrink_runs[v]; ++r) {
+            const lora::ShrinkCut from = cuts[r], to = cuts[r + 1];
+            const int32_t last_tile = std::min(to.part > 0 ? to.tile : to.tile - 1, p->n_tiles - 1);
+            for (int32_t t = from.tile; t <= last_tile; ++t) {
+                const int32_t lo = t == from.tile ? from.part : 0, hi = t == to.tile ? to.part : quanta;
+                if (lo >= hi) continue;
+                const int32_t k_begin = lora::shrink_part_stage(lo, quanta, h_in, SK) * SK;
+                const int32_t k_end = std::min(h_in, lora::shrink_part_stage(hi, quanta, h_in, SK) * SK);
+                const bool whole = lo == 0 && hi == quanta;
+                put_unit(LORA_UNIT_TILE_SHRINK, tile_off[t], tiles[t].n_tok, tiles[t].row, tiles[t].rank, k_begin, k_end,
+                         (v << 20) | r, whole ? -1.f : (float)lora::shrink_slot(r, from.tile, t));
+            }
+        }
+        for (int32_t t = 0; t < p->n_tiles; ++t)
+            for (int32_t j = 0; j < sums[t].n_pieces && sums[t].n_pieces > 1; ++j)
+                put_unit(LORA_UNIT_TILE_SUM, tile_off[t], tiles[t].n_tok, tiles[t].row, tiles[t].rank, j, sums[t].n_pieces, v << 20,
+                         (float)(j == 0 ? sums[t].first_slot : 2 * (sums[t].first_slot / 2 + j)));
     }
     auto gemv_tokens = [&](const lora::GemvItem &it) -> int32_t {
         int32_t n = 0;
@@ -1408,8 +1562,26 @@ constexpr int FUSED_GEMV_MAX_ITEMS = 8192;
 // then their expands.
 static Scratch pool_scratch(lora_cache_t *c)
 {
-    return Scratch{c->pool + c->off_v, c->v_set_bytes, N_VSETS, c->pool + c->off_vpart, c->vpart_set_bytes, c->vpart_rows,
+    return Scratch{c->pool + c->off_v, c->v_set_bytes, N_VSETS, c->pool + c->off_vpart, c->vpart_rows, false,
                    c->pool + c->off_vtag, c->vtag_set_bytes, &c->tag_epoch, &c->cap_id, &c->cap_plan, &c->cap_sets};
+}
+
+// The run table of a tile-shrink launch for n projections, and where their partial sums go in `vpart`.
+static int shrink_setup(const lora_cache_t *c, const lora_plan_t *p, int n, char *vpart, int64_t vpart_rows, bool small, lora::ShrinkProjs &ps)
+{
+    const int v = small ? SHRINK_VARIANT_SMALL : n - 1;
+    if (n < 1 || n > lora::MAX_SHRINK_PROJS || (small && n != 1)) return LORA_E_INVAL;
+    ps.n = n;
+    ps.n_runs = p->shrink_runs[v];
+    ps.quanta = p->shrink_quanta;
+    ps.any_pieces = p->shrink_pieces[v] ? 1 : 0;
+    ps.cuts = reinterpret_cast<const lora::ShrinkCut *>(p->dev + p->off_cuts[v]);
+    ps.sums = reinterpret_cast<const lora::ShrinkSum *>(p->dev + p->off_sums[v]);
+    const int64_t rows_per_proj = 2 * (int64_t)lora::SHRINK_SLOT_ROWS * ps.n_runs;
+    if (rows_per_proj * n > vpart_rows) return LORA_E_NOMEM;
+    for (int i = 0; i < lora::MAX_SHRINK_PROJS; ++i)
+        ps.part[i] = i < n ? reinterpret_cast<float *>(vpart) + (size_t)i * rows_per_proj * c->v_stride : nullptr;
+    return LORA_OK;
 }
 
 // The GEMV part of a group of n projections that read the same x: one launch with the in-kernel
@@ -1506,8 +1678,7 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
 
     lora::ApplyArgs a[N_VSETS];
     lora::ShrinkProjs ps;
-    ps.n = n;
-    for (int j = 0; j < 9; ++j) ps.xcd_tile[j] = p->xcd_tile[j];
+    if (const int rc_s = shrink_setup(c, p, n, sc.vpart, sc.vpart_rows, sc.small, ps)) return rc_s;
     for (int i = 0; i < n; ++i) {
         const int32_t proj = descs[i].proj;
         a[i].proj_base = c->pool + (size_t)descs[i].layer * c->layer_stride + c->proj_off[proj];
@@ -1523,20 +1694,42 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
         ps.proj_base[i] = a[i].proj_base;
         ps.row_bytes[i] = a[i].row_bytes;
         ps.v[i] = a[i].v;
-        ps.part[i] = reinterpret_cast<float *>(sc.vpart + (size_t)i * sc.vpart_set_bytes);
     }
     for (int i = n; i < N_VSETS; ++i) {
         ps.proj_base[i] = nullptr;
         ps.row_bytes[i] = 0;
-        ps.v[i] = ps.part[i] = nullptr;
+        ps.v[i] = nullptr;
+    }
+    // The GEMV launch and the tile kernels of a group work on different tokens (rows of base_out) with different
+    // scratch: when a batch has both, the GEMV launch goes to the cache's side stream, forked off here and
+    // joined again behind the tile expands (also under stream capture, where fork and join become edges of the graph).
+    // Not while kernels are being timed: a kernel's duration is then its own, not that of two kernels sharing the memory.
+    const bool fork = p->n_tiles > 0 && p->n_gs > 0 && c->side_stream != nullptr && c->side_stream != st && tm == nullptr;
+    hipStream_t gemv_st = st;
+    if (fork) {
+        HIP_TRY(hipEventRecord(c->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
+        gemv_st = c->side_stream;
     }
     // everything that reads x
     if (p->n_tiles > 0) {
-        // the scratch of the partials is sized for about 640 blocks of 64 tokens per projection
-        const int splits = choose_k_splits(sc.vpart_rows, p->n_tiles * n, p->n_tile_tok, a[0].h_in);
-        HIP_TRY(lora::launch_mfma_shrink(a[0], ps, tiles, p->n_tiles, p->n_tile_tok, splits, st, tm));
+        HIP_TRY(lora::launch_mfma_shrink(a[0], ps, tiles, p->n_tiles, st, tm));
     }
-    if (const int rc = enqueue_gemv(c, p, a, nullptr, n, true, st, sc, tm)) return rc;
+    // joined behind the tile expands, whatever happens in between: a captured fork must not stay open
+    struct Join {
+        lora_cache_t *c;
+        hipStream_t st;
+        bool armed;
+        hipError_t now()
+        {
+            if (!armed) return hipSuccess;
+            armed = false;
+            const hipError_t e = hipEventRecord(c->ev_join, c->side_stream);
+            return e == hipSuccess ? hipStreamWaitEvent(st, c->ev_join, 0) : e;
+        }
+        ~Join() { (void)now(); }
+    } join{c, st, fork};
+    if (const int rc_g = enqueue_gemv(c, p, a, nullptr, n, true, gemv_st, sc, tm)) return rc_g;
     // the updates of base_out
     for (int i = 0; i < n; ++i) {
         HIP_TRY(lora::launch_mfma_expand(a[i], tiles, p->n_tiles, st, tm));
@@ -1547,6 +1740,7 @@ static int enqueue_group(lora_cache_t *c, lora_plan_t *p, const lora_apply_desc_
             ++c->slots[sl].use_count;
         }
     }
+    HIP_TRY(join.now());
     return LORA_OK;
 }
 
@@ -1594,7 +1788,7 @@ int lora_apply_plan_static(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32
     if (rc != LORA_OK) return rc;
     StaticScratch &ss = g_static[c->device];  // set up by lora_cache_create on this device
     if (!ss.ptr) return LORA_E_STATE;
-    const Scratch sc{ss.ptr, STATIC_V_BYTES, 1, ss.ptr + STATIC_V_BYTES, STATIC_VPART_BYTES, STATIC_VPART_ROWS,
+    const Scratch sc{ss.ptr, STATIC_V_BYTES, 1, ss.ptr + STATIC_V_BYTES, STATIC_VPART_ROWS, true,
                      ss.ptr + STATIC_V_BYTES + STATIC_VPART_BYTES, STATIC_VTAG_BYTES, &ss.epoch, &ss.cap_id, &ss.cap_plan, &ss.cap_sets};
     const lora_apply_desc_t d{layer, proj, x, base_out};
     const bool timing = c->timing;
@@ -1650,15 +1844,13 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
     // shrink of the tiles and of the GEMV groups (x is read, v written)
     if (p->n_tiles > 0) {
         lora::ShrinkProjs ps;
-        ps.n = 1;
-        for (int j = 0; j < 9; ++j) ps.xcd_tile[j] = p->xcd_tile[j];
+        if (const int rc_s = shrink_setup(c, p, 1, c->pool + c->off_vpart, c->vpart_rows, false, ps)) return rc_s;
         for (int i = 0; i < lora::MAX_SHRINK_PROJS; ++i) {
             ps.proj_base[i] = i ? nullptr : a.proj_base;
             ps.row_bytes[i] = i ? 0 : a.row_bytes;
             ps.v[i] = i ? nullptr : a.v;
-            ps.part[i] = i ? nullptr : reinterpret_cast<float *>(c->pool + c->off_vpart);
         }
-        HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, p->n_tile_tok, choose_k_splits(c->vpart_rows, p->n_tiles, p->n_tile_tok, a.h_in), st, tm));
+        HIP_TRY(lora::launch_mfma_shrink(a, ps, tiles, p->n_tiles, st, tm));
     }
     // the adapter term of the GEMV tokens: as fp32 into the caller's workspace (row = token), or, without
     // one, into their zeroed output rows (rounded to the output type on the way)
@@ -1673,7 +1865,7 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
     lin.tok_list = reinterpret_cast<const int32_t *>(p->dev + p->off_lin_tok);
     // (the partial sums of split tiles go where the tile shrink's k-split partials went: that kernel is done)
     HIP_TRY(lora::launch_linear_tiles(lin, Wt, reinterpret_cast<const lora::DevItem *>(p->dev + p->off_lin_tiles), p->n_lin_tiles,
-                                      c->pool + c->off_vpart, c->vpart_set_bytes * N_VSETS, reinterpret_cast<uint32_t *>(c->pool + c->off_fault),
+                                      c->pool + c->off_vpart, c->vpart_bytes, reinterpret_cast<uint32_t *>(c->pool + c->off_fault),
                                       N_LINEAR_FLAGS, c->fault_dev, c->n_cu, st, tm));
     const int64_t seq = ++c->apply_seq;
     ++c->stats.applies;

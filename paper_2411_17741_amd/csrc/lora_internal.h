@@ -184,27 +184,51 @@ hipError_t launch_gemv(int dtype, const GemvMap &m, const GemvArgs &a, hipStream
 size_t gemv_handover_bytes(int dtype, int64_t max_tokens);
 // zeroes the hand-over words of tokens toks[0 .. n) (device list) in `vw`
 hipError_t launch_gemv_clear(int dtype, unsigned long long *vw, const int32_t *toks, int n, hipStream_t st);
+// Tile shrink.  Its work is the sequence of all tiles' k ranges, every tile's range divided into `quanta`
+// equal parts (a part is a whole number of the kernel's k stages for every projection of the cache).  A plan
+// cuts that sequence into n_runs runs of about equal cost (a tile's cost per part: its x rows plus its At
+// rows); run r is worked on by one block per projection of the launch, all blocks of a launch being
+// resident at once (two per compute unit), so that the launch ends when a run ends.  A run covers a tail of
+// its first tile, whole tiles, and a head of its last tile; a piece that is not a whole tile leaves a partial
+// sum in the scratch rows of (run, first or last piece) and mfma_reduce_kernel adds a tile's pieces up.
+// Cuts lie on part boundaries at least SHRINK_MIN_PARTS parts from a tile's ends and from each other, or on a
+// tile boundary; the last runs of a table may be empty (the table is padded to a multiple of 8 runs).
+struct ShrinkCut {  // where run r starts (it ends where run r + 1 starts; entry n_runs = {n_tiles, 0})
+    int32_t tile;
+    int32_t part;   // 0 <= part < quanta
+};
+struct ShrinkSum {  // per tile, for the reduce: its pieces' partial sums
+    int32_t first_slot;  // scratch slot of the first piece; piece j > 0 lies in slot 2 * (first_slot / 2 + j)
+    int32_t n_pieces;    // 1: the tile was worked on whole, the shrink wrote the result itself
+};
+constexpr int SHRINK_MIN_PARTS = 2;
+constexpr int SHRINK_SLOT_ROWS = LORA_TILE_TOKENS;  // rows (of v_stride floats) of one partial-sum slot
+// scratch slot of the piece of tile `tile` in run `run` that starts in tile `first_tile`
+inline __host__ __device__ int32_t shrink_slot(int32_t run, int32_t first_tile, int32_t tile) { return 2 * run + (tile != first_tile); }
+// k stages (of stage_k elements) before part boundary `part` of a row of h_in elements
+inline __host__ __device__ int32_t shrink_part_stage(int32_t part, int32_t quanta, int32_t h_in, int32_t stage_k)
+{
+    const int32_t n_st = (h_in + stage_k - 1) / stage_k;
+    return (int32_t)(((int64_t)part * n_st + quanta / 2) / quanta);
+}
+constexpr int SHRINK_STAGE_K = 128;
 // The projections one tile-shrink launch serves (they read the same x): slab base and row pitch,
-// destination of the intermediate, scratch for k-split partials (splits * n_tile_tok rows of
-// v_stride floats each, unused when the launch does not split).
+// destination of the intermediate, scratch for the partial sums (2 * n_runs slots of SHRINK_SLOT_ROWS rows).
 constexpr int MAX_SHRINK_PROJS = 4;
 struct ShrinkProjs {
     int n;
-    // tiles [xcd_tile[j], xcd_tile[j+1]) are worked on by the blocks of XCD j: contiguous runs (tiles
-    // of a prompt share At, which then stays in that XCD's L2) of about equal cost (a tile of rank
-    // 128 takes twice as long as one of rank 16; with equal counts the XCD that got a long
-    // high-rank prompt finished last by a factor of two)
-    int xcd_tile[9];
+    int n_runs, quanta;       // n_runs: a multiple of 8 (run r is worked on by XCD r / (n_runs / 8))
+    int any_pieces;           // some tile is worked on in pieces: the reduce launch is needed
+    const ShrinkCut *cuts;    // device, n_runs + 1
+    const ShrinkSum *sums;    // device, n_tiles
     const char *proj_base[MAX_SHRINK_PROJS];
     int64_t row_bytes[MAX_SHRINK_PROJS];
     float *v[MAX_SHRINK_PROJS];
     float *part[MAX_SHRINK_PROJS];
 };
-// n_tile_tok = tokens of all tiles (the leading part of tok_list); proj_base, row_bytes and v of
-// `a` are ignored (taken from ps)
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, int n_tile_tok,
-                              int k_splits, hipStream_t st, const KernelTimer *tm);
-int mfma_shrink_splits(int h_in, int want);  // k ranges the shrink launch will really use
+// proj_base, row_bytes and v of `a` are ignored (taken from ps)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, hipStream_t st,
+                              const KernelTimer *tm);
 hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_tiles, hipStream_t st, const KernelTimer *tm);
 // y = x . Wt^T + adapter update for row tiles (tiles of the plan, then plain runs of the other tokens:
 // rank 0); a.tok_list must be the list the row tiles index; a.v holds the shrink results

@@ -37,15 +37,18 @@ constexpr int VS_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per token row of the st
 //  - From 4 rank blocks (of 16) up, wavefront w owns rank blocks w and w+4 for the whole k range
 //    and writes its part of V itself.  Below that, the wavefronts split the four MFMA k steps of
 //    a stage instead, each covering all rank blocks, and their partials are summed through LDS.
-//  - When a tile's k is split over several blocks (few tiles, many CUs), each block writes its
-//    partial to a scratch row set of its split and mfma_reduce_kernel adds the splits up.
-// Blocks are numbered so that the splits of a tile and neighbouring tiles (same segment, same
-// At) fall on one XCD (blocks b, b + 8, ... run on XCD b % 8), each XCD taking a contiguous run of
-// tiles of about equal cost.
+//  - The launch's work -- every tile's k range -- is cut into runs of about equal cost, one block per run
+//    (and projection), all blocks resident at once: a block walks the pieces of its run, a piece being a k
+//    range of one tile.  A piece that is not a whole tile leaves a partial sum in the scratch slot of its run
+//    and mfma_reduce_kernel adds a tile's pieces up.  (With one block per tile and a fixed number of k ranges
+//    the launch ended when the XCD with the most or the costliest tiles did: a timeline of the prefill
+//    configuration showed half of the blocks done at 15 us and the last at 26 us.)
+// Blocks are numbered so that consecutive runs (same tiles, same segment, same At) fall on one XCD (blocks
+// b, b + 8, ... run on XCD b % 8).
 // One launch can serve several projections that read the same x (q, k, v; gate, up).
 // ---------------------------------------------------------------------------------------
 namespace {
-constexpr int SK = 128;                 // k elements per stage
+constexpr int SK = SHRINK_STAGE_K;      // k elements per stage
 constexpr int XROW = SK * 2 + 16;       // bytes per token row of a stage in LDS
 constexpr int NSTAGE = 3;
 }  // namespace
@@ -199,9 +202,9 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
         for (int r = 0; r < 4; ++r) {
             const int ti = 16 * mb + 4 * g + r, jr = 16 * nbq[q] + m;
             if (ti < it.n_tok && jr < it.rank) {
-                // whole k range in this block: the result itself; else this split's partial, one row
-                // per position in tok_list (mfma_reduce_kernel adds the splits up)
-                if (part) part[(size_t)(it.tok_off + ti) * a.v_stride + jr] = val[r];
+                // the tile's whole k range: the result itself; else this piece's partial sum, one row per row
+                // of the tile (mfma_reduce_kernel adds the pieces up)
+                if (part) part[(size_t)ti * a.v_stride + jr] = val[r];
                 else a.v[(size_t)tile_token(a, it, ti) * a.v_stride + jr] = val[r];
             }
         }
@@ -234,53 +237,62 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     }
 }
 
-__global__ __launch_bounds__(256) void mfma_shrink_kernel(ApplyArgs a, ShrinkProjs ps, const DevItem *__restrict__ tiles,
-                                                          int n_tiles, int splits, int k_len, int n_tile_tok)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void mfma_shrink_kernel(const ShrinkCut *__restrict__ cuts, const DevItem *__restrict__ tiles,
+                                                          int runs_per_xcd, int n_proj, int quanta, int n_tiles, ApplyArgs a,
+                                                          ShrinkProjs ps)
 {
     __shared__ __attribute__((aligned(16))) unsigned char xs[NSTAGE][LORA_TILE_TOKENS * XROW];
     static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the k-split reduction reuses the x ring");
 
-    // XCD j = blockIdx % 8 works on the tiles [xcd_tile[j], xcd_tile[j+1]); its i-th block on item i of
-    // ((tile, split), projection), projection innermost: the blocks that read the same part of x
-    // for the projections of a group are neighbours in the dispatch order of one XCD and walk k in
-    // the same order, so that x is fetched from memory once and found in L2 by the others
+    // XCD j = blockIdx % 8 works on the runs [j * runs_per_xcd, (j + 1) * runs_per_xcd); its i-th block on
+    // (run, projection) number i, projection innermost: the blocks that read the same part of x for the
+    // projections of a group are neighbours in the dispatch order of one XCD and walk k in the same order, so
+    // that x is fetched from memory once and found in L2 by the others
     const int xcd = (int)blockIdx.x & 7, local = (int)blockIdx.x >> 3;
-    const int per_tile = splits * ps.n;
-    if (local >= (ps.xcd_tile[xcd + 1] - ps.xcd_tile[xcd]) * per_tile) return;  // uniform
-    const int ts = ps.xcd_tile[xcd] * splits + local / ps.n, pj = local % ps.n;
-    const int tile = ts / splits, split = ts - tile * splits;
-    const DevItem it = tiles[tile];
-    const int k_begin = split * k_len;
-    const int k_end = min(a.h_in, k_begin + k_len);
-    if (k_begin >= k_end) return;
+    const int run = xcd * runs_per_xcd + local / n_proj, pj = local % n_proj;
+    const ShrinkCut from = cuts[run], to = cuts[run + 1];
     a.proj_base = ps.proj_base[pj];
     a.row_bytes = ps.row_bytes[pj];
     a.v = ps.v[pj];
-    const int n_st = (k_end - k_begin + SK - 1) / SK;
-    const int phase = (int)(((unsigned)ts * 5u) % (unsigned)n_st);
-    float *my_part = splits > 1 ? ps.part[pj] + (size_t)split * n_tile_tok * a.v_stride : nullptr;
-    const int NB = (it.rank + 15) >> 4;
-    if (NB > 4) mfma_shrink_body<true, 2>(a, it, k_begin, k_end, phase, my_part, xs);
-    else if (NB == 4) mfma_shrink_body<true, 1>(a, it, k_begin, k_end, phase, my_part, xs);
-    else if (NB == 3) mfma_shrink_body<false, 3>(a, it, k_begin, k_end, phase, my_part, xs);
-    else if (NB == 2) mfma_shrink_body<false, 2>(a, it, k_begin, k_end, phase, my_part, xs);
-    else mfma_shrink_body<false, 1>(a, it, k_begin, k_end, phase, my_part, xs);
+    const int last_tile = min(to.part > 0 ? to.tile : to.tile - 1, n_tiles - 1);
+    for (int tile = from.tile; tile <= last_tile; ++tile) {
+        const int lo = tile == from.tile ? from.part : 0, hi = tile == to.tile ? to.part : quanta;
+        if (lo >= hi) continue;  // (an empty run)
+        const DevItem it = tiles[tile];
+        const int k_begin = shrink_part_stage(lo, quanta, a.h_in, SK) * SK;
+        const int k_end = min(a.h_in, shrink_part_stage(hi, quanta, a.h_in, SK) * SK);
+        const int n_st = (k_end - k_begin + SK - 1) / SK;
+        const int phase = (int)(((unsigned)(run + tile) * 5u) % (unsigned)n_st);
+        float *my_part = (lo == 0 && hi == quanta)
+                             ? nullptr
+                             : ps.part[pj] + (size_t)shrink_slot(run, from.tile, tile) * SHRINK_SLOT_ROWS * a.v_stride;
+        const int NB = (it.rank + 15) >> 4;
+        if (NB > 4) mfma_shrink_body<true, 2>(a, it, k_begin, k_end, phase, my_part, xs);
+        else if (NB == 4) mfma_shrink_body<true, 1>(a, it, k_begin, k_end, phase, my_part, xs);
+        else if (NB == 3) mfma_shrink_body<false, 3>(a, it, k_begin, k_end, phase, my_part, xs);
+        else if (NB == 2) mfma_shrink_body<false, 2>(a, it, k_begin, k_end, phase, my_part, xs);
+        else mfma_shrink_body<false, 1>(a, it, k_begin, k_end, phase, my_part, xs);
+        __syncthreads();  // the next piece reuses the ring
+    }
 }
 
-// V[token][0..rank) = sum over the k splits of the partials.  One block per tile.  (Atomic adds
-// into V instead cost about 30 us per launch: device-scope fp32 atomics execute at the memory side.)
-__global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkProjs ps, const DevItem *__restrict__ tiles,
-                                                          int splits, int n_tile_tok)
+// V[token][0..rank) = sum over the tile's pieces of their partial sums, for the tiles worked on in pieces.
+// (Atomic adds into V instead cost about 30 us per launch: device-scope fp32 atomics execute at the memory side.)
+__global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkProjs ps, const DevItem *__restrict__ tiles)
 {
     // 8 blocks per tile (and projection of the group: blockIdx.y), 8 tokens each; a thread sums one
     // float4 column of one token
-    const DevItem it = tiles[blockIdx.x >> 3];
+    const int tile = blockIdx.x >> 3;
+    const ShrinkSum sm = ps.sums[tile];
+    if (sm.n_pieces < 2) return;
+    const DevItem it = tiles[tile];
     const int ti = (blockIdx.x & 7) * 8 + (threadIdx.x >> 5), j4 = threadIdx.x & 31;
     if (ti >= it.n_tok || j4 * 4 >= rank_storage(it.rank)) return;  // entries past the rank are never used
-    const float4 *src = reinterpret_cast<const float4 *>(ps.part[blockIdx.y] + (size_t)(it.tok_off + ti) * a.v_stride) + j4;
-    float4 sum = src[0];
-    for (int sp = 1; sp < splits; ++sp) {
-        const float4 v = src[(size_t)sp * n_tile_tok * (a.v_stride >> 2)];
+    const size_t slot_f4 = (size_t)SHRINK_SLOT_ROWS * (a.v_stride >> 2);
+    const float4 *src = reinterpret_cast<const float4 *>(ps.part[blockIdx.y]) + (size_t)ti * (a.v_stride >> 2) + j4;
+    float4 sum = src[(size_t)sm.first_slot * slot_f4];
+    for (int pc = 1; pc < sm.n_pieces; ++pc) {
+        const float4 v = src[(size_t)(2 * ((sm.first_slot >> 1) + pc)) * slot_f4];
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
     reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)tile_token(a, it, ti) * a.v_stride)[j4] = sum;
@@ -308,7 +320,7 @@ constexpr int CS_ROW = 64 * 4 + 16;  // bytes per token row of a wavefront's par
 // KS: MFMA k steps of 32 ranks.  As in the shrink, global loads are unconditional from clamped
 // addresses: rank chunks past the stored rank re-read the last stored chunk and meet zeros in V.
 template <int KS>
-__device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevItem &it, int n_pass, unsigned char *vs,
+__device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevItem &it, int col_run, int n_pass, unsigned char *vs,
                                                  unsigned char (*cs)[32 * CS_ROW])
 {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -331,7 +343,7 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
         yoff[i] = (size_t)(yok[i] ? tile_token(a, it, ti) : it.tok0) * a.h_out + rc * 8;
     }
     const bool half_live = 32 * th < it.n_tok;
-    const int col0 = blockIdx.y * n_pass * 128 + 64 * ch;
+    const int col0 = col_run * n_pass * 128 + 64 * ch;
 
     // base_out of pass `cp`
     auto load_y = [&](int cp, uint4(&d)[4]) {
@@ -429,47 +441,46 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_pass)
+// Blocks -> (tile, column run).  With few tiles (runs_fast): block b works on column run b % runs_padded of tile
+// b / runs_padded, runs_padded a multiple of 8 (or a power of two below 8): block b runs on XCD b % 8, so a column
+// run -- the same columns of every tile -- always falls on the same XCD (or the same 8 / runs_padded of them) and a
+// prompt's Bp is fetched from memory by one XCD per column run instead of by all eight (with the tiles as the fast
+// index the prefill expand fetched 147 MB for 101 MB; -6 % time on the prefill and stress configurations).  With
+// many tiles the tiles are the fast index: there the other order measured 4 % slower (mixed configuration).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_tiles,
+                                                                                                        int n_pass, int n_runs, int runs_padded)
 {
     __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
     __shared__ __attribute__((aligned(16))) unsigned char cs[4][32 * CS_ROW];
-    const DevItem it = tiles[blockIdx.x];
+    int tile, col_run;
+    if (runs_padded > 0) {
+        tile = (int)blockIdx.x / runs_padded;
+        col_run = (int)blockIdx.x - tile * runs_padded;
+        if (col_run >= n_runs) return;  // padding
+    } else {
+        col_run = (int)blockIdx.x / n_tiles;
+        tile = (int)blockIdx.x - col_run * n_tiles;
+    }
+    const DevItem it = tiles[tile];
     switch ((it.rank + 31) >> 5) {
-    case 1: mfma_expand_body<1>(a, it, n_pass, vs, cs); break;
-    case 2: mfma_expand_body<2>(a, it, n_pass, vs, cs); break;
-    case 3: mfma_expand_body<3>(a, it, n_pass, vs, cs); break;
-    default: mfma_expand_body<4>(a, it, n_pass, vs, cs); break;
+    case 1: mfma_expand_body<1>(a, it, col_run, n_pass, vs, cs); break;
+    case 2: mfma_expand_body<2>(a, it, col_run, n_pass, vs, cs); break;
+    case 3: mfma_expand_body<3>(a, it, col_run, n_pass, vs, cs); break;
+    default: mfma_expand_body<4>(a, it, col_run, n_pass, vs, cs); break;
     }
 }
 
 // k ranges are multiples of the 128-element stage.
-static int shrink_k_len(int h_in, int want)
+hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, hipStream_t st,
+                              const KernelTimer *tm)
 {
-    int k_len = (h_in + want - 1) / want;
-    return (k_len + SK - 1) / SK * SK;
-}
-
-int mfma_shrink_splits(int h_in, int want)
-{
-    if (want < 1) want = 1;
-    const int k_len = shrink_k_len(h_in, want);
-    return (h_in + k_len - 1) / k_len;
-}
-
-hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, int n_tile_tok,
-                              int k_splits, hipStream_t st, const KernelTimer *tm)
-{
-    if (n_tiles <= 0 || ps.n <= 0) return hipSuccess;
-    const int k_len = shrink_k_len(a.h_in, k_splits < 1 ? 1 : k_splits);
-    const int splits = (a.h_in + k_len - 1) / k_len;
-    int most = 0;
-    for (int j = 0; j < 8; ++j) most = std::max(most, ps.xcd_tile[j + 1] - ps.xcd_tile[j]);
-    const int blocks = 8 * most * splits * ps.n;  // XCD j takes the blocks j, j + 8, ...
-    launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(blocks), dim3(256), st, a, ps, tiles, n_tiles, splits, k_len,
-             n_tile_tok);
-    if (splits > 1)
-        launch_k(tm, LORA_K_MFMA_REDUCE, mfma_reduce_kernel, dim3(n_tiles * 8, ps.n), dim3(256), st, a, ps, tiles, splits,
-                 n_tile_tok);
+    if (n_tiles <= 0 || ps.n <= 0 || ps.n_runs <= 0) return hipSuccess;
+    if (ps.n_runs % 8 != 0 || ps.quanta < 1) return hipErrorInvalidValue;
+    const int runs_per_xcd = ps.n_runs / 8;
+    launch_k(tm, LORA_K_MFMA_SHRINK, mfma_shrink_kernel, dim3(ps.n_runs * ps.n), dim3(256), st, ps.cuts, tiles, runs_per_xcd, ps.n,
+             ps.quanta, n_tiles, a, ps);
+    if (ps.any_pieces)
+        launch_k(tm, LORA_K_MFMA_REDUCE, mfma_reduce_kernel, dim3(n_tiles * 8, ps.n), dim3(256), st, a, ps, tiles);
     return hipGetLastError();
 }
 
@@ -479,8 +490,16 @@ hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_ti
     // the widest column run per block that still gives 512 blocks (two per CU), else the narrowest
     int cols = 1024;
     while (cols > 256 && (int64_t)n_tiles * ((a.h_out + cols - 1) / cols) < 512) cols >>= 1;
-    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles, (a.h_out + cols - 1) / cols), dim3(256), st, a, tiles,
-             cols / 128);
+    const int n_runs = (a.h_out + cols - 1) / cols;
+    int runs_padded = 0;  // 0: tiles are the fast index
+    if (n_tiles <= 256) {
+        runs_padded = 1;
+        if (n_runs >= 8) runs_padded = (n_runs + 7) / 8 * 8;
+        else
+            while (runs_padded < n_runs) runs_padded <<= 1;
+    }
+    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles * (runs_padded ? runs_padded : n_runs)), dim3(256), st, a, tiles,
+             n_tiles, cols / 128, n_runs, runs_padded);
     return hipGetLastError();
 }
 

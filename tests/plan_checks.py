@@ -50,7 +50,49 @@ def check_plan_units(cache, plan, T, seg_offsets, seg_slot, seg_rank, projs, alp
             assert list(toks_of(u)) == wt and (u["slot"], u["rank"]) == (slot, rank)
             assert 1 <= u["n_tok"] <= B.LORA_TILE_TOKENS
             same_entry(u)
-        assert (np.diff(tiles["where"]) >= 0).all() and ((tiles["where"] >= 0) & (tiles["where"] < 8)).all()
+
+        # --- tile shrink: under every run table the pieces of a tile cover its input columns [0, h_in) once, in pieces
+        # of whole 128-column stages; runs are walked in order, each at most a tail, whole tiles and a head; pieces that
+        # are not whole tiles leave partial sums in slots of their own, and the reduce adds up exactly those
+        pieces = units[units["kind"] == B.LORA_UNIT_TILE_SHRINK]
+        sums = units[units["kind"] == B.LORA_UNIT_TILE_SUM]
+        tile_of_off = {int(u["tok_off"]): i for i, u in enumerate(tiles)}
+        for table in range(5):
+            pc = pieces[(pieces["where"] >> 20) == table]
+            sm = sums[(sums["where"] >> 20) == table]
+            if len(tiles) == 0:
+                assert len(pc) == 0 and len(sm) == 0
+                continue
+            runs = pc["where"] & 0xFFFFF
+            assert (np.diff(runs) >= 0).all() and runs.max() < 512 // (1 if table == 4 else table + 1)
+            if table == 4:
+                assert runs.max() < 128
+            cover = np.zeros((len(tiles), h_in), np.int8)
+            slots_of_tile = [[] for _ in tiles]
+            order = []
+            for u in pc:
+                i = tile_of_off[int(u["tok_off"])]
+                assert (u["n_tok"], u["slot"], u["rank"]) == (tiles[i]["n_tok"], tiles[i]["slot"], tiles[i]["rank"])
+                assert 0 <= u["lo"] < u["hi"] <= h_in and u["lo"] % 128 == 0 and (u["hi"] % 128 == 0 or u["hi"] == h_in)
+                cover[i, u["lo"] : u["hi"]] += 1
+                whole = u["lo"] == 0 and u["hi"] == h_in
+                assert (u["alpha"] == -1) == whole
+                if not whole:
+                    assert u["hi"] - u["lo"] >= min(256, h_in // 2), u  # no slivers
+                    slots_of_tile[i].append(int(u["alpha"]))
+                order.append((i, int(u["lo"])))
+            assert (cover == 1).all()
+            assert order == sorted(order)  # the runs walk the tiles' columns in order
+            all_slots = [s for l in slots_of_tile for s in l]
+            assert len(set(all_slots)) == len(all_slots) and all(0 <= s < 2 * (int(runs.max()) + 1) for s in all_slots)
+            for r in np.unique(runs):  # a run leaves at most two partial sums
+                assert (pc[runs == r]["alpha"] >= 0).sum() <= 2
+            got = [[] for _ in tiles]
+            for u in sm:
+                i = tile_of_off[int(u["tok_off"])]
+                assert u["lo"] == len(got[i]) and u["hi"] == len(slots_of_tile[i])
+                got[i].append(int(u["alpha"]))
+            assert got == slots_of_tile
 
         # --- GEMV shrink: every (token, rank row) once
         gs = units[units["kind"] == B.LORA_UNIT_GEMV_SHRINK]
@@ -95,5 +137,6 @@ def check_plan_units(cache, plan, T, seg_offsets, seg_slot, seg_rank, projs, alp
                 assert (tm_slot[toks_of(u)] == -1).all()
         else:
             assert len(lin) == 0
-        counts[p] = {"tiles": len(tiles), "gemv_shrink": len(gs), "gemv_expand": len(ge), "linear_rows": len(lin)}
+        counts[p] = {"tiles": len(tiles), "gemv_shrink": len(gs), "gemv_expand": len(ge), "linear_rows": len(lin),
+                     "tile_partial_sums": int((pieces["alpha"] >= 0).sum())}
     return counts

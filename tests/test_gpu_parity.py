@@ -376,8 +376,9 @@ def test_whole_adapter_fill_in_one_call():
 def test_multi_apply_groups_projections_that_share_their_input():
     """q, k, v read one x: the list form runs one tile-shrink launch for all of them, then their
     expands.  Results must be those of one apply after the other -- also when one of the outputs
-    is the shared input itself (then nothing may be reordered) -- for both GEMV launch forms, with
-    and without k splits."""
+    is the shared input itself (then nothing may be reordered) -- for both GEMV launch forms, with the
+    GEMV launch beside the tile kernels on the cache's side stream (the default) and behind them on the
+    caller's."""
     B, H = _mods()
     base_inst = wl.small_mixed(seed=9)
     projs = [wl.Projection("q", 512, 512, 0), wl.Projection("k", 512, 256, 0), wl.Projection("v", 512, 384, 0),
@@ -386,7 +387,7 @@ def test_multi_apply_groups_projections_that_share_their_input():
     inst = wl.Instance(name="qkv", dtype="bf16", seed=9, projs=projs, ranks=base_inst.ranks, adapter_ids=base_inst.adapter_ids,
                        alpha=base_inst.alpha, scale=base_inst.scale, seg_offsets=base_inst.seg_offsets,
                        seg_adapter=base_inst.seg_adapter)
-    for flags in (B.LORA_CACHE_FUSED_GEMV, B.LORA_CACHE_SPLIT_GEMV):
+    for flags in (B.LORA_CACHE_FUSED_GEMV, B.LORA_CACHE_SPLIT_GEMV, B.LORA_CACHE_FUSED_GEMV | B.LORA_CACHE_NO_OVERLAP):
         pi = H.PooledInstance(inst, mfma_min_tokens=16, flags=flags)
         try:
             plan = pi.pool.plan(inst.T, inst.seg_offsets, pi.seg_slot, pi.seg_rank)

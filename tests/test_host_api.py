@@ -129,6 +129,25 @@ def test_plan_work_units_on_random_batches():
         _host_plan_check(int(off[-1]), off, slot, rank, projs, B.LORA_BF16, int(rng.choice([0, 1, 8, 16, 64])))
 
 
+def test_plan_tile_shrink_pieces_on_random_prompt_batches():
+    """Wide inputs and long segments: tiles are worked on in pieces, with cuts inside tiles (checked by check_plan_units)."""
+    rng = np.random.default_rng(7)
+    in_pieces = 0
+    for trial in range(12):
+        n_seg = int(rng.integers(1, 14))
+        lens = rng.choice([1, 3, 40, 64, 65, 128, 200, 513, 1000], size=n_seg)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        n_names = int(rng.integers(1, 6))
+        name_rank = rng.choice([8, 16, 32, 64, 100, 128], size=n_names)
+        slot = rng.integers(-1, n_names, size=n_seg).astype(np.int32)
+        rank = np.where(slot >= 0, name_rank[np.maximum(slot, 0)], 0).astype(np.int32)
+        widths = [int(w) for w in rng.choice([1024, 1536, 2048, 4096, 5120], size=int(rng.integers(1, 3)))]
+        projs = [(w, 64 * int(rng.choice([1, 16, 17]))) for w in widths]
+        counts = _host_plan_check(int(off[-1]), off, slot, rank, projs, B.LORA_BF16, int(rng.choice([0, 16])))
+        in_pieces += counts[0]["tile_partial_sums"] > 0
+    assert in_pieces >= 6
+
+
 def test_slot_state_call():
     h = _host_cache()
     assert B.lora_cache_slot_state(h, 2) == (B.LORA_OK, B.LORA_SLOT_EMPTY)
