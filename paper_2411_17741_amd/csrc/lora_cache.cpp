@@ -513,7 +513,7 @@ void build_shrink_runs(const lora::DevItem *tiles, int n_tiles, int quanta, int 
         return runs;
     };
     int64_t lo = w_max * std::min<int64_t>(MINP, quanta) + PIECE, hi = std::max(total, lo);  // hi: one run takes everything
-    while (lo < hi) {
+    while (hi - lo > hi / 128) {  // to within 1 % of the smallest limit
         const int64_t mid = lo + (hi - lo) / 2;
         if (walk(mid, nullptr) <= max_runs) hi = mid;
         else lo = mid + 1;
@@ -652,6 +652,7 @@ int build_plan(lora_cache &c, lora_plan &p, int32_t T, const int32_t *seg_offset
         const int64_t slots = std::min<int64_t>(SHRINK_MAX_RUNS, 2 * (int64_t)c.n_cu);
         const lora::DevItem *dev_tiles = reinterpret_cast<const lora::DevItem *>(w.tiles);  // stamped above
         for (int v = 0; v < SHRINK_VARIANTS && w.n_tiles > 0 && c.vpart_rows > 0; ++v) {
+            if (v == SHRINK_VARIANT_SMALL && T > LORA_STATIC_MAX_TOKENS) continue;  // lora_apply_plan_static refuses such a batch
             const int n = v == SHRINK_VARIANT_SMALL ? 1 : v + 1;
             int64_t max_runs = slots / 8 / n * 8;
             max_runs = std::min(max_runs, (v == SHRINK_VARIANT_SMALL ? STATIC_VPART_ROWS : c.vpart_rows) / (2 * lora::SHRINK_SLOT_ROWS) / n / 8 * 8);
@@ -1472,6 +1473,7 @@ int lora_plan_dump(lora_cache_t *c, const lora_plan_t *p, int32_t proj, lora_pla
     // the tile shrink's pieces for this projection's h_in, per run table, walked as the kernel walks them; and the
     // scratch slots the reduce adds up per tile
     for (int v = 0; v < SHRINK_VARIANTS && p->n_tiles > 0; ++v) {
+        if (p->shrink_runs[v] == 0) continue;  // (no such table: the batch is too large for the call it serves)
         const lora::ShrinkCut *cuts = reinterpret_cast<const lora::ShrinkCut *>(buf + p->off_cuts[v]);
         const lora::ShrinkSum *sums = reinterpret_cast<const lora::ShrinkSum *>(buf + p->off_sums[v]);
         const int32_t quanta = p->shrink_quanta, h_in = c->proj[proj].h_in, SK = lora::SHRINK_STAGE_K;
@@ -1573,6 +1575,7 @@ static int shrink_setup(const lora_cache_t *c, const lora_plan_t *p, int n, char
     if (n < 1 || n > lora::MAX_SHRINK_PROJS || (small && n != 1)) return LORA_E_INVAL;
     ps.n = n;
     ps.n_runs = p->shrink_runs[v];
+    if (p->n_tiles > 0 && ps.n_runs == 0) return LORA_E_STATE;  // the plan carries no such table
     ps.quanta = p->shrink_quanta;
     ps.any_pieces = p->shrink_pieces[v] ? 1 : 0;
     ps.cuts = reinterpret_cast<const lora::ShrinkCut *>(p->dev + p->off_cuts[v]);
