@@ -13,11 +13,11 @@ What the paper fixes:
 * every queue owns a quota of tokens; a request needs its input tokens + its output tokens + the
   tokens its adapter's memory amounts to; an admitted request borrows what it needs and gives it
   back when it ends;
-* a batch is formed in two phases (the paper's batch-generation listing): first every queue, from
+* a batch is formed in two rounds (the paper's batch-generation algorithm): first every queue, from
   the smallest requests up, admits requests in arrival order while its own free quota lasts and
-  stops at the first that does not fit; a queue that ran empty puts its unused quota into a common
-  spare bucket; then, again from the smallest requests up, each queue admits further requests out
-  of the bucket in the same way, until the bucket is empty;
+  stops at the first that does not fit; a queue that ran empty leaves its unused quota as spare
+  tokens; then, again from the smallest requests up, each queue admits further requests out
+  of the spare tokens in the same way, until none are left;
 * the least quota of a queue whose largest request has S tokens, takes D to process, arrives at rate
   lambda and must meet an SLO is  S * D * (1 / SLO + lambda);  every queue gets its least quota and the
   rest of the tokens is split in proportion to given weights.
@@ -41,6 +41,9 @@ traces, first-come-first-served order within a queue.
 """
 from __future__ import annotations
 
+import bisect
+import functools
+import itertools
 import math
 from collections import deque
 from typing import Dict, List, Sequence, Tuple
@@ -71,28 +74,35 @@ def _sse(values: Sequence[float]) -> float:
 def kmeans_1d(values: Sequence[float], k: int) -> Tuple[float, List[float]]:
     """Optimal K-means of numbers on a line -> (within-cluster sum of squares, centroids ascending).
 
-    In one dimension the optimal clusters are runs of the sorted values, so the optimum is found by
-    trying, for every prefix and every number of clusters, every place for the last cut."""
+    In one dimension the optimal clusters are runs of the sorted values.  Stated as a recursion on what
+    is left: the best way to put the values from position `i` on into `c` clusters is the best choice of
+    where the first of them ends, plus the best way to put the rest into c - 1 (memoised)."""
     xs = sorted(values)
     n = len(xs)
     k = min(k, n)
-    best = [[math.inf] * (n + 1) for _ in range(k + 1)]
-    cut = [[0] * (n + 1) for _ in range(k + 1)]
-    best[0][0] = 0.0
-    for c in range(1, k + 1):
-        for end in range(c, n + 1):
-            for start in range(c - 1, end):
-                cost = best[c - 1][start] + _sse(xs[start:end])
-                if cost < best[c][end]:
-                    best[c][end] = cost
-                    cut[c][end] = start
-    centroids = []
-    end = n
-    for c in range(k, 0, -1):
-        start = cut[c][end]
-        centroids.append(sum(xs[start:end]) / (end - start))
-        end = start
-    return best[k][n], centroids[::-1]
+    # sums and sums of squares up to a position: the sum of squares of a run around its own mean in closed form
+    s1 = [0.0] + list(itertools.accumulate(xs))
+    s2 = [0.0] + list(itertools.accumulate(x * x for x in xs))
+
+    def spread(i: int, j: int) -> float:  # of xs[i:j], j > i
+        return max(0.0, (s2[j] - s2[i]) - (s1[j] - s1[i]) ** 2 / (j - i))
+
+    @functools.lru_cache(maxsize=None)
+    def rest(i: int, c: int) -> Tuple[float, Tuple[int, ...]]:
+        """-> (sum of squares, ends of the clusters) for xs[i:] in c clusters."""
+        if c == 1:
+            return spread(i, n), (n,)
+        options = ((spread(i, j) + rest(j, c - 1)[0], j) for j in range(i + 1, n - c + 2))
+        cost, j = min(options)  # ties: the earliest end
+        return cost, (j,) + rest(j, c - 1)[1]
+
+    if n == 0:
+        return 0.0, []
+    cost, ends = rest(0, k)
+    starts = (0,) + ends[:-1]
+    # the cost once more from the clusters themselves, around their means (no cancellation)
+    exact = sum(_sse(xs[i:j]) for i, j in zip(starts, ends))
+    return exact, [sum(xs[i:j]) / (j - i) for i, j in zip(starts, ends)]
 
 
 def fit_queues(sizes: Sequence[float], k_max: int = 4) -> Tuple[int, List[float]]:
@@ -164,41 +174,52 @@ class Scheduler:
     def needed(self, r: Request) -> int:
         return r.input_len + r.output_len + r.rank * self.tokens_per_rank
 
-    def _put_batch(self, q: int, sources: List[List[int]], batch: List[Request]) -> int:
-        """Admit requests of queue q in arrival order out of `sources` ([queue, tokens] pairs, drawn in
-        order); stop at the first that does not fit.  -> tokens consumed."""
-        consumed = 0
-        while self.queues[q]:
-            r = self.queues[q][0]
-            need = self.needed(r)
-            if sum(t for _, t in sources) < need:
-                break
-            take = need
-            for src in sources:
-                part = min(take, src[1])
-                if part > 0:
-                    src[1] -= part
-                    self.free[src[0]] -= part
-                    r.borrowed.append((src[0], part))
-                    take -= part
-            consumed += need
-            self.queues[q].popleft()
-            self.running[r.req_id] = r
-            batch.append(r)
-        return consumed
+    def _fitting(self, q: int, tokens: int) -> int:
+        """How many requests at the head of queue q can be admitted, in arrival order, out of `tokens`:
+        the longest prefix whose needs add up to no more than that (admission stops at the first request
+        that does not fit, later ones do not overtake it)."""
+        upto = list(itertools.accumulate(self.needed(r) for r in self.queues[q]))
+        return bisect.bisect_right(upto, tokens)
 
     def generate_batch(self) -> List[int]:
+        """One batch, as section 4.3 describes its formation (two rounds over the queues, smallest requests first).
+
+        Round 1 is per queue and independent of the others: a queue admits what fits its own free quota.
+        Round 2 hands out what emptied queues left over.  Those leftovers are laid end to end, queue after
+        queue, as one line of tokens; every request admitted in round 2 takes the next stretch of that line,
+        and owes each queue the part of its stretch that lies in that queue's leftover."""
         batch: List[Request] = []
-        bucket: List[List[int]] = []
-        for q in range(len(self.queues)):            # phase 1: every queue out of its own free quota
-            own = [[q, self.free[q]]]
-            self._put_batch(q, own, batch)
-            if not self.queues[q] and own[0][1] > 0:
-                bucket.append(own[0])                # what an emptied queue did not use is spare
-        for q in range(len(self.queues)):            # phase 2: the spare tokens, smallest requests first
-            if sum(t for _, t in bucket) == 0:
+
+        def admit(r: Request) -> None:
+            self.running[r.req_id] = r
+            batch.append(r)
+
+        lots: List[Tuple[int, int]] = []  # (owner queue, tokens), in queue order
+        for q in range(len(self.queues)):
+            for _ in range(self._fitting(q, self.free[q])):
+                r = self.queues[q].popleft()
+                r.borrowed.append((q, self.needed(r)))
+                self.free[q] -= self.needed(r)
+                admit(r)
+            if not self.queues[q] and self.free[q] > 0:
+                lots.append((q, self.free[q]))
+
+        ends = list(itertools.accumulate(t for _, t in lots))  # where each lot ends on the line
+        line = ends[-1] if ends else 0
+        at = 0  # tokens of the line handed out so far
+        for q in range(len(self.queues)):
+            if at == line:
                 break
-            self._put_batch(q, bucket, batch)
+            for _ in range(self._fitting(q, line - at)):
+                r = self.queues[q].popleft()
+                lo, hi = at, at + self.needed(r)
+                for (owner, tokens), end in zip(lots, ends):
+                    part = min(hi, end) - max(lo, end - tokens)  # overlap of [lo, hi) with this lot
+                    if part > 0:
+                        r.borrowed.append((owner, part))
+                        self.free[owner] -= part
+                at = hi
+                admit(r)
         return [r.req_id for r in batch]
 
     def finish(self, req_id: int) -> None:
