@@ -13,7 +13,7 @@ What the paper fixes:
 * every queue owns a quota of tokens; a request needs its input tokens + its output tokens + the
   tokens its adapter's memory amounts to; an admitted request borrows what it needs and gives it
   back when it ends;
-* a batch is formed in two rounds (the paper's batch-generation algorithm): first every queue, from
+* a batch is formed in two passes (the paper's batch-generation algorithm): first every queue, from
   the smallest requests up, admits requests in arrival order while its own free quota lasts and
   stops at the first that does not fit; a queue that ran empty leaves its unused quota as spare
   tokens; then, again from the smallest requests up, each queue admits further requests out
@@ -182,11 +182,11 @@ class Scheduler:
         return bisect.bisect_right(upto, tokens)
 
     def generate_batch(self) -> List[int]:
-        """One batch, as section 4.3 describes its formation (two rounds over the queues, smallest requests first).
+        """One batch, as section 4.3 describes its formation (two passes over the queues, smallest requests first).
 
-        Round 1 is per queue and independent of the others: a queue admits what fits its own free quota.
-        Round 2 hands out what emptied queues left over.  Those leftovers are laid end to end, queue after
-        queue, as one line of tokens; every request admitted in round 2 takes the next stretch of that line,
+        The first pass is per queue and independent of the others: a queue admits what fits its own free quota.
+        The second pass hands out what emptied queues left over.  Those leftovers are laid end to end, queue after
+        queue, as one line of tokens; every request admitted in the second pass takes the next stretch of that line,
         and owes each queue the part of its stretch that lies in that queue's leftover."""
         batch: List[Request] = []
 
