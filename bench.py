@@ -463,6 +463,8 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
     n_layers = args.layers or DEFAULT_LAYERS[workload]
     if workload == "decode_paper":
         inst = wl.decode_paper(seed=0, n_adapters=args.adapters, n_decode=args.tokens)
+    elif workload == "decode_qkv" and args.tokens != 64:
+        inst = wl.decode_qkv(seed=0, n_decode=args.tokens)
     else:
         inst = wl.CONFIGS[workload](seed=0)
     t_setup = time.time()
@@ -734,7 +736,7 @@ def main() -> int:
     ap.add_argument("--mfma-min-tokens", type=int, default=0, help="tokens of one slot from which the matrix-core tile path is taken (0: library default)")
     ap.add_argument("--direct-fill", action="store_true", help="fills read pinned host memory from the repack kernel (LORA_CACHE_DIRECT_FILL)")
     ap.add_argument("--adapters", type=int, default=100, help="decode_paper: number of adapters N_a (a multiple of 5)")
-    ap.add_argument("--tokens", type=int, default=64, help="decode_paper: one-token requests in the batch")
+    ap.add_argument("--tokens", type=int, default=64, help="decode_paper, decode_qkv: one-token requests in the batch")
     ap.add_argument("--fused-base", action="store_true", help="time lora_linear_plan (base projection and adapter update in one pass; "
                     "random base weights) instead of the apply on a given base output; prints its own JSON line")
     ap.add_argument("--prefetch-depths", default="", help="e.g. 0,1,2,4: run the queue-driven prefetch experiment instead (own JSON line); "
