@@ -298,10 +298,12 @@ void compute_layout(lora_cache &c, const lora_cache_config_t *cfg)
     c.off_v = cur;
     c.v_set_bytes = align_up(sizeof(float) * (size_t)c.max_tokens * c.v_stride);
     cur += c.v_set_bytes * N_VSETS;
-    // partial sums of the tile shrink: two slots per run; a batch of few tiles has few runs (a run is at least an
-    // eighth of a tile)
+    // partial sums of the tile shrink: two slots per run and projection of a group; a launch has at most
+    // SHRINK_MAX_RUNS blocks whatever the group's size, and a batch of few tiles has few runs (a piece is at least
+    // two of the parts a tile's k range is cut into)
     {
-        const int64_t runs = std::min<int64_t>(SHRINK_MAX_RUNS, 8 * std::max<int64_t>(N_VSETS, ((int64_t)c.max_tokens + LORA_TILE_TOKENS - 1) / LORA_TILE_TOKENS));
+        const int64_t tiles = std::max<int64_t>(1, ((int64_t)c.max_tokens + LORA_TILE_TOKENS - 1) / LORA_TILE_TOKENS);
+        const int64_t runs = std::min<int64_t>(SHRINK_MAX_RUNS, 16 * N_VSETS * tiles);
         c.vpart_rows = c.dtype == LORA_BF16 ? 2 * lora::SHRINK_SLOT_ROWS * runs : 0;
     }
     c.off_vpart = cur;
