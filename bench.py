@@ -43,7 +43,7 @@ TRAFFIC_SOURCE = "profiles/kernel_traffic_all_workloads.txt"
 MEASURED_TRAFFIC = {("decode", "gemv_fused"): 24.94e6, ("decode_qkv", "gemv_fused"): 72.14e6, ("prefill", "mfma_shrink"): 66.56e6,
                     ("prefill", "mfma_expand"): 125.55e6, ("mixed", "mfma_expand"): 661.75e6, ("mixed", "mfma_shrink"): 406.01e6,
                     ("mixed", "gemv_fused"): 178.29e6, ("stress", "gemv_fused"): 357.24e6, ("stress", "mfma_expand"): 105.16e6,
-                    ("stress", "mfma_shrink"): 71.32e6}
+                    ("stress", "mfma_shrink"): 73.27e6}
 DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32, "decode_qkv": 16}
 DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100, "decode_qkv": 100}
 
