@@ -290,10 +290,28 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkPro
     if (ti >= it.n_tok || j4 * 4 >= rank_storage(it.rank)) return;  // entries past the rank are never used
     const size_t slot_f4 = (size_t)SHRINK_SLOT_ROWS * (a.v_stride >> 2);
     const float4 *src = reinterpret_cast<const float4 *>(ps.part[blockIdx.y]) + (size_t)ti * (a.v_stride >> 2) + j4;
-    float4 sum = src[(size_t)sm.first_slot * slot_f4];
-    for (int pc = 1; pc < sm.n_pieces; ++pc) {
-        const float4 v = src[(size_t)(2 * ((sm.first_slot >> 1) + pc)) * slot_f4];
-        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    // four pieces at a time: their loads are issued together (one after the other, a tile in seven pieces took
+    // seven trips to memory: 6.5 us per launch on the stress configuration), and only the loads that are needed (loads of a
+    // padded batch cost the mixed configuration, two to three pieces per tile, 1 to 2 us)
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto piece = [&](int pc) __attribute__((always_inline)) {
+        return src[(size_t)(pc == 0 ? sm.first_slot : 2 * ((sm.first_slot >> 1) + pc)) * slot_f4];
+    };
+    auto add = [&](const float4 &v) __attribute__((always_inline)) { sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w; };
+    for (int p0 = 0; p0 < sm.n_pieces; p0 += 4) {
+        const int n = sm.n_pieces - p0;  // the same for the whole block: the branches below are scalar
+        if (n >= 4) {
+            const float4 v0 = piece(p0), v1 = piece(p0 + 1), v2 = piece(p0 + 2), v3 = piece(p0 + 3);
+            add(v0); add(v1); add(v2); add(v3);
+        } else if (n == 3) {
+            const float4 v0 = piece(p0), v1 = piece(p0 + 1), v2 = piece(p0 + 2);
+            add(v0); add(v1); add(v2);
+        } else if (n == 2) {
+            const float4 v0 = piece(p0), v1 = piece(p0 + 1);
+            add(v0); add(v1);
+        } else {
+            add(piece(p0));
+        }
     }
     reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)tile_token(a, it, ti) * a.v_stride)[j4] = sum;
 }
