@@ -473,25 +473,29 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     }
 }
 
-// Blocks -> (tile, column run).  With few tiles (runs_fast): block b works on column run b % runs_padded of tile
-// b / runs_padded, runs_padded a multiple of 8 (or a power of two below 8): block b runs on XCD b % 8, so a column
-// run -- the same columns of every tile -- always falls on the same XCD (or the same 8 / runs_padded of them) and a
-// prompt's Bp is fetched from memory by one XCD per column run instead of by all eight (with the tiles as the fast
-// index the prefill expand fetched 147 MB for 101 MB; -6 % time on the prefill and stress configurations).  With
-// many tiles the tiles are the fast index: there the other order measured 4 % slower (mixed configuration).
+// Blocks -> (tile, column run).  Block b runs on XCD b % 8; the blocks are numbered so that a column run -- the same
+// columns of every tile -- always falls on the same XCD (or the same two or four), and a prompt's Bp is fetched
+// from memory by one XCD per column run instead of by all eight (with the tiles as the fast index the prefill
+// expand fetched 147 MB for 101 MB).  The column runs go in groups of eight: within a group block
+// (tile * 8 + run % 8) works on that tile and run; what is left over after the whole groups forms a last group of
+// 1, 2, 4 or 8 runs (the next power of two: at most a twelfth of a launch's blocks are padding, which return at once --
+// padding every launch to a multiple of 8 runs cost the two 11-run launches of the mixed configuration 29 us each).
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void mfma_expand_kernel(ApplyArgs a, const DevItem *__restrict__ tiles, int n_tiles,
-                                                                                                        int n_pass, int n_runs, int runs_padded)
+                                                                                                        int n_pass, int n_runs, int last_width)
 {
     __shared__ __attribute__((aligned(16))) unsigned char vs[LORA_TILE_TOKENS * VS_ROW];
     __shared__ __attribute__((aligned(16))) unsigned char cs[4][32 * CS_ROW];
+    const int whole = (n_runs >> 3) * n_tiles * 8;  // blocks of the groups of eight
     int tile, col_run;
-    if (runs_padded > 0) {
-        tile = (int)blockIdx.x / runs_padded;
-        col_run = (int)blockIdx.x - tile * runs_padded;
-        if (col_run >= n_runs) return;  // padding
+    if ((int)blockIdx.x < whole) {
+        const int grp = (int)blockIdx.x / (n_tiles * 8), r = (int)blockIdx.x - grp * n_tiles * 8;
+        tile = r >> 3;
+        col_run = 8 * grp + (r & 7);
     } else {
-        col_run = (int)blockIdx.x / n_tiles;
-        tile = (int)blockIdx.x - col_run * n_tiles;
+        const int r = (int)blockIdx.x - whole;
+        tile = r / last_width;
+        col_run = (n_runs & ~7) + (r - tile * last_width);
+        if (col_run >= n_runs) return;  // padding
     }
     const DevItem it = tiles[tile];
     switch ((it.rank + 31) >> 5) {
@@ -523,15 +527,13 @@ hipError_t launch_mfma_expand(const ApplyArgs &a, const DevItem *tiles, int n_ti
     int cols = 1024;
     while (cols > 256 && (int64_t)n_tiles * ((a.h_out + cols - 1) / cols) < 512) cols >>= 1;
     const int n_runs = (a.h_out + cols - 1) / cols;
-    int runs_padded = 0;  // 0: tiles are the fast index
-    if (n_tiles <= 256) {
-        runs_padded = 1;
-        if (n_runs >= 8) runs_padded = (n_runs + 7) / 8 * 8;
-        else
-            while (runs_padded < n_runs) runs_padded <<= 1;
+    int last_width = 0;  // of the last, partial group of column runs: the next power of two
+    if (n_runs & 7) {
+        last_width = 1;
+        while (last_width < (n_runs & 7)) last_width <<= 1;
     }
-    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles * (runs_padded ? runs_padded : n_runs)), dim3(256), st, a, tiles,
-             n_tiles, cols / 128, n_runs, runs_padded);
+    launch_k(tm, LORA_K_MFMA_EXPAND, mfma_expand_kernel, dim3(n_tiles * ((n_runs & ~7) + last_width)), dim3(256), st, a, tiles, n_tiles,
+             cols / 128, n_runs, last_width);
     return hipGetLastError();
 }
 
