@@ -717,6 +717,7 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[workload], "tokens": inst.T, "segments": inst.n_seg, "projections": n_proj,
                    "pool_adapters": int(inst.n_adapters), "distinct_adapters": int(len(inst.used_adapters())), "layers_per_step": n_layers, "activation_sets": n_sets,
+                   "library_limits": "h_in and h_out multiples of 64, rank 1..128",
                    "ms_per_layer": ms_per_layer, "us_per_layer_spread": spread, "cold_single_call_us": cold_call_us,
                    "host_index_us": index_us, "host_plan_create_us": plan_us, "graph_replay": graph_replay,
                    "mfma_min_tokens": plan_info.mfma_min_tokens, "tiles": len(w["tiles"]), "gemv_shrink_items": plan_info.n_gemv_shrink_items, "gemv_groups": len(w["groups"])},
