@@ -326,7 +326,7 @@ int lora_apply_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t proj
 /* lora_apply_plan for callers that cannot allocate device memory or hand any over for scratch: code
  * whose memory is fixed before it starts (a serving loop with a frozen memory plan, a harness that
  * forbids allocation, work recorded for later replay).  Same arguments, same result, same kernels;
- * the intermediate buffers (shrink results, k-split partial sums, hand-over words) do not come from
+ * the intermediate buffers (shrink results, the tile shrink's partial sums, hand-over words) do not come from
  * the cache's pool but from a fixed array of LORA_STATIC_SCRATCH_BYTES (14 MiB) in the library's
  * device image, which every device the library has run on holds until the process ends.  The call
  * allocates nothing and frees nothing, on the device or through the runtime.

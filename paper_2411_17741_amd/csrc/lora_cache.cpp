@@ -41,7 +41,7 @@ constexpr int N_VSETS = lora::MAX_SHRINK_PROJS;  // applies that share their inp
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
 
 // Device memory an apply needs beside its inputs and outputs: the shrink results (one set per
-// projection of a group), the partial sums of a k-split tile shrink, and the tagged words through
+// projection of a group), the partial sums that the runs of the tile shrink leave, and the tagged words through
 // which the one-launch GEMV form hands its intermediate over.
 struct Scratch {
     char *v;
@@ -1874,7 +1874,7 @@ int lora_linear_plan(lora_cache_t *c, lora_plan_t *p, int32_t layer, int32_t pro
     // base product of every token + adapter product of the tiles (+ the term just computed for the others)
     lora::ApplyArgs lin = a;
     lin.tok_list = reinterpret_cast<const int32_t *>(p->dev + p->off_lin_tok);
-    // (the partial sums of split tiles go where the tile shrink's k-split partials went: that kernel is done)
+    // (the partial sums of split tiles go where the tile shrink's partial sums went: that kernel is done)
     HIP_TRY(lora::launch_linear_tiles(lin, Wt, reinterpret_cast<const lora::DevItem *>(p->dev + p->off_lin_tiles), p->n_lin_tiles,
                                       c->pool + c->off_vpart, c->vpart_bytes, reinterpret_cast<uint32_t *>(c->pool + c->off_fault),
                                       N_LINEAR_FLAGS, c->fault_dev, c->n_cu, st, tm));

@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                           ShrinkProjs ps)
 {
     __shared__ __attribute__((aligned(16))) unsigned char xs[NSTAGE][LORA_TILE_TOKENS * XROW];
-    static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the k-split reduction reuses the x ring");
+    static_assert(sizeof(xs) >= 4 * 4 * 3 * 4 * 64 * 4, "the sum over the wavefronts' k parts reuses the x ring");
 
     // XCD j = blockIdx % 8 works on the runs [j * runs_per_xcd, (j + 1) * runs_per_xcd); its i-th block on
     // (run, projection) number i, projection innermost: the blocks that read the same part of x for the
