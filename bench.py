@@ -468,7 +468,7 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
     else:
         inst = wl.CONFIGS[workload](seed=0)
     t_setup = time.time()
-    pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv] | (B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0))
+    pi = H.PooledInstance(inst, n_layers=n_layers, mfma_min_tokens=args.mfma_min_tokens, flags={"auto": 0, "fused": B.LORA_CACHE_FUSED_GEMV, "split": B.LORA_CACHE_SPLIT_GEMV}[args.gemv] | (B.LORA_CACHE_DIRECT_FILL if args.direct_fill else 0) | (B.LORA_CACHE_NO_OVERLAP if args.no_overlap else 0))
     h = pi.pool.handle
     dev = torch.device("cuda:0")
 
@@ -765,6 +765,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the graph-replay timing of the step")
+    ap.add_argument("--no-overlap", action="store_true", help="the GEMV launch of an apply behind its tile kernels instead of beside them (LORA_CACHE_NO_OVERLAP): "
+                    "per-kernel durations of a trace then stand for the kernels alone")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1\n")

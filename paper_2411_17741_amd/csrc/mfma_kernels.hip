@@ -64,6 +64,21 @@ __device__ __forceinline__ int tile_token(const ApplyArgs &a, const DevItem &it,
     return tile_token_of(a.tok_list, it, ti);
 }
 
+// token ids of N rows of a tile at once (rows past the tile's last count as its last): one round of lookups,
+// or none for a tile of consecutive tokens.  A conditional lookup per row is a branch per row, and after each
+// the compiler waits for everything outstanding, the loads requested before it included.
+template <int N>
+__device__ __forceinline__ void tile_tokens(const ApplyArgs &a, const DevItem &it, const int (&ti)[N], int (&tok)[N])
+{
+    if (it.consecutive) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) tok[i] = it.tok0 + min(ti[i], it.n_tok - 1);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) tok[i] = a.tok_list[it.tok_off + min(ti[i], it.n_tok - 1)];
+    }
+}
+
 template <bool NSPLIT, int NBW>  // NBW: rank blocks (of 16) a wavefront works on
 __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevItem &it, int k_begin, int k_end, int phase,
                                                  float *part, unsigned char (*xs)[LORA_TILE_TOKENS * XROW])
@@ -94,13 +109,17 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
     const __bf16 *xg[4];
     int lds_off[4];
     bool x_ok[4];
+    {
+        int row[4], tok[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 16 * w + 4 * i + (lane >> 4);
-        x_ok[i] = row < it.n_tok;
-        const int tok = x_ok[i] ? tile_token(a, it, row) : it.tok0;
-        xg[i] = x + (size_t)tok * a.h_in;
-        lds_off[i] = row * XROW + lp * 16;
+        for (int i = 0; i < 4; ++i) row[i] = 16 * w + 4 * i + (lane >> 4);
+        tile_tokens(a, it, row, tok);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x_ok[i] = row[i] < it.n_tok;
+            xg[i] = x + (size_t)tok[i] * a.h_in;
+            lds_off[i] = row[i] * XROW + lp * 16;
+        }
     }
     // At operands: block slot q -> rank block nbq; rows past the stored rank are clamped (their
     // results are never written)
@@ -188,32 +207,53 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
         load_x(st + 3, xr[CUR ^ 1]);
         __syncthreads();
     };
-    for (int st = 0; st < n_st; st += 6) {
+    // (the walk leaves through a break after its last stage: with every stage under a condition of its own a
+    // stage can be reached past a skipped one as far as the compiler can tell, the load counts it merges at
+    // such a join are the smallest of both ways, and every wait for x then also waited for the requests of
+    // the stage before -- the two-stage lead of x was one)
+    for (int st = 0;; st += 6) {
         stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, st);
-        if (st + 1 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, st + 1);
-        if (st + 2 < n_st) stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{}, st + 2);
-        if (st + 3 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, st + 3);
-        if (st + 4 < n_st) stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, st + 4);
-        if (st + 5 < n_st) stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, st + 5);
+        if (st + 1 >= n_st) break;
+        stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, st + 1);
+        if (st + 2 >= n_st) break;
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{}, st + 2);
+        if (st + 3 >= n_st) break;
+        stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, st + 3);
+        if (st + 4 >= n_st) break;
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, st + 4);
+        if (st + 5 >= n_st) break;
+        stage(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, st + 5);
+        if (st + 6 >= n_st) break;
     }
 
-    auto write_v = [&](int mb, int q, const floatx4 &val) {
+    // Where the rows go.  The tile's whole k range: the result itself, into the rows of v that belong to the
+    // tile's tokens; else this piece's partial sum, one row per row of the tile (mfma_reduce_kernel adds the
+    // pieces up).  The row numbers are all fetched before the first store: a lookup between two stores makes
+    // the second wait for the first to be acknowledged (loads and stores share the counter, which can only
+    // be waited down), 0.3 us each -- 10 us for the 32 stores of a rank-128 piece
+    float *const out = part ? part : a.v;
+    auto rows_of = [&](int mb, int (&rows)[4]) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rows[r] = 16 * mb + 4 * g + r;
+        if (part) return;
+        const int ti[4] = {rows[0], rows[1], rows[2], rows[3]};
+        tile_tokens(a, it, ti, rows);
+    };
+    auto write_v = [&](int mb, const int (&rows)[4], int q, const floatx4 &val) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int ti = 16 * mb + 4 * g + r, jr = 16 * nbq[q] + m;
-            if (ti < it.n_tok && jr < it.rank) {
-                // the tile's whole k range: the result itself; else this piece's partial sum, one row per row
-                // of the tile (mfma_reduce_kernel adds the pieces up)
-                if (part) part[(size_t)ti * a.v_stride + jr] = val[r];
-                else a.v[(size_t)tile_token(a, it, ti) * a.v_stride + jr] = val[r];
-            }
+            if (ti < it.n_tok && jr < it.rank) out[(size_t)rows[r] * a.v_stride + jr] = val[r];
         }
     };
     if (NSPLIT) {
+        int rows[4][4];
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) rows_of(mb, rows[mb]);
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int q = 0; q < NBW; ++q) write_v(mb, q, acc[mb][q]);
+            for (int q = 0; q < NBW; ++q) write_v(mb, rows[mb], q, acc[mb][q]);
     } else {
         // the four wavefronts hold partial sums over k: park them in the (now idle) x ring and let
         // wavefront w add up and write token block w
@@ -224,6 +264,8 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
             for (int q = 0; q < NBW; ++q)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) red[(((w * 4 + mb) * NBW + q) * 4 + r) * 64 + lane] = acc[mb][q][r];
+        int rows[4];
+        rows_of(w, rows);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < NBW; ++q) {
@@ -232,7 +274,7 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
             for (int src = 0; src < 4; ++src)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sum[r] += red[(((src * 4 + w) * NBW + q) * 4 + r) * 64 + lane];
-            write_v(w, q, sum);
+            write_v(w, rows, q, sum);
         }
     }
 }
@@ -345,20 +387,28 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     const int m = lane & 15, g = lane >> 4;
     const int th = w & 1, ch = w >> 1;
     const int rs = rank_storage(it.rank), rs8 = rs >> 3;
-    constexpr int c8 = KS * 4;  // staged chunks (8 ranks) per token
     const float s = a.scale * it.alpha;
     const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
 
     // read-modify-write layout: instruction i covers token rows 32*th + 8*i + lane/8, 8 columns at 8*(lane%8)
     const int rt = lane >> 3, rc = lane & 7;
+    // the token ids of the rows this thread updates and of the rows of V it stages, looked up together and
+    // before anything else is requested
+    constexpr int c8 = KS * 4;  // staged chunks (8 ranks) per token
+    static_assert(LORA_TILE_TOKENS * c8 == 256 * KS, "a thread stages KS pieces");
+    int rows[4 + KS], toks[4 + KS];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rows[i] = 32 * th + 8 * i + rt;
+#pragma unroll
+    for (int i = 0; i < KS; ++i) rows[4 + i] = (tid + 256 * i) / c8;
+    tile_tokens(a, it, rows, toks);
     size_t yoff[4];
     bool yok[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int ti = 32 * th + 8 * i + rt;
-        yok[i] = ti < it.n_tok;
-        yoff[i] = (size_t)(yok[i] ? tile_token(a, it, ti) : it.tok0) * a.h_out + rc * 8;
+        yok[i] = rows[i] < it.n_tok;
+        yoff[i] = (size_t)toks[i] * a.h_out + rc * 8;
     }
     const bool half_live = 32 * th < it.n_tok;
     const int col0 = col_run * n_pass * 128 + 64 * ch;
@@ -382,26 +432,28 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
 
     uint4 yr[2][4];
     uint4 br[KS][4];
-    load_y(0, yr[0]);  // the first pass's base_out and Bp are on their way while V is staged
-    load_b(min(col0, a.h_out - 64), br);
 
     // stage s.V as bf16: vs[token][rank].  A thread's KS pieces (8 ranks of one token each) are all requested before
     // the first is converted: taken one after the other, each with its own trip to memory, the staging took 4.6 us
-    // (rank 16) to 8.2 us (rank 128) of a block's 17 to 21 us on the prefill configuration.
+    // (rank 16) to 8.2 us (rank 128) of a block's 17 to 21 us on the prefill configuration.  V is requested first
+    // and the first pass's base_out and Bp behind it (loads complete in the order of their requests): those are
+    // on their way while V is staged.
     {
-        static_assert(LORA_TILE_TOKENS * c8 == 256 * KS, "a thread stages KS pieces");
         const float4 *vr[KS];
         bool ok[KS];
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
             const int idx = tid + 256 * i, ti = idx / c8, j8 = idx - ti * c8;
             ok[i] = ti < it.n_tok;
-            vr[i] = reinterpret_cast<const float4 *>(a.v + (size_t)(ok[i] ? tile_token(a, it, ti) : it.tok0) * a.v_stride + j8 * 8);
+            vr[i] = reinterpret_cast<const float4 *>(a.v + (size_t)toks[4 + i] * a.v_stride + j8 * 8);
         }
         float4 lo[KS], hi[KS];
 #pragma unroll
         for (int i = 0; i < KS; ++i) lo[i] = vr[i][0], hi[i] = vr[i][1];
         __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from trading loads in flight for registers
+        load_y(0, yr[0]);
+        load_b(min(col0, a.h_out - 64), br);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
             const int idx = tid + 256 * i, ti = idx / c8, j8 = idx - ti * c8;
