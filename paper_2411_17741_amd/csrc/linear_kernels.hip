@@ -54,10 +54,6 @@ constexpr int SV_ROW = LORA_MAX_RANK * 2 + 16;  // bytes per row of the staged s
 static_assert(8 * 128 * 128 <= 2 * L_STAGE && LBM * SV_ROW <= 2 * L_STAGE, "s.v is staged in the stage buffers");
 }  // namespace
 
-__device__ __forceinline__ int row_tile_token(const int32_t *tok_list, const DevItem &it, int ti)
-{
-    return tile_token_of(tok_list, it, ti);
-}
 
 // split of the last round: blocks [0, n_whole) work on whole tiles; block n_whole + S * j + p on part p of tile n_whole + j
 struct LinearSplit {
@@ -113,12 +109,13 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
     const int lr = lane >> 3, ls = lane & 7;
     const int piece_even = ls ^ ((lane >> 4) & 7), piece_odd = ls ^ (((lane >> 4) + 4) & 7);  // (row/2)%8 for q even / odd
     const __bf16 *xg[4];
+    {
+        int ti[4], tok[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const DevItem &t = tile_of_wave;
-        const int ti = 32 * (w & 1) + 8 * q + lr;
-        const int tok = ti < t.n_tok ? row_tile_token(a.tok_list, t, ti) : dead_tok;
-        xg[q] = x + (size_t)tok * a.h_in + ((q & 1) ? piece_odd : piece_even) * 8;
+        for (int q = 0; q < 4; ++q) ti[q] = 32 * (w & 1) + 8 * q + lr;
+        tile_tokens_of(a.tok_list, tile_of_wave, ti, dead_tok, tok);  // (rows past the tile's end repeat its last)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xg[q] = x + (size_t)tok[q] * a.h_in + ((q & 1) ? piece_odd : piece_even) * 8;
     }
     // Wt rows n0 + 32w + 8q + lr; h_out is a multiple of 64, so a run of 32 rows is inside or outside as a whole
     const int w_row0 = min(n0 + 32 * w, a.h_out - 32);
@@ -257,27 +254,33 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
     // s.v of the block's rows to LDS as bf16 (zero past a tile's rank or end)
     unsigned char *sv = lds;
     {
-        // chunk tid%16 (8 ranks) of rows tid/16 + 32*j: row tile j/2, row (tid/16 + 32*(j%2)) of it
+        // chunk tid%16 (8 ranks) of rows tid/16 and tid/16 + 32 of each row tile that has an adapter: per tile the
+        // two token ids in one round, then both rows' pieces in one round (unconditional, from addresses inside v)
         const int c8 = tid & 15, r0 = tid >> 4;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const DevItem &t = tile_of(j >> 1);
-            const int ti = r0 + 32 * (j & 1);
-            const int ks32 = (t.rank + 31) >> 5;  // k steps this tile's products will read
-            if (c8 < 4 * ks32) {
-                bf16x8 o;
+        for (int jj = 0; jj < 4; ++jj) {
+            const DevItem &t = tile_of(jj);
+            if (t.rank == 0 || t.n_tok == 0) continue;  // uniform over the block; nothing of such a tile is read below
+            const int ks32 = (t.rank + 31) >> 5;        // k steps this tile's products will read
+            const float s = a.scale * t.alpha;
+            const int ti[2] = {r0, r0 + 32};
+            int tok[2];
+            tile_tokens_of(a.tok_list, t, ti, dead_tok, tok);
+            float4 lo[2], hi[2];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
-                if (ti < t.n_tok && c8 * 8 < t.rank) {
-                    const float s = a.scale * t.alpha;
-                    const float4 *vr = reinterpret_cast<const float4 *>(
-                        a.v + (size_t)row_tile_token(a.tok_list, t, ti) * a.v_stride + c8 * 8);
-                    const float4 lo = vr[0], hi = vr[1];
-                    const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            for (int h = 0; h < 2; ++h) {
+                const float4 *vr = reinterpret_cast<const float4 *>(a.v + (size_t)tok[h] * a.v_stride + c8 * 8);
+                lo[h] = vr[0], hi[h] = vr[1];
+            }
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)(c8 * 8 + e < t.rank ? s * f[e] : 0.f);
+            for (int h = 0; h < 2; ++h) {
+                if (c8 < 4 * ks32) {
+                    const float f[8] = {lo[h].x, lo[h].y, lo[h].z, lo[h].w, hi[h].x, hi[h].y, hi[h].z, hi[h].w};
+                    bf16x8 o;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)((ti[h] < t.n_tok && c8 * 8 + e < t.rank) ? s * f[e] : 0.f);
+                    *reinterpret_cast<bf16x8 *>(sv + (64 * jj + ti[h]) * SV_ROW + c8 * 16) = o;
                 }
-                *reinterpret_cast<bf16x8 *>(sv + (64 * (j >> 1) + ti) * SV_ROW + c8 * 16) = o;
             }
         }
     }
@@ -321,36 +324,52 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         const DevItem &t = tl ? mine1 : mine0;
         if (t.n_tok == 0 || !cols_live) continue;  // wavefront-uniform
         const bool add_y = t.rank == 0 && t.a == 1;
+        if (add_y) {
+            // rows whose adapter term is already in y (or, as fp32, at the same place of the workspace): the four
+            // token ids in one round, then per row block the four old values in one round and the four stores
+            int ti4[4], tok4[4];
+#pragma unroll
+            for (int mbl = 0; mbl < 4; ++mbl) ti4[mbl] = 16 * mbl + m;
+            tile_tokens_of(a.tok_list, t, ti4, dead_tok, tok4);
+#pragma unroll
+            for (int mbl = 0; mbl < 4; ++mbl) {
+                if (ti4[mbl] >= t.n_tok) continue;
+                __bf16 *yr = y + (size_t)tok4[mbl] * a.h_out + n0 + 64 * cq + 4 * g;
+                floatx4 term[4];
+                if (a.y32) {
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) term[nb] = *reinterpret_cast<const floatx4 *>(a.y32 + (yr - y) + 16 * nb);
+                } else {
+                    bf16x4 old[4];
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) old[nb] = *reinterpret_cast<const bf16x4 *>(yr + 16 * nb);
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) term[nb][e] = (float)old[nb][e];
+                }
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const floatx4 c = acc[4 * tl + mbl][nb];
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + term[nb][e]);
+                    *reinterpret_cast<bf16x4 *>(yr + 16 * nb) = o;
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int mbl = 0; mbl < 4; ++mbl) {
             const int ti = 16 * mbl + m, row = 64 * tl + ti;
-            __bf16 *yr = nullptr;
-            if (add_y && ti < t.n_tok) yr = y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 4 * g;
             unsigned char *pr = park + row * 128;
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
                 const floatx4 c = acc[4 * tl + mbl][nb];
-                if (add_y) {
-                    if (yr) {
-                        bf16x4 *dst = reinterpret_cast<bf16x4 *>(yr + 16 * nb);
-                        bf16x4 o;
-                        if (a.y32) {  // the rows' adapter term as fp32, same place in the workspace as in y
-                            const floatx4 t32 = *reinterpret_cast<const floatx4 *>(a.y32 + (yr - y) + 16 * nb);
+                bf16x4 o;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + t32[e]);
-                        } else {
-                            const bf16x4 old = *dst;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(c[e] + (float)old[e]);
-                        }
-                        *dst = o;
-                    }
-                } else {
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)c[e];
-                    *reinterpret_cast<bf16x4 *>(pr + (((4 * nb + g) ^ (((row >> 1) & 7) << 1)) << 3)) = o;
-                }
+                for (int e = 0; e < 4; ++e) o[e] = (__bf16)c[e];
+                *reinterpret_cast<bf16x4 *>(pr + (((4 * nb + g) ^ (((row >> 1) & 7) << 1)) << 3)) = o;
             }
         }
     }
@@ -361,12 +380,16 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
         const DevItem &t = tl ? mine1 : mine0;
         if (t.n_tok == 0 || !cols_live || (t.rank == 0 && t.a == 1)) continue;  // wavefront-uniform
         const int rl = lane >> 3, sl = lane & 7;
+        int ti8[8], tok8[8];  // the rows' token ids all before the first store (a lookup between two stores makes the second wait for the first)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ti8[i] = 8 * i + rl;
+        tile_tokens_of(a.tok_list, t, ti8, dead_tok, tok8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int ti = 8 * i + rl, row = 64 * tl + ti;
-            if (ti < t.n_tok) {
+            const int row = 64 * tl + ti8[i];
+            if (ti8[i] < t.n_tok) {
                 const uint4 v = *reinterpret_cast<const uint4 *>(park + row * 128 + ((sl ^ ((row >> 1) & 7)) << 4));
-                *reinterpret_cast<uint4 *>(y + (size_t)row_tile_token(a.tok_list, t, ti) * a.h_out + n0 + 64 * cq + 8 * sl) = v;
+                *reinterpret_cast<uint4 *>(y + (size_t)tok8[i] * a.h_out + n0 + 64 * cq + 8 * sl) = v;
             }
         }
     }

@@ -37,6 +37,25 @@ inline __host__ __device__ int32_t tile_token_of(const int32_t *tok_list, const 
     return (it.consecutive || ti == 0) ? it.tok0 + ti : tok_list[it.tok_off + ti];
 }
 
+// Token ids of N rows of a tile in one round of lookups (none for a tile of consecutive tokens).  Rows past the
+// tile's last count as its last, the rows of an empty tile as token `dead`.  (A conditional lookup per row is a
+// branch per row in a kernel, and after each the compiler waits for every load and store still outstanding.)
+template <int N>
+inline __host__ __device__ void tile_tokens_of(const int32_t *tok_list, const DevItem &it, const int (&ti)[N], int32_t dead,
+                                               int (&tok)[N])
+{
+    if (it.n_tok <= 0) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) tok[i] = dead;
+    } else if (it.consecutive) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) tok[i] = it.tok0 + (ti[i] < it.n_tok ? ti[i] : it.n_tok - 1);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) tok[i] = tok_list[it.tok_off + (ti[i] < it.n_tok ? ti[i] : it.n_tok - 1)];
+    }
+}
+
 // GEMV work item: a batch of up to GEMV_BATCH tokens of one slot, named directly so that the kernels
 // reach their data with one lookup.  A shrink item stands for GEMV_SHRINK_ROWS stored rank rows from
 // `a` on (stored rows past the rank hold zeros, so an item is always whole); an expand item for one

@@ -64,19 +64,11 @@ __device__ __forceinline__ int tile_token(const ApplyArgs &a, const DevItem &it,
     return tile_token_of(a.tok_list, it, ti);
 }
 
-// token ids of N rows of a tile at once (rows past the tile's last count as its last): one round of lookups,
-// or none for a tile of consecutive tokens.  A conditional lookup per row is a branch per row, and after each
-// the compiler waits for everything outstanding, the loads requested before it included.
+// token ids of N rows of a tile at once (rows past the tile's last count as its last)
 template <int N>
 __device__ __forceinline__ void tile_tokens(const ApplyArgs &a, const DevItem &it, const int (&ti)[N], int (&tok)[N])
 {
-    if (it.consecutive) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) tok[i] = it.tok0 + min(ti[i], it.n_tok - 1);
-    } else {
-#pragma unroll
-        for (int i = 0; i < N; ++i) tok[i] = a.tok_list[it.tok_off + min(ti[i], it.n_tok - 1)];
-    }
+    tile_tokens_of(a.tok_list, it, ti, it.tok0, tok);
 }
 
 template <bool NSPLIT, int NBW>  // NBW: rank blocks (of 16) a wavefront works on
