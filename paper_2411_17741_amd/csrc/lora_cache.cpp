@@ -471,10 +471,11 @@ bool shrink_pieces_of(const lora::DevItem *tiles, int n_tiles, int quanta, Shrin
 }
 // Runs of about equal cost, at most max_runs of them (a multiple of 8).  A piece costs its parts times its tile's
 // weight, plus a fixed amount.  Measured with every block of a launch resident from the start (two per compute unit):
-// a block spends about 7 us beside its k loop (the item, the first loads, the write of the result); a stage of 128 k
-// takes it 1.75 us at rank 16, 2.1 us at rank 32, 2.3 us at rank 64 and 3.0 to 3.3 us at rank 128 when the launch is
-// long (x arrives at the rate the memory gives, the higher ranks add their At loads and products), and 1.0 against 2.4 us
-// at ranks 16 and 128 when it is short.  For a cost limit the sequence is walked once, every run taking pieces until
+// a block spends about 6.5 us beside its k loop (the item, the first three stages of loads that every block requests at
+// once, the write of the result); a stage of 128 k takes it 1.4 us at rank 16, 1.6 us at rank 32, 1.9 us at rank 64 and
+// 2.6 us at rank 128 when the launch is long (x arrives at the rate the memory gives, the higher ranks add their At
+// loads).  The result is flat around these weights: a fixed amount of 3 to 6 stages and a stage offset of 30 to 60
+// gave the same launch times to within 1 %.  For a cost limit the sequence is walked once, every run taking pieces until
 // the limit is reached; the smallest limit that needs no more than max_runs runs is found by bisection.
 void build_shrink_runs(const lora::DevItem *tiles, int n_tiles, int quanta, int max_runs, ShrinkRuns &out)
 {
