@@ -318,10 +318,9 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkPro
     // float4 column of one token
     const int tile = blockIdx.x >> 3;
     const ShrinkSum sm = ps.sums[tile];
-    if (sm.n_pieces < 2) return;
-    const DevItem it = tiles[tile];
+    const DevItem it = tiles[tile];  // (requested together with sm: one trip to memory, not two)
     const int ti = (blockIdx.x & 7) * 8 + (threadIdx.x >> 5), j4 = threadIdx.x & 31;
-    if (ti >= it.n_tok || j4 * 4 >= rank_storage(it.rank)) return;  // entries past the rank are never used
+    if ((sm.n_pieces < 2) | (ti >= it.n_tok) | (j4 * 4 >= rank_storage(it.rank))) return;  // entries past the rank are never used
     const size_t slot_f4 = (size_t)SHRINK_SLOT_ROWS * (a.v_stride >> 2);
     const float4 *src = reinterpret_cast<const float4 *>(ps.part[blockIdx.y]) + (size_t)ti * (a.v_stride >> 2) + j4;
     // four pieces at a time: their loads are issued together (one after the other, a tile in seven pieces took
