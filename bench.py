@@ -606,10 +606,10 @@ def run_workload(args, workload: str, steps: int = 0, cpu_baseline: bool = True,
     kernels = {}
     if not args.no_kernel_timing:
         # second pass over the same steps with an event pair around every kernel.  The host-side measurements above
-        # left the GPU idle (its first work after that runs slower): a quarter of a second of untimed steps first, then
+        # left the GPU idle (its first work after that runs slower): a second of untimed steps first, then
         # the steps once with the event pairs on and unread, so that the pool of events has its size
         t_pre = time.perf_counter()
-        while time.perf_counter() - t_pre < min(0.25, args.prewarm_s):
+        while time.perf_counter() - t_pre < min(1.0, args.prewarm_s):
             for s in range(4):
                 step(s)
             torch.cuda.synchronize()
