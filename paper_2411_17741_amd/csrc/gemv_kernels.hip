@@ -96,10 +96,14 @@ __device__ __forceinline__ bool fetch_words(const GemvArgs &a, const unsigned lo
         for (int t = 0; t < TB; ++t) out[t] = (uint32_t)__hip_atomic_load(p[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }
+    // Polls travel the same way as the slabs, past the caches: only the words that are waited for are asked for (the
+    // batch's own tokens -- nt is the same for the wavefront -- and the lanes below the stored rank), and a failed
+    // poll is followed by a short sleep.  (With all four token slots and all 64 lanes polled back to back the decode
+    // layer took 10.4 us instead of 9.65.)
     for (int spin = 0; spin < WAIT_SPINS; ++spin) {
         unsigned long long w[TB];
 #pragma unroll
-        for (int t = 0; t < TB; ++t) w[t] = __hip_atomic_load(p[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int t = 0; t < TB; ++t) w[t] = (t < nt && need) ? __hip_atomic_load(p[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
         bool ok = true;
 #pragma unroll
         for (int t = 0; t < TB; ++t) ok = ok && (!need || t >= nt || (uint32_t)(w[t] >> 32) == a.epoch);
@@ -108,7 +112,7 @@ __device__ __forceinline__ bool fetch_words(const GemvArgs &a, const unsigned lo
             for (int t = 0; t < TB; ++t) out[t] = (uint32_t)w[t];
             return true;
         }
-        if (spin >= 4) __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(8);
     }
     if ((threadIdx.x & 63) == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // pinned host memory
     return false;
