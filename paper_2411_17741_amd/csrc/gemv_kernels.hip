@@ -100,6 +100,9 @@ __device__ __forceinline__ bool fetch_words(const GemvArgs &a, const unsigned lo
     // batch's own tokens -- nt is the same for the wavefront -- and the lanes below the stored rank), and a failed
     // poll is followed by a short sleep.  (With all four token slots and all 64 lanes polled back to back the decode
     // layer took 10.4 us instead of 9.65.)
+    // The first poll goes out when the loads requested before it (the unit's Bp and base_out) are in: its answer would
+    // come back behind them anyway, and asked for earlier it is nearly always a miss (decode layer 9.6 -> 9.45 us).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     for (int spin = 0; spin < WAIT_SPINS; ++spin) {
         unsigned long long w[TB];
 #pragma unroll
