@@ -262,23 +262,20 @@ __global__ __launch_bounds__(512) void linear_tiles_kernel(ApplyArgs a, const __
             const DevItem &t = tile_of(jj);
             if (t.rank == 0 || t.n_tok == 0) continue;  // uniform over the block; nothing of such a tile is read below
             const int ks32 = (t.rank + 31) >> 5;        // k steps this tile's products will read
-            const float s = a.scale * t.alpha;
             const int ti[2] = {r0, r0 + 32};
             int tok[2];
             tile_tokens_of(a.tok_list, t, ti, dead_tok, tok);
-            float4 lo[2], hi[2];
+            uint4 pc[2];  // s.v comes as bf16 from the shrink or the reduce (rows of the fp32 pitch)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float4 *vr = reinterpret_cast<const float4 *>(a.v + (size_t)tok[h] * a.v_stride + c8 * 8);
-                lo[h] = vr[0], hi[h] = vr[1];
-            }
+            for (int h = 0; h < 2; ++h)
+                pc[h] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const __bf16 *>(a.v) + (size_t)tok[h] * (2 * a.v_stride) + c8 * 8);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if (c8 < 4 * ks32) {
-                    const float f[8] = {lo[h].x, lo[h].y, lo[h].z, lo[h].w, hi[h].x, hi[h].y, hi[h].z, hi[h].w};
+                    const bf16x8 f = __builtin_bit_cast(bf16x8, pc[h]);
                     bf16x8 o;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)((ti[h] < t.n_tok && c8 * 8 + e < t.rank) ? s * f[e] : 0.f);
+                    for (int e = 0; e < 8; ++e) o[e] = (ti[h] < t.n_tok && c8 * 8 + e < t.rank) ? f[e] : (__bf16)0.f;
                     *reinterpret_cast<bf16x8 *>(sv + (64 * jj + ti[h]) * SV_ROW + c8 * 16) = o;
                 }
             }

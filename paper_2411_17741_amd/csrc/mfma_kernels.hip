@@ -231,11 +231,17 @@ __device__ __forceinline__ void mfma_shrink_body(const ApplyArgs &a, const DevIt
         const int ti[4] = {rows[0], rows[1], rows[2], rows[3]};
         tile_tokens(a, it, ti, rows);
     };
+    // (a whole tile's result goes out as the expand takes it: scaled and rounded to bf16, rows of the same pitch)
+    const float s_v = a.scale * it.alpha;
+    __bf16 *const out16 = reinterpret_cast<__bf16 *>(a.v);
     auto write_v = [&](int mb, const int (&rows)[4], int q, const floatx4 &val) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int ti = 16 * mb + 4 * g + r, jr = 16 * nbq[q] + m;
-            if (ti < it.n_tok && jr < it.rank) out[(size_t)rows[r] * a.v_stride + jr] = val[r];
+            if (ti < it.n_tok && jr < it.rank) {
+                if (part) out[(size_t)rows[r] * a.v_stride + jr] = val[r];
+                else out16[(size_t)rows[r] * (2 * a.v_stride) + jr] = (__bf16)(s_v * val[r]);
+            }
         }
     };
     if (NSPLIT) {
@@ -346,7 +352,12 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(ApplyArgs a, ShrinkPro
             add(piece(p0));
         }
     }
-    reinterpret_cast<float4 *>(ps.v[blockIdx.y] + (size_t)tile_token(a, it, ti) * a.v_stride)[j4] = sum;
+    // the sum goes out as the expand takes it: scaled and rounded to bf16 (rows of the same pitch as the fp32 ones)
+    const float s_v = a.scale * it.alpha;
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16x4_t o;
+    o[0] = (__bf16)(s_v * sum.x), o[1] = (__bf16)(s_v * sum.y), o[2] = (__bf16)(s_v * sum.z), o[3] = (__bf16)(s_v * sum.w);
+    reinterpret_cast<bf16x4_t *>(reinterpret_cast<__bf16 *>(ps.v[blockIdx.y]) + (size_t)tile_token(a, it, ti) * (2 * a.v_stride))[j4] = o;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -378,7 +389,6 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     const int m = lane & 15, g = lane >> 4;
     const int th = w & 1, ch = w >> 1;
     const int rs = rank_storage(it.rank), rs8 = rs >> 3;
-    const float s = a.scale * it.alpha;
     const __bf16 *Bp = reinterpret_cast<const __bf16 *>(a.proj_base + (int64_t)it.row * a.row_bytes) + (size_t)rs * a.h_in;
     __bf16 *y = static_cast<__bf16 *>(a.y);
 
@@ -431,23 +441,24 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
     uint4 yr[2][4];
     uint4 br[KS][4];
 
-    // stage s.V as bf16: vs[token][rank].  A thread's KS pieces (8 ranks of one token each) are all requested before
-    // the first is converted: taken one after the other, each with its own trip to memory, the staging took 4.6 us
-    // (rank 16) to 8.2 us (rank 128) of a block's 17 to 21 us on the prefill configuration.  V is requested first
+    // stage s.V (written as bf16 by the shrink or the reduce): vs[token][rank].  A thread's KS pieces (8 ranks of one
+    // token each) are all requested before the first is used: taken one after the other, each with its own trip to
+    // memory, the staging took 4.6 us (rank 16) to 8.2 us (rank 128) of a block's 17 to 21 us on the prefill
+    // configuration.  V is requested first
     // and the first pass's base_out and Bp behind it (loads complete in the order of their requests): those are
     // on their way while V is staged.
     {
-        const float4 *vr[KS];
+        const uint4 *vr[KS];
         bool ok[KS];
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
             const int idx = tid + 256 * i, ti = idx / c8, j8 = idx - ti * c8;
             ok[i] = ti < it.n_tok;
-            vr[i] = reinterpret_cast<const float4 *>(a.v + (size_t)toks[4 + i] * a.v_stride + j8 * 8);
+            vr[i] = reinterpret_cast<const uint4 *>(reinterpret_cast<const __bf16 *>(a.v) + (size_t)toks[4 + i] * (2 * a.v_stride) + j8 * 8);
         }
-        float4 lo[KS], hi[KS];
+        uint4 pc[KS];
 #pragma unroll
-        for (int i = 0; i < KS; ++i) lo[i] = vr[i][0], hi[i] = vr[i][1];
+        for (int i = 0; i < KS; ++i) pc[i] = vr[i][0];
         __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from trading loads in flight for registers
         load_y(0, yr[0]);
         load_b(min(col0, a.h_out - 64), br);
@@ -455,10 +466,10 @@ __device__ __forceinline__ void mfma_expand_body(const ApplyArgs &a, const DevIt
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
             const int idx = tid + 256 * i, ti = idx / c8, j8 = idx - ti * c8;
-            const float f[8] = {lo[i].x, lo[i].y, lo[i].z, lo[i].w, hi[i].x, hi[i].y, hi[i].z, hi[i].w};
+            const bf16x8 f = __builtin_bit_cast(bf16x8, pc[i]);
             bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)((ok[i] && j8 * 8 + e < it.rank) ? s * f[e] : 0.f);
+            for (int e = 0; e < 8; ++e) o[e] = (ok[i] && j8 * 8 + e < it.rank) ? f[e] : (__bf16)0.f;  // entries past the rank were never written
             *reinterpret_cast<bf16x8 *>(&vs[ti * VS_ROW + j8 * 16]) = o;
         }
     }
