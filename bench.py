@@ -40,10 +40,10 @@ WORKLOAD_TEXT = {
 # 256 MiB copy).  A counter run cannot happen inside this process, so the figures measured for the same workloads
 # are carried here; the line names their source, and they are left out when the flags change what is launched.
 TRAFFIC_SOURCE = "profiles/kernel_traffic_all_workloads.txt"
-MEASURED_TRAFFIC = {("decode", "gemv_fused"): 24.74e6, ("decode_qkv", "gemv_fused"): 71.79e6, ("prefill", "mfma_shrink"): 66.65e6,
-                    ("prefill", "mfma_expand"): 127.45e6, ("mixed", "mfma_expand"): 570.90e6, ("mixed", "mfma_shrink"): 405.54e6,
-                    ("mixed", "gemv_fused"): 177.94e6, ("stress", "gemv_fused"): 356.77e6, ("stress", "mfma_expand"): 106.63e6,
-                    ("stress", "mfma_shrink"): 73.22e6}
+MEASURED_TRAFFIC = {("decode", "gemv_fused"): 24.74e6, ("decode_qkv", "gemv_fused"): 71.81e6, ("prefill", "mfma_shrink"): 66.64e6,
+                    ("prefill", "mfma_expand"): 121.58e6, ("mixed", "mfma_expand"): 558.77e6, ("mixed", "mfma_shrink"): 404.12e6,
+                    ("mixed", "gemv_fused"): 177.94e6, ("stress", "gemv_fused"): 356.77e6, ("stress", "mfma_expand"): 103.75e6,
+                    ("stress", "mfma_shrink"): 73.25e6}
 DEFAULT_LAYERS = {"decode": 32, "prefill": 8, "mixed": 2, "stress": 4, "decode_heavy": 8, "decode_paper": 32, "decode_qkv": 16}
 DEFAULT_STEPS = {"decode": 100, "prefill": 60, "mixed": 20, "stress": 20, "decode_heavy": 40, "decode_paper": 100, "decode_qkv": 100}
 
