@@ -170,7 +170,8 @@ struct ApplyArgs {
     const int32_t *tok_list;  // device
     const void *x;            // device [T][h_in]
     void *y;                  // device [T][h_out], in/out
-    float *v;                 // device [max_tokens][v_stride] shrink result
+    float *v;                 // device, rows of v_stride floats, one per token: the tile path's shrink result, kept as
+                              // bf16 entries s.v[j] (scale and alpha applied) at the front of the token's row
     int32_t h_in, h_out, v_stride;
     float scale;
     // when set, the GEMV expand writes its term s.v.B there as fp32 ([token][h_out]) instead of adding it to y,
@@ -242,8 +243,8 @@ struct ShrinkProjs {
     const ShrinkSum *sums;    // device, n_tiles
     const char *proj_base[MAX_SHRINK_PROJS];
     int64_t row_bytes[MAX_SHRINK_PROJS];
-    float *v[MAX_SHRINK_PROJS];
-    float *part[MAX_SHRINK_PROJS];
+    float *v[MAX_SHRINK_PROJS];     // as ApplyArgs::v
+    float *part[MAX_SHRINK_PROJS];  // fp32 partial sums of the tiles worked on in pieces
 };
 // proj_base, row_bytes and v of `a` are ignored (taken from ps)
 hipError_t launch_mfma_shrink(const ApplyArgs &a, const ShrinkProjs &ps, const DevItem *tiles, int n_tiles, hipStream_t st,
